@@ -1,0 +1,224 @@
+/*
+ * qkvcard.h — C ABI of the CacheCard library for MI355X (gfx950).
+ *
+ * A CacheCard is the artifact one agent hands to the next (paper Sec. 4.2.1):
+ * the sender's K/V cache as quantized groups, the token-level bit-width vector,
+ * sequence length, model / sender identifiers, a position-offset placeholder and
+ * the achieved average bit width.  The receiver rebuilds a dense fp16 K/V cache
+ * from it before its next forward pass (paper Sec. 4.2.2).
+ *
+ * The paper fixes what a card carries, not its bytes; this header fixes the
+ * bytes ("card layout v1").  All multi-byte fields are little-endian.
+ *
+ * Tensors.  K and V are fp16, contiguous [layers][kv_heads][tokens][head_dim]
+ * (paper Sec. 3.1: K^(l,h), V^(l,h) in R^{n x d}).  A "plane" is one (kv, l, h)
+ * matrix; planes are numbered p = kv*L*H + l*H + h with kv = 0 for K, 1 for V,
+ * P = 2*L*H planes in all.  A "row" is the head_dim values of one token in one
+ * plane.
+ *
+ * Bit widths.  Every token t has one width b(t) in {2, 4, 8, 16} shared by all
+ * planes (paper Sec. 3.3); 16 means the fp16 row is carried unchanged.  Classes
+ * are numbered 0..3 for widths 2, 4, 8, 16.
+ *
+ * Quantizer (per row, per group of G consecutive head_dim values, b < 16):
+ *   mn, mx   = min / max of the group under the fp16 total order (-0 < +0)
+ *   scale_h  = fp16_rne( (f32(mx) - f32(mn)) / (2^b - 1) )     fp32, IEEE division
+ *   zero_h   = mn
+ *   inv      = scale_h > 0 ? 1.0f / f32(scale_h) : 0           fp32, IEEE division
+ *   code_i   = min(2^b - 1, rne_int( (f32(x_i) - f32(mn)) * inv ))
+ *              (difference rounded to fp32, product exact, rounded once)
+ *   decode   = fp16_rne( fma(f32(code_i), f32(scale_h), f32(zero_h)) )   fp32 fma
+ * Code i of a row sits in bits [(i*b) mod 8, +b) of row byte floor(i*b/8).
+ *
+ * Card layout v1.  al(x) = x rounded up to a multiple of 256.  Sections, in order,
+ * each starting 256-byte aligned, pad bytes zero:
+ *   header            256 bytes, see qkv_card_header_t
+ *   bits              u8 [T]           al(T)      the token-level bit-width vector
+ *   slot              u32[T]           al(4T)     rank of t among tokens of its width
+ *   order             u32[T]           al(4T)     tokens sorted by (class, t)
+ *   codes_2, meta_2   [P][n2][D*2/8] bytes, then [P][n2][D/G]{fp16 scale, fp16 zero}
+ *   codes_4, meta_4   likewise for the 4-bit tokens
+ *   codes_8, meta_8   likewise for the 8-bit tokens
+ *   fp16              [P][n16][D] raw fp16
+ * Row j of a segment belongs to token order[base_c + j], base_c = number of tokens
+ * in lower classes.  The card holds byte offsets only, so it can be copied, saved
+ * and reloaded freely.
+ *
+ * Conventions for every entry point.
+ *   - Return value: QKV_OK (0) or a negative QKV_ERR_* code.  Nothing is thrown or
+ *     aborted across this boundary.  When an error is returned no output buffer has
+ *     been written and no GPU work has been enqueued.
+ *   - "device" pointers are HIP device memory of the current device; "host"
+ *     pointers are ordinary process memory.  The caller owns every buffer; the
+ *     library keeps no pointer after a call returns and no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  GPU
+ *     work is enqueued there and the call returns without waiting, except where
+ *     a function says it synchronises.
+ *   - Supported shapes: head_dim in {64, 128, 256}; group_size in {32, 64, 128},
+ *     group_size <= head_dim; layers, kv_heads, tokens >= 1; P * tokens < 2^32.
+ */
+#ifndef QKVCARD_H
+#define QKVCARD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QKV_OK             0
+#define QKV_ERR_NULL      -1  /* a required pointer is NULL                                  */
+#define QKV_ERR_SHAPE     -2  /* layers / kv_heads / tokens / head_dim outside the supported set */
+#define QKV_ERR_GROUP     -3  /* group_size unsupported or not dividing head_dim              */
+#define QKV_ERR_BUDGET    -4  /* average-bit budget outside [2, 16] or not finite             */
+#define QKV_ERR_CAPACITY  -5  /* card buffer smaller than the card                            */
+#define QKV_ERR_ALIGN     -6  /* a device pointer is not aligned as required                  */
+#define QKV_ERR_COUNTS    -7  /* class counts negative or not summing to tokens               */
+#define QKV_ERR_HIP       -8  /* a HIP runtime call failed                                    */
+#define QKV_ERR_FORMAT    -9  /* card header is not a valid layout-v1 header (peek only)      */
+
+#define QKV_CARD_VERSION        1u
+#define QKV_CARD_HEADER_BYTES   256u
+#define QKV_CARD_ALIGN          256u
+
+/* bits in the status words written by the kernels */
+#define QKV_STATUS_BAD_BITS     0x1u  /* a bits[] value was not 2, 4, 8 or 16 (treated as 2)   */
+#define QKV_STATUS_BAD_COUNTS   0x2u  /* counts[] passed by the host differ from the histogram */
+#define QKV_STATUS_BAD_HEADER   0x4u  /* unpack: magic / version / shape / sizes do not match  */
+#define QKV_STATUS_BAD_ORDER    0x8u  /* unpack: an order[] entry was >= tokens (row skipped)  */
+
+/* Problem description, host memory, caller-owned (paper Sec. 3.1 shape, Sec. 4.2.1 metadata). */
+typedef struct qkv_desc {
+  int32_t  layers;          /* L                                                   */
+  int32_t  kv_heads;        /* H: heads the cache stores (8 for Llama-3.1-8B)      */
+  int32_t  head_dim;        /* D                                                   */
+  int32_t  group_size;      /* G: consecutive head_dim values sharing scale / zero */
+  int64_t  tokens;          /* T: sequence length                                  */
+  uint64_t model_id;        /* opaque, copied into the header                      */
+  uint64_t sender_id;       /* opaque, copied into the header                      */
+  int64_t  position_offset; /* placeholder, stored, not interpreted                */
+} qkv_desc_t;
+
+/* The first 256 bytes of a card (paper Sec. 4.2.1: metadata and average-bit statistics). */
+typedef struct qkv_card_header {
+  uint8_t  magic[8];        /*   0  "QKVCARD\0"                                 */
+  uint32_t version;         /*   8  QKV_CARD_VERSION                            */
+  uint32_t header_bytes;    /*  12  256                                         */
+  uint32_t layers;          /*  16                                              */
+  uint32_t kv_heads;        /*  20                                              */
+  uint32_t head_dim;        /*  24                                              */
+  uint32_t group_size;      /*  28                                              */
+  uint64_t tokens;          /*  32                                              */
+  uint64_t count[4];        /*  40  tokens of width 2, 4, 8, 16                 */
+  uint64_t total_bytes;     /*  72  size of the whole card                      */
+  uint64_t off_bits;        /*  80  byte offsets of the sections from card start */
+  uint64_t off_slot;        /*  88                                              */
+  uint64_t off_order;       /*  96                                              */
+  uint64_t off_codes[3];    /* 104  widths 2, 4, 8                              */
+  uint64_t off_meta[3];     /* 128  widths 2, 4, 8                              */
+  uint64_t off_fp16;        /* 152                                              */
+  uint64_t model_id;        /* 160                                              */
+  uint64_t sender_id;       /* 168                                              */
+  int64_t  position_offset; /* 176                                              */
+  float    avg_bits;        /* 184  (float)((double)sum of b(t) / (double)T)    */
+  uint32_t flags;           /* 188  0 in layout v1                              */
+  uint32_t status;          /* 192  QKV_STATUS_* bits set by the packing kernels */
+  uint8_t  reserved[60];    /* 196  zero                                        */
+} qkv_card_header_t;
+
+/* Library version as major*10000 + minor*100 + patch.  Host only. */
+int qkv_version(void);
+
+/* Static, NUL-terminated text for a return code.  Host only; never NULL. */
+const char* qkv_error_string(int code);
+
+/*
+ * Exact size in bytes of the card for `desc` and class counts {n2, n4, n8, n16}
+ * (closed form of the layout above; the paper's size model, Sec. 3.1, is its
+ * leading term).  Pure host integer arithmetic, no GPU call.
+ *   desc, counts, bytes_out: host.  counts must be >= 0 and sum to desc->tokens.
+ */
+int qkv_card_bytes(const qkv_desc_t* desc, const int64_t counts[4], uint64_t* bytes_out);
+
+/*
+ * Class counts {n2, n4, n8, n16} that an average code-bit budget buys for T tokens
+ * (paper Sec. 3.3: sum of b(t) stays within the budget).  Piecewise-linear between
+ * three anchor mixes: all 2-bit at 2.0; 30 % / 40 % / 25 % / 5 % (2/4/8/16 bit) at
+ * 5.0; all fp16 at 16.0.  Integer arithmetic on round(budget*1000), floors, so
+ * sum b(t) <= budget*T.  Pure host arithmetic, no GPU call.
+ */
+int qkv_budget_counts(int64_t tokens, double avg_bits_budget, int64_t counts_out[4]);
+
+/*
+ * Bit-width assignment from per-token scores and a budget (paper Sec. 3.3: S(t)
+ * decides b(t) under a memory budget).  Tokens are ranked by (score descending,
+ * index ascending), scores compared in the IEEE total order (-0 < +0; NaN is a
+ * precondition violation); the first n16 get 16, the next n8 get 8, the next n4
+ * get 4, the rest 2, with the counts of qkv_budget_counts.
+ *   scores_dev: device, float[T].   bits_dev: device, uint8_t[T], written.
+ *   counts_out: host, int64_t[4], filled before return without a device sync.
+ * Asynchronous on `stream`.
+ */
+int qkv_assign_bits(const float* scores_dev, int64_t tokens, double avg_bits_budget,
+                    uint8_t* bits_dev, int64_t counts_out[4], void* stream);
+
+/*
+ * Histogram of a caller-made bits vector (uniform cards, explicit mixes).
+ *   bits_dev: device, uint8_t[T].  counts_out: host, int64_t[4] for widths 2,4,8,16.
+ * Values other than 2/4/8/16 are not counted (the sum then falls short of T).
+ * Allocates and frees a small device scratch buffer and SYNCHRONISES `stream`.
+ */
+int qkv_count_bits(const uint8_t* bits_dev, int64_t tokens, int64_t counts_out[4], void* stream);
+
+/*
+ * CacheCard creation (paper Sec. 4.2.1): classify tokens by width and compact them
+ * stably into per-width segments (slot, order), quantize and bit-pack K and V rows
+ * at their token's width, copy 16-bit rows unchanged, write header and metadata.
+ *   desc:     host.
+ *   k_dev, v_dev: device, fp16 [L][H][T][D], 16-byte aligned, read only.  Values of
+ *             tokens with b < 16 must be finite; 16-bit tokens may hold anything.
+ *   bits_dev: device, uint8_t[T], values in {2,4,8,16}.
+ *   counts:   host, {n2,n4,n8,n16}, must equal the histogram of bits_dev (it fixes
+ *             the segment sizes before the device has looked at bits_dev).
+ *   card_dev: device, 256-byte aligned, card_capacity >= qkv_card_bytes(desc, counts).
+ *             Exactly qkv_card_bytes bytes are written, none beyond.
+ * Faults only the device can see set header.status: QKV_STATUS_BAD_BITS,
+ * QKV_STATUS_BAD_COUNTS.  The card is then unusable but every access stayed in bounds.
+ * Asynchronous on `stream`.
+ */
+int qkv_quantize_pack(const qkv_desc_t* desc, const void* k_dev, const void* v_dev,
+                      const uint8_t* bits_dev, const int64_t counts[4],
+                      void* card_dev, uint64_t card_capacity, void* stream);
+
+/*
+ * Receiver-side injection (paper Sec. 4.2.2): unpack and dequantize a card into a
+ * dense fp16 K/V cache.
+ *   card_dev:   device, 256-byte aligned, card_bytes readable bytes.
+ *   expect:     host; layers, kv_heads, head_dim, group_size, tokens the caller's
+ *               output buffers were sized for (ids and position_offset ignored).
+ *   k_out_dev, v_out_dev: device, fp16 [L][H][T][D], 16-byte aligned, written in full
+ *               when the card is valid.
+ *   status_dev: device uint32_t, may be NULL.  Set to 0 when the header matches
+ *               `expect` and fits in card_bytes, else to QKV_STATUS_BAD_HEADER and
+ *               the outputs are left untouched; QKV_STATUS_BAD_ORDER is or-ed in if
+ *               a corrupt order[] entry was skipped.
+ * The kernels read the class counts from the header on the device, so no host copy
+ * of the card is needed.  Asynchronous on `stream`.
+ */
+int qkv_unpack_dequant(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect,
+                       void* k_out_dev, void* v_out_dev, uint32_t* status_dev, void* stream);
+
+/*
+ * Read a card's header back to the host and validate it (magic, version, shape
+ * domain, counts summing to tokens, section offsets equal to the closed form,
+ * total_bytes <= card_bytes).  Any out pointer may be NULL.  SYNCHRONISES `stream`.
+ * Returns QKV_ERR_FORMAT for an invalid header (out values are then not written).
+ */
+int qkv_card_peek(const void* card_dev, uint64_t card_bytes, qkv_desc_t* desc_out,
+                  int64_t counts_out[4], float* avg_bits_out, uint32_t* status_out,
+                  void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QKVCARD_H */

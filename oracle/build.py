@@ -1,0 +1,21 @@
+"""Compile the CPU oracle (test infrastructure) into oracle/libqkvref.so with g++."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "qkv_ref.cpp")
+LIB = os.path.join(HERE, "libqkvref.so")
+
+
+def build(force=True):
+    """Build the shared library; returns its path.  With force=False an up-to-date one is kept."""
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+        return LIB
+    cmd = ["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math",
+           "-Wall", "-Wextra", "-o", LIB, SRC]
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())
