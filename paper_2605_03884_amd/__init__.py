@@ -1,0 +1,11 @@
+"""CacheCard creation and receiver-side dequantization on MI355X.
+
+Thin ctypes binding over libqkvcard.so (see include/qkvcard.h): argument marshalling only.
+torch supplies device memory and the current HIP stream; every step runs in the library's
+HIP kernels.  There is no CPU path: a missing library raises at first use.
+"""
+from .binding import (  # noqa: F401
+    QkvError, Desc, lib, lib_path, version, error_string, card_bytes, budget_counts, assign_bits, count_bits,
+    quantize_pack, unpack_dequant, card_peek, STATUS_BAD_BITS, STATUS_BAD_COUNTS, STATUS_BAD_HEADER,
+    STATUS_BAD_ORDER,
+)

@@ -1,0 +1,174 @@
+"""ctypes marshalling for the C ABI declared in include/qkvcard.h (same names, same order)."""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libqkvcard.so"
+
+STATUS_BAD_BITS = 0x1
+STATUS_BAD_COUNTS = 0x2
+STATUS_BAD_HEADER = 0x4
+STATUS_BAD_ORDER = 0x8
+
+
+class QkvError(RuntimeError):
+    def __init__(self, code, where):
+        super().__init__("%s: %s (%d)" % (where, error_string(code), code))
+        self.code = code
+
+
+class Desc(ctypes.Structure):
+    """qkv_desc_t."""
+    _fields_ = [
+        ("layers", ctypes.c_int32),
+        ("kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("group_size", ctypes.c_int32),
+        ("tokens", ctypes.c_int64),
+        ("model_id", ctypes.c_uint64),
+        ("sender_id", ctypes.c_uint64),
+        ("position_offset", ctypes.c_int64),
+    ]
+
+    @classmethod
+    def make(cls, layers, kv_heads, tokens, head_dim, group_size, model_id=0, sender_id=0, position_offset=0):
+        return cls(layers, kv_heads, head_dim, group_size, tokens, model_id, sender_id, position_offset)
+
+
+_lib = None
+
+
+def lib_path():
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def lib():
+    """The loaded library.  Built once by paper_2605_03884_amd.build if it is not there; never replaced by a fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        from . import build as _build
+        _build.build()
+    L = ctypes.CDLL(path)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    vp = ctypes.c_void_p
+    L.qkv_version.restype = ctypes.c_int
+    L.qkv_version.argtypes = []
+    L.qkv_error_string.restype = ctypes.c_char_p
+    L.qkv_error_string.argtypes = [ctypes.c_int]
+    L.qkv_card_bytes.restype = ctypes.c_int
+    L.qkv_card_bytes.argtypes = [ctypes.POINTER(Desc), i64p, ctypes.POINTER(ctypes.c_uint64)]
+    L.qkv_budget_counts.restype = ctypes.c_int
+    L.qkv_budget_counts.argtypes = [ctypes.c_int64, ctypes.c_double, i64p]
+    L.qkv_assign_bits.restype = ctypes.c_int
+    L.qkv_assign_bits.argtypes = [vp, ctypes.c_int64, ctypes.c_double, vp, i64p, vp]
+    L.qkv_count_bits.restype = ctypes.c_int
+    L.qkv_count_bits.argtypes = [vp, ctypes.c_int64, i64p, vp]
+    L.qkv_quantize_pack.restype = ctypes.c_int
+    L.qkv_quantize_pack.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, i64p, vp, ctypes.c_uint64, vp]
+    L.qkv_unpack_dequant.restype = ctypes.c_int
+    L.qkv_unpack_dequant.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, vp, vp, vp]
+    L.qkv_card_peek.restype = ctypes.c_int
+    L.qkv_card_peek.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), i64p, ctypes.POINTER(ctypes.c_float),
+                                ctypes.POINTER(ctypes.c_uint32), vp]
+    _lib = L
+    return L
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise QkvError(rc, where)
+
+
+def _counts(counts):
+    arr = (ctypes.c_int64 * 4)(*[int(c) for c in counts])
+    return arr
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev_ptr(t, dtype=None, name="tensor"):
+    if not t.is_cuda:
+        raise ValueError("%s must live in device memory" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("%s must be %s" % (name, dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def version():
+    return lib().qkv_version()
+
+
+def error_string(code):
+    return lib().qkv_error_string(int(code)).decode()
+
+
+def card_bytes(desc, counts):
+    out = ctypes.c_uint64(0)
+    _check(lib().qkv_card_bytes(ctypes.byref(desc), _counts(counts), ctypes.byref(out)), "qkv_card_bytes")
+    return out.value
+
+
+def budget_counts(tokens, avg_bits_budget):
+    out = (ctypes.c_int64 * 4)()
+    _check(lib().qkv_budget_counts(int(tokens), float(avg_bits_budget), out), "qkv_budget_counts")
+    return list(out)
+
+
+def assign_bits(scores, avg_bits_budget, bits=None, stream=None):
+    """scores: device float32[T].  Returns (bits device uint8[T], counts list)."""
+    T = scores.numel()
+    if bits is None:
+        bits = torch.empty(T, dtype=torch.uint8, device=scores.device)
+    out = (ctypes.c_int64 * 4)()
+    _check(lib().qkv_assign_bits(_dev_ptr(scores, torch.float32, "scores"), T, float(avg_bits_budget),
+                                 _dev_ptr(bits, torch.uint8, "bits"), out, _stream(stream)), "qkv_assign_bits")
+    return bits, list(out)
+
+
+def count_bits(bits, stream=None):
+    out = (ctypes.c_int64 * 4)()
+    _check(lib().qkv_count_bits(_dev_ptr(bits, torch.uint8, "bits"), bits.numel(), out, _stream(stream)),
+           "qkv_count_bits")
+    return list(out)
+
+
+def quantize_pack(desc, k, v, bits, counts, card, stream=None):
+    """k, v: device float16 [L, H, T, D]; bits: device uint8[T]; card: device uint8 buffer, written in place."""
+    _check(lib().qkv_quantize_pack(ctypes.byref(desc), _dev_ptr(k, torch.float16, "k"), _dev_ptr(v, torch.float16, "v"),
+                                   _dev_ptr(bits, torch.uint8, "bits"), _counts(counts),
+                                   _dev_ptr(card, torch.uint8, "card"), card.numel(), _stream(stream)),
+           "qkv_quantize_pack")
+    return card
+
+
+def unpack_dequant(card, expect, k_out, v_out, status=None, card_nbytes=None, stream=None):
+    """card: device uint8; k_out, v_out: device float16 [L, H, T, D]; status: device int32[1] or None."""
+    n = card.numel() if card_nbytes is None else int(card_nbytes)
+    sp = ctypes.c_void_p(0) if status is None else _dev_ptr(status, None, "status")
+    _check(lib().qkv_unpack_dequant(_dev_ptr(card, torch.uint8, "card"), n, ctypes.byref(expect),
+                                    _dev_ptr(k_out, torch.float16, "k_out"), _dev_ptr(v_out, torch.float16, "v_out"),
+                                    sp, _stream(stream)), "qkv_unpack_dequant")
+    return k_out, v_out
+
+
+def card_peek(card, card_nbytes=None, stream=None):
+    """Returns (Desc, counts, avg_bits, status).  Synchronises the stream."""
+    n = card.numel() if card_nbytes is None else int(card_nbytes)
+    d = Desc()
+    counts = (ctypes.c_int64 * 4)()
+    avg = ctypes.c_float(0)
+    st = ctypes.c_uint32(0)
+    _check(lib().qkv_card_peek(_dev_ptr(card, torch.uint8, "card"), n, ctypes.byref(d), counts, ctypes.byref(avg),
+                               ctypes.byref(st), _stream(stream)), "qkv_card_peek")
+    return d, list(counts), avg.value, st.value

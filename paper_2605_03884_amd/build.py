@@ -1,0 +1,28 @@
+"""Compile the HIP kernels and the C ABI into paper_2605_03884_amd/libqkvcard.so for gfx950."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libqkvcard.so")
+SOURCES = ["api.hip", "classify.hip", "pack.hip", "unpack.hip", "assign.hip"]
+
+# -ffp-contract=off: every fused multiply-add in the kernels is written out, none is invented;
+# packed fp32 instructions are switched off on this target.
+FLAGS = ["-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950", "-ffp-contract=off", "-fno-fast-math",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
+
+
+def build(verbose=False):
+    """Always recompiles; returns the library path."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + FLAGS + ["-I", os.path.join(HERE, "..", "include"), "-o", LIB] + \
+          [os.path.join(CSRC, s) for s in SOURCES]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,279 @@
+// api.hip — the C ABI of the CacheCard library: argument checks, card geometry, launch
+// planning.  Every operation's arithmetic runs in the HIP kernels of this directory; there
+// is no host fallback.
+#include <atomic>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+
+#include "qkv_common.h"
+
+namespace qkv {
+
+namespace {
+std::atomic<int> g_cu_count[64];   // compute units per device ordinal, 0 = not asked yet
+
+int compute_units() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  int n = g_cu_count[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    g_cu_count[dev].store(n, std::memory_order_relaxed);
+  }
+  return n;
+}
+}  // namespace
+
+// Grid size for the streaming kernels: one wave per tile while that stays within the
+// resident set, else a persistent grid of QKV_BLOCKS_PER_CU (default 8) workgroups per
+// compute unit whose waves stride over the tiles.
+int persistent_blocks(uint64_t tiles) {
+  static const int per_cu = [] {
+    const char* e = std::getenv("QKV_BLOCKS_PER_CU");
+    const int v = e ? std::atoi(e) : 0;
+    return (v >= 1 && v <= 4096) ? v : 8;
+  }();
+  const uint64_t want = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+  const uint64_t cap = (uint64_t)compute_units() * (uint64_t)per_cu;
+  const uint64_t n = want < cap ? want : cap;
+  return n < 1 ? 1 : (int)n;
+}
+
+namespace {
+
+int check_desc(const qkv_desc_t* d) {
+  if (!d) return QKV_ERR_NULL;
+  return check_shape(d->layers, d->kv_heads, d->head_dim, d->group_size, d->tokens);
+}
+
+// Class counts bought by a budget: linear blend between the all-2-bit mix at 2.0, the
+// 30/40/25/5 % mix at 5.0 and the all-fp16 mix at 16.0, in thousandths of a bit, with floors
+// so that the code bits never exceed budget * T.
+int counts_for_budget(int64_t T, double budget, int64_t out[4]) {
+  if (T < 1) return QKV_ERR_SHAPE;
+  if (!std::isfinite(budget) || budget < 2.0 || budget > 16.0) return QKV_ERR_BUDGET;
+  const long long milli = std::llrint(budget * 1000.0);
+  if (milli < 2000 || milli > 16000) return QKV_ERR_BUDGET;
+  // shares of the 16-, 8- and 4-bit classes as numerator / denominator of T
+  unsigned __int128 num16, num8, num4, den;
+  if (milli <= 5000) {
+    const unsigned long long up = (unsigned long long)(milli - 2000);   // 0 .. 3000
+    num16 = 5ull * up; num8 = 25ull * up; num4 = 40ull * up;
+    den = 100ull * 3000ull;
+  } else {
+    const unsigned long long up = (unsigned long long)(milli - 5000);   // 0 .. 11000
+    const unsigned long long down = 11000ull - up;
+    num16 = 5ull * down + 100ull * up; num8 = 25ull * down; num4 = 40ull * down;
+    den = 100ull * 11000ull;
+  }
+  const unsigned __int128 t = (unsigned __int128)(uint64_t)T;
+  out[3] = (int64_t)(uint64_t)(num16 * t / den);
+  out[2] = (int64_t)(uint64_t)(num8 * t / den);
+  out[1] = (int64_t)(uint64_t)(num4 * t / den);
+  out[0] = T - out[3] - out[2] - out[1];
+  return QKV_OK;
+}
+
+void to_u64(const int64_t in[4], uint64_t out[4]) {
+  for (int c = 0; c < 4; ++c) out[c] = (uint64_t)in[c];
+}
+
+// Host-side validation of a header read back from a card.
+bool header_valid(const qkv_card_header_t& h, uint64_t card_bytes, CardGeom& g) {
+  static const uint8_t magic[8] = {'Q', 'K', 'V', 'C', 'A', 'R', 'D', 0};
+  if (std::memcmp(h.magic, magic, 8) != 0) return false;
+  if (h.version != QKV_CARD_VERSION || h.header_bytes != QKV_CARD_HEADER_BYTES) return false;
+  if (h.layers > 0x7FFFFFFFu || h.kv_heads > 0x7FFFFFFFu || h.head_dim > 0x7FFFFFFFu || h.group_size > 0x7FFFFFFFu ||
+      h.tokens > 0x7FFFFFFFFFFFFFFFull)
+    return false;
+  if (check_shape((int32_t)h.layers, (int32_t)h.kv_heads, (int32_t)h.head_dim, (int32_t)h.group_size,
+                  (int64_t)h.tokens) != QKV_OK)
+    return false;
+  uint64_t sum = 0;
+  for (int c = 0; c < 4; ++c) {
+    if (h.count[c] > h.tokens) return false;
+    sum += h.count[c];
+  }
+  if (sum != h.tokens) return false;
+  build_geom(g, h.layers, h.kv_heads, h.head_dim, h.group_size, h.tokens, h.count);
+  if (h.total_bytes != g.total || g.total > card_bytes) return false;
+  if (h.off_bits != g.off_bits || h.off_slot != g.off_slot || h.off_order != g.off_order || h.off_fp16 != g.off_fp16)
+    return false;
+  for (int c = 0; c < 3; ++c)
+    if (h.off_codes[c] != g.off_codes[c] || h.off_meta[c] != g.off_meta[c]) return false;
+  return true;
+}
+
+}  // namespace
+}  // namespace qkv
+
+using namespace qkv;
+
+extern "C" {
+
+int qkv_version(void) { return 100; }   // 0.1.0
+
+const char* qkv_error_string(int code) {
+  switch (code) {
+    case QKV_OK: return "ok";
+    case QKV_ERR_NULL: return "a required pointer is null";
+    case QKV_ERR_SHAPE: return "unsupported layers / kv_heads / tokens / head_dim";
+    case QKV_ERR_GROUP: return "unsupported group_size";
+    case QKV_ERR_BUDGET: return "average-bit budget outside [2, 16]";
+    case QKV_ERR_CAPACITY: return "card buffer too small";
+    case QKV_ERR_ALIGN: return "device pointer not aligned as required";
+    case QKV_ERR_COUNTS: return "class counts negative or not summing to tokens";
+    case QKV_ERR_HIP: return "a HIP runtime call failed";
+    case QKV_ERR_FORMAT: return "not a valid layout-v1 card header";
+    default: return "unknown error code";
+  }
+}
+
+int qkv_card_bytes(const qkv_desc_t* desc, const int64_t counts[4], uint64_t* bytes_out) {
+  if (!desc || !counts || !bytes_out) return QKV_ERR_NULL;
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  rc = check_counts(desc->tokens, counts);
+  if (rc) return rc;
+  uint64_t n[4];
+  to_u64(counts, n);
+  CardGeom g;
+  build_geom(g, desc->layers, desc->kv_heads, desc->head_dim, desc->group_size, desc->tokens, n);
+  *bytes_out = g.total;
+  return QKV_OK;
+}
+
+int qkv_budget_counts(int64_t tokens, double avg_bits_budget, int64_t counts_out[4]) {
+  if (!counts_out) return QKV_ERR_NULL;
+  int64_t tmp[4];
+  const int rc = counts_for_budget(tokens, avg_bits_budget, tmp);
+  if (rc) return rc;
+  std::memcpy(counts_out, tmp, sizeof(tmp));
+  return QKV_OK;
+}
+
+int qkv_assign_bits(const float* scores_dev, int64_t tokens, double avg_bits_budget, uint8_t* bits_dev,
+                    int64_t counts_out[4], void* stream) {
+  if (!scores_dev || !bits_dev || !counts_out) return QKV_ERR_NULL;
+  if (tokens < 1 || tokens >= (1ll << 31)) return QKV_ERR_SHAPE;
+  if (reinterpret_cast<uintptr_t>(scores_dev) % 4 != 0) return QKV_ERR_ALIGN;
+  int64_t counts[4];
+  const int rc = counts_for_budget(tokens, avg_bits_budget, counts);
+  if (rc) return rc;
+  const uint32_t cuts[3] = {(uint32_t)counts[3], (uint32_t)(counts[3] + counts[2]),
+                            (uint32_t)(counts[3] + counts[2] + counts[1])};
+  if (launch_assign(scores_dev, (uint32_t)tokens, cuts, bits_dev, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return QKV_ERR_HIP;
+  std::memcpy(counts_out, counts, sizeof(counts));
+  return QKV_OK;
+}
+
+int qkv_count_bits(const uint8_t* bits_dev, int64_t tokens, int64_t counts_out[4], void* stream) {
+  if (!bits_dev || !counts_out) return QKV_ERR_NULL;
+  if (tokens < 1) return QKV_ERR_SHAPE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned long long* dev = nullptr;
+  if (hipMalloc(reinterpret_cast<void**>(&dev), 4 * sizeof(unsigned long long)) != hipSuccess) return QKV_ERR_HIP;
+  unsigned long long host[4] = {0, 0, 0, 0};
+  bool ok = launch_count(bits_dev, (uint64_t)tokens, dev, s) == hipSuccess;
+  ok = ok && hipMemcpyAsync(host, dev, sizeof(host), hipMemcpyDeviceToHost, s) == hipSuccess;
+  ok = (hipStreamSynchronize(s) == hipSuccess) && ok;
+  ok = (hipFree(dev) == hipSuccess) && ok;
+  if (!ok) return QKV_ERR_HIP;
+  for (int c = 0; c < 4; ++c) counts_out[c] = (int64_t)host[c];
+  return QKV_OK;
+}
+
+int qkv_quantize_pack(const qkv_desc_t* desc, const void* k_dev, const void* v_dev, const uint8_t* bits_dev,
+                      const int64_t counts[4], void* card_dev, uint64_t card_capacity, void* stream) {
+  if (!desc || !k_dev || !v_dev || !bits_dev || !counts || !card_dev) return QKV_ERR_NULL;
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  rc = check_counts(desc->tokens, counts);
+  if (rc) return rc;
+  if (reinterpret_cast<uintptr_t>(k_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(v_dev) % 16 != 0 ||
+      reinterpret_cast<uintptr_t>(card_dev) % QKV_CARD_ALIGN != 0)
+    return QKV_ERR_ALIGN;
+  uint64_t n[4];
+  to_u64(counts, n);
+  CardGeom g;
+  build_geom(g, desc->layers, desc->kv_heads, desc->head_dim, desc->group_size, desc->tokens, n);
+  if (card_capacity < g.total) return QKV_ERR_CAPACITY;
+
+  qkv_card_header_t h;
+  std::memset(&h, 0, sizeof(h));
+  static const uint8_t magic[8] = {'Q', 'K', 'V', 'C', 'A', 'R', 'D', 0};
+  std::memcpy(h.magic, magic, 8);
+  h.version = QKV_CARD_VERSION;
+  h.header_bytes = QKV_CARD_HEADER_BYTES;
+  h.layers = (uint32_t)desc->layers;
+  h.kv_heads = (uint32_t)desc->kv_heads;
+  h.head_dim = (uint32_t)desc->head_dim;
+  h.group_size = (uint32_t)desc->group_size;
+  h.tokens = (uint64_t)desc->tokens;
+  uint64_t code_bits = 0;
+  for (int c = 0; c < 4; ++c) { h.count[c] = n[c]; code_bits += n[c] * width_of_class(c); }
+  h.total_bytes = g.total;
+  h.off_bits = g.off_bits; h.off_slot = g.off_slot; h.off_order = g.off_order;
+  for (int c = 0; c < 3; ++c) { h.off_codes[c] = g.off_codes[c]; h.off_meta[c] = g.off_meta[c]; }
+  h.off_fp16 = g.off_fp16;
+  h.model_id = desc->model_id;
+  h.sender_id = desc->sender_id;
+  h.position_offset = desc->position_offset;
+  h.avg_bits = (float)((double)code_bits / (double)h.tokens);   // achieved average bit width (Sec. 4.2.1)
+  h.flags = 0;
+  h.status = 0;
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint8_t* card = static_cast<uint8_t*>(card_dev);
+  if (launch_classify(bits_dev, g, h, card, s) != hipSuccess) return QKV_ERR_HIP;
+  if (launch_pack(g, k_dev, v_dev, card, s) != hipSuccess) return QKV_ERR_HIP;
+  return QKV_OK;
+}
+
+int qkv_unpack_dequant(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, void* k_out_dev,
+                       void* v_out_dev, uint32_t* status_dev, void* stream) {
+  if (!card_dev || !expect || !k_out_dev || !v_out_dev) return QKV_ERR_NULL;
+  const int rc = check_desc(expect);
+  if (rc) return rc;
+  if (card_bytes < QKV_CARD_HEADER_BYTES) return QKV_ERR_CAPACITY;
+  if (reinterpret_cast<uintptr_t>(k_out_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(v_out_dev) % 16 != 0 ||
+      reinterpret_cast<uintptr_t>(card_dev) % QKV_CARD_ALIGN != 0 || reinterpret_cast<uintptr_t>(status_dev) % 4 != 0)
+    return QKV_ERR_ALIGN;
+  const uint64_t zero[4] = {0, 0, 0, (uint64_t)expect->tokens};
+  CardGeom g;
+  build_geom(g, expect->layers, expect->kv_heads, expect->head_dim, expect->group_size, expect->tokens, zero);
+  if (launch_unpack(static_cast<const uint8_t*>(card_dev), card_bytes, g, k_out_dev, v_out_dev, status_dev,
+                    static_cast<hipStream_t>(stream)) != hipSuccess)
+    return QKV_ERR_HIP;
+  return QKV_OK;
+}
+
+int qkv_card_peek(const void* card_dev, uint64_t card_bytes, qkv_desc_t* desc_out, int64_t counts_out[4],
+                  float* avg_bits_out, uint32_t* status_out, void* stream) {
+  if (!card_dev) return QKV_ERR_NULL;
+  if (card_bytes < QKV_CARD_HEADER_BYTES) return QKV_ERR_FORMAT;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  qkv_card_header_t h;
+  if (hipMemcpyAsync(&h, card_dev, sizeof(h), hipMemcpyDeviceToHost, s) != hipSuccess) return QKV_ERR_HIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return QKV_ERR_HIP;
+  CardGeom g;
+  if (!header_valid(h, card_bytes, g)) return QKV_ERR_FORMAT;
+  if (desc_out) {
+    desc_out->layers = (int32_t)h.layers;
+    desc_out->kv_heads = (int32_t)h.kv_heads;
+    desc_out->head_dim = (int32_t)h.head_dim;
+    desc_out->group_size = (int32_t)h.group_size;
+    desc_out->tokens = (int64_t)h.tokens;
+    desc_out->model_id = h.model_id;
+    desc_out->sender_id = h.sender_id;
+    desc_out->position_offset = h.position_offset;
+  }
+  if (counts_out) for (int c = 0; c < 4; ++c) counts_out[c] = (int64_t)h.count[c];
+  if (avg_bits_out) *avg_bits_out = h.avg_bits;
+  if (status_out) *status_out = h.status;
+  return QKV_OK;
+}
+
+}  // extern "C"

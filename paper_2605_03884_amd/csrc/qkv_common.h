@@ -1,0 +1,98 @@
+// qkv_common.h — geometry of a card and small device helpers shared by the HIP kernels.
+// Internal to the GPU library (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/qkvcard.h"
+
+namespace qkv {
+
+constexpr int kWaveSize = 64;
+constexpr int kTileChunks = 512;        // 16-byte fp16 chunks one wave handles per tile (8 per lane)
+constexpr int kTileIters = kTileChunks / kWaveSize;
+constexpr int kBlockThreads = 256;      // 4 independent waves per workgroup
+constexpr int kWavesPerBlock = kBlockThreads / kWaveSize;
+
+// Everything a kernel needs to find its way around a card.  Built on the host for the
+// packing kernels (counts are an argument there) and rebuilt on the device from the header
+// for unpacking.
+struct CardGeom {
+  uint32_t layers, kv_heads, head_dim, group_size;
+  uint32_t tokens;          // T
+  uint32_t planes;          // P = 2 * L * H
+  uint32_t k_rows;          // L * H * T: rows (plane, token) below this belong to K
+  uint32_t lpr_shift;       // log2(lanes per row) = log2(head_dim / 8)
+  uint32_t n[4];            // tokens per class (widths 2, 4, 8, 16)
+  uint32_t base[4];         // first index of each class inside order[]
+  uint64_t off_bits, off_slot, off_order;
+  uint64_t off_codes[3], off_meta[3];
+  uint64_t off_fp16;
+  uint64_t total;
+};
+
+__host__ __device__ inline uint64_t align256(uint64_t x) { return (x + 255u) & ~(uint64_t)255u; }
+
+__host__ __device__ inline uint32_t width_of_class(int c) { return 2u << c; }   // 2, 4, 8, 16
+
+// Fills every field from (L, H, D, G, T) and the four class counts.  Shape must have been
+// validated by the caller.
+__host__ __device__ inline void build_geom(CardGeom& g, uint32_t L, uint32_t H, uint32_t D, uint32_t G,
+                                           uint64_t T, const uint64_t counts[4]) {
+  g.layers = L; g.kv_heads = H; g.head_dim = D; g.group_size = G;
+  g.tokens = (uint32_t)T;
+  g.planes = 2u * L * H;
+  g.k_rows = L * H * (uint32_t)T;
+  g.lpr_shift = (D == 64) ? 3u : (D == 128) ? 4u : 5u;
+  uint32_t b = 0;
+  for (int c = 0; c < 4; ++c) { g.n[c] = (uint32_t)counts[c]; g.base[c] = b; b += g.n[c]; }
+  const uint64_t P = g.planes;
+  uint64_t off = QKV_CARD_HEADER_BYTES;
+  g.off_bits = off;  off += align256(T);
+  g.off_slot = off;  off += align256(4 * T);
+  g.off_order = off; off += align256(4 * T);
+  for (int c = 0; c < 3; ++c) {
+    const uint64_t row_bytes = (uint64_t)D * width_of_class(c) / 8;
+    g.off_codes[c] = off; off += align256(P * counts[c] * row_bytes);
+    g.off_meta[c] = off;  off += align256(P * counts[c] * (uint64_t)(D / G) * 4);
+  }
+  g.off_fp16 = off; off += align256(P * counts[3] * (uint64_t)D * 2);
+  g.total = off;
+}
+
+// Host-side checks of the supported shape domain; returns QKV_OK or an error code.
+inline int check_shape(int32_t L, int32_t H, int32_t D, int32_t G, int64_t T) {
+  if (L < 1 || H < 1 || T < 1) return QKV_ERR_SHAPE;
+  if (D != 64 && D != 128 && D != 256) return QKV_ERR_SHAPE;
+  if (G != 32 && G != 64 && G != 128) return QKV_ERR_GROUP;
+  if (G > D || D % G != 0) return QKV_ERR_GROUP;
+  if ((int64_t)L * H > (1 << 24)) return QKV_ERR_SHAPE;
+  const uint64_t rows = 2ull * (uint64_t)L * (uint64_t)H * (uint64_t)T;
+  if (rows >= (1ull << 32)) return QKV_ERR_SHAPE;
+  return QKV_OK;
+}
+
+inline int check_counts(int64_t T, const int64_t counts[4]) {
+  int64_t sum = 0;
+  for (int c = 0; c < 4; ++c) {
+    if (counts[c] < 0 || counts[c] > T) return QKV_ERR_COUNTS;
+    sum += counts[c];
+  }
+  return sum == T ? QKV_OK : QKV_ERR_COUNTS;
+}
+
+// Number of persistent workgroups for a streaming kernel with `tiles` wave-tiles of work.
+int persistent_blocks(uint64_t tiles);
+
+// Kernel launchers (one per source file).  All enqueue on `stream` and return a hipError_t.
+hipError_t launch_classify(const uint8_t* bits, const CardGeom& geom, const qkv_card_header_t& header,
+                           uint8_t* card, hipStream_t stream);
+hipError_t launch_pack(const CardGeom& geom, const void* k, const void* v, uint8_t* card, hipStream_t stream);
+hipError_t launch_unpack(const uint8_t* card, uint64_t card_bytes, const CardGeom& expect, void* k_out, void* v_out,
+                         uint32_t* status, hipStream_t stream);
+hipError_t launch_assign(const float* scores, uint32_t tokens, const uint32_t cuts[3], uint8_t* bits,
+                         hipStream_t stream);
+hipError_t launch_count(const uint8_t* bits, uint64_t tokens, unsigned long long* counts4, hipStream_t stream);
+
+}  // namespace qkv

@@ -1,0 +1,381 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle.
+
+Bar: every card byte (header, bits, slot, order, codes, scale/zero pairs, raw rows, pad) and
+every dequantized fp16 value bit-identical to the oracle's on the same seeded inputs.  (The
+stated floating-point tolerance is 1 fp16 ulp for the dequantized cache; both sides use one
+fp32 fma and one round-to-nearest-even conversion, so 0 ulp is what is asserted.)
+"""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_03884_amd as qkv
+import qkv_synth
+from oracle import ref
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def gpu_card(desc, K, V, bits, counts, extra=0):
+    """Runs qkv_quantize_pack; returns the card bytes (numpy) and the bytes of a canary behind it."""
+    n = qkv.card_bytes(desc, counts)
+    buf = torch.full((n + extra,), 0xA5, dtype=torch.uint8, device=DEV)
+    qkv.quantize_pack(desc, K, V, bits, counts, buf[:n] if extra == 0 else buf)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    return host[:n], host[n:], buf
+
+
+def gpu_unpack(card_dev, desc, nbytes=None):
+    shape = (desc.layers, desc.kv_heads, desc.tokens, desc.head_dim)
+    k = torch.full(shape, float("nan"), dtype=torch.float16, device=DEV)
+    v = torch.full(shape, float("nan"), dtype=torch.float16, device=DEV)
+    status = torch.full((1,), 0x7777, dtype=torch.int32, device=DEV)
+    qkv.unpack_dequant(card_dev, desc, k, v, status=status, card_nbytes=nbytes)
+    torch.cuda.synchronize()
+    return k.cpu().numpy().view(np.uint16), v.cpu().numpy().view(np.uint16), int(status.item())
+
+
+def ref_desc(d):
+    return ref.make_desc(d.layers, d.kv_heads, d.tokens, d.head_dim, d.group_size, d.model_id, d.sender_id,
+                         d.position_offset)
+
+
+def first_diff(a, b):
+    idx = np.flatnonzero(a != b)
+    return None if idx.size == 0 else (int(idx[0]), int(a[idx[0]]), int(b[idx[0]]), int(idx.size))
+
+
+def check_round_trip(desc, K, V, bits_np, label):
+    """K, V: host float16 arrays.  Full byte comparison of card and dequantized cache."""
+    say(label)
+    counts = [int((bits_np == w).sum()) for w in (2, 4, 8, 16)]
+    Kd = torch.from_numpy(K).to(DEV)
+    Vd = torch.from_numpy(V).to(DEV)
+    bd = torch.from_numpy(bits_np).to(DEV)
+    assert qkv.count_bits(bd) == counts
+    card, canary, card_dev = gpu_card(desc, Kd, Vd, bd, counts, extra=512)
+    assert np.all(canary == 0xA5), "bytes behind the card were written"
+    rd = ref_desc(desc)
+    want = ref.quantize_pack(rd, K, V, bits_np, counts)
+    assert card.shape == want.shape
+    assert first_diff(card, want) is None, "card differs (offset, gpu, oracle, n): %r" % (first_diff(card, want),)
+    d2, c2, avg, status = qkv.card_peek(card_dev, card_nbytes=card.size)
+    assert status == 0 and c2 == counts
+    assert (d2.layers, d2.kv_heads, d2.tokens, d2.head_dim, d2.group_size) == (
+        desc.layers, desc.kv_heads, desc.tokens, desc.head_dim, desc.group_size)
+    assert (d2.model_id, d2.sender_id, d2.position_offset) == (desc.model_id, desc.sender_id, desc.position_offset)
+    k, v, st = gpu_unpack(card_dev, desc, nbytes=card.size)
+    assert st == 0
+    wk, wv = ref.unpack_dequant(want, rd)
+    assert first_diff(k.ravel(), wk.ravel()) is None, "K differs: %r" % (first_diff(k.ravel(), wk.ravel()),)
+    assert first_diff(v.ravel(), wv.ravel()) is None, "V differs: %r" % (first_diff(v.ravel(), wv.ravel()),)
+    return card, k, v
+
+
+def make_problem(L, H, T, D, G, seed, kind="llama"):
+    K, V = qkv_synth.make_kv(L, H, T, D, seed, kind)
+    desc = qkv.Desc.make(L, H, T, D, G, model_id=0xC0FFEE1234, sender_id=seed, position_offset=-3)
+    return desc, K.numpy(), V.numpy()
+
+
+# ------------------------------------------------------------------------------ whole cards
+
+
+def test_tiny_config_card_and_cache_bit_exact():
+    cfg = qkv_synth.CONFIGS["tiny"]
+    desc, K, V = make_problem(cfg["layers"], cfg["kv_heads"], cfg["tokens"], cfg["head_dim"], cfg["group_size"],
+                              cfg["data_seed"], cfg["kind"])
+    bits = qkv_synth.make_bits_uniform_choice(cfg["tokens"], cfg["bits"][1]).numpy()
+    check_round_trip(desc, K, V, bits, "tiny config")
+
+
+@pytest.mark.parametrize("L,H,T,D,G", [
+    (1, 1, 1, 128, 32),        # a single token
+    (2, 3, 77, 128, 32),       # ragged: 77 tokens, tiles of 32 rows end mid-plane
+    (1, 2, 1000, 128, 64),
+    (3, 1, 333, 128, 128),
+    (2, 2, 129, 64, 32),       # 64 rows per tile
+    (1, 3, 515, 64, 64),
+    (2, 1, 260, 256, 32),      # 16 rows per tile
+    (1, 2, 97, 256, 64),
+    (1, 1, 181, 256, 128),
+    (4, 4, 2048, 128, 32),
+])
+def test_shapes_mixed_widths(L, H, T, D, G):
+    desc, K, V = make_problem(L, H, T, D, G, seed=100 + T)
+    bits = qkv_synth.make_bits_uniform_choice(T, 200 + T).numpy()
+    check_round_trip(desc, K, V, bits, "mixed L%d H%d T%d D%d G%d" % (L, H, T, D, G))
+
+
+@pytest.mark.parametrize("width", [2, 4, 8, 16])
+@pytest.mark.parametrize("G", [32, 64])
+def test_uniform_cards(width, G):
+    L, H, T, D = 2, 2, 700, 128
+    desc, K, V = make_problem(L, H, T, D, G, seed=300 + width)
+    bits = np.full(T, width, dtype=np.uint8)
+    card, k, v = check_round_trip(desc, K, V, bits, "uniform %d-bit G%d" % (width, G))
+    if width == 16:   # raw rows pass through unchanged
+        assert np.array_equal(k, K.view(np.uint16)) and np.array_equal(v, V.view(np.uint16))
+
+
+def test_skewed_mixes_and_empty_classes():
+    L, H, T, D, G = 2, 2, 600, 128, 32
+    desc, K, V = make_problem(L, H, T, D, G, seed=77)
+    rng = np.random.default_rng(5)
+    for probs in [(0.97, 0.01, 0.01, 0.01), (0.0, 0.5, 0.0, 0.5), (0.5, 0.0, 0.5, 0.0), (0.01, 0.01, 0.01, 0.97),
+                  (0.0, 0.0, 1.0, 0.0)]:
+        bits = rng.choice(np.array([2, 4, 8, 16], dtype=np.uint8), size=T, p=probs)
+        check_round_trip(desc, K, V, bits, "mix %r" % (probs,))
+
+
+def special_values(L, H, T, D):
+    """Rows built to hit the corners of the quantizer: signed zeros, subnormals, constant
+    groups, ranges whose fp16 scale is subnormal (clamp active) or zero, the full fp16 range,
+    exact grids, rounding ties."""
+    rng = np.random.default_rng(11)
+    shape = (L, H, T, D)
+    K = rng.standard_normal(shape).astype(np.float16)
+    V = rng.standard_normal(shape).astype(np.float16)
+    u = K.view(np.uint16)
+    # token 0: all +0 / -0 mixes
+    u[..., 0, :] = rng.choice(np.array([0x0000, 0x8000], dtype=np.uint16), size=(L, H, D))
+    # token 1: subnormals of both signs
+    u[..., 1, :] = rng.integers(0, 0x0400, size=(L, H, D)).astype(np.uint16) | (
+        rng.integers(0, 2, size=(L, H, D)).astype(np.uint16) << 15)
+    # token 2: constant rows
+    K[..., 2, :] = np.float16(3.140625)
+    # token 3: tiny ranges around 1.0 (scale rounds to an fp16 subnormal or to zero)
+    u[..., 3, :] = (0x3C00 + rng.integers(0, 3, size=(L, H, D))).astype(np.uint16)
+    # token 4: tiny ranges near zero: values k * 2^-24, k < 40
+    u[..., 4, :] = rng.integers(0, 40, size=(L, H, D)).astype(np.uint16)
+    # token 5: whole finite range
+    u[..., 5, :] = rng.choice(np.array([0x7BFF, 0xFBFF, 0x0001, 0x8001, 0x3C00], dtype=np.uint16), size=(L, H, D))
+    # token 6: exact grid z + k * 2^-3
+    K[..., 6, :] = (np.float32(-2.0) + rng.integers(0, 4, size=(L, H, D)).astype(np.float32) * 0.125).astype(np.float16)
+    # token 7: values at exact midpoints between grid points (ties)
+    K[..., 7, :] = (rng.integers(0, 31, size=(L, H, D)).astype(np.float32) * 0.5).astype(np.float16)
+    # token 8: only two distinct values
+    K[..., 8, :] = rng.choice(np.array([-1.5, 2.25], dtype=np.float16), size=(L, H, D))
+    # token 9: one element differs by one ulp
+    K[..., 9, :] = np.float16(0.333251953125)
+    u[..., 9, 5] += 1
+    V.view(np.uint16)[..., :10, :] = u[..., :10, ::-1]
+    return K, V
+
+
+@pytest.mark.parametrize("G", [32, 64, 128])
+def test_special_values_every_width(G):
+    L, H, T, D = 1, 2, 64, 128
+    K, V = special_values(L, H, T, D)
+    desc = qkv.Desc.make(L, H, T, D, G)
+    for width in (2, 4, 8):
+        bits = np.full(T, width, dtype=np.uint8)
+        check_round_trip(desc, K, V, bits, "special values %d-bit G%d" % (width, G))
+
+
+def test_raw_rows_carry_nan_and_inf_payloads():
+    L, H, T, D, G = 1, 2, 40, 128, 32
+    desc, K, V = make_problem(L, H, T, D, G, seed=9)
+    bits = np.full(T, 4, dtype=np.uint8)
+    bits[::3] = 16
+    ku = K.view(np.uint16)
+    rng = np.random.default_rng(2)
+    ku[:, :, ::3, :] = rng.integers(0, 65536, size=ku[:, :, ::3, :].shape).astype(np.uint16)   # any pattern at all
+    card, k, v = check_round_trip(desc, K, V, bits, "raw rows with arbitrary bit patterns")
+    assert np.array_equal(k[:, :, ::3, :], ku[:, :, ::3, :])
+
+
+def test_llama_shape_slice_with_budget_bits():
+    # the benchmark's value recipe and allocator at a size the oracle finishes quickly
+    L, H, T, D, G = 4, 8, 1024, 128, 32
+    desc, K, V = make_problem(L, H, T, D, G, seed=2001)
+    scores = qkv_synth.make_scores(T, 2002)
+    for budget in (5.0, 4.0, 3.0):
+        bits_dev, counts = qkv.assign_bits(scores.to(DEV), budget)
+        torch.cuda.synchronize()
+        want_bits, want_counts = ref.assign_bits(scores.numpy(), budget)
+        assert counts == want_counts.tolist()
+        assert np.array_equal(bits_dev.cpu().numpy(), want_bits)
+        check_round_trip(desc, K, V, want_bits, "llama slice budget %.1f" % budget)
+
+
+def test_two_hops_requantize_dequantized_cache():
+    # hop 2 quantizes what hop 1 dequantized: needs 0 ulp, not 1
+    L, H, T, D, G = 2, 4, 512, 128, 32
+    desc, K, V = make_problem(L, H, T, D, G, seed=5001)
+    for hop, budget in enumerate((6.0, 4.0, 3.0, 2.0)):
+        scores = qkv_synth.make_scores(T, 5003 + hop)
+        bits, _ = ref.assign_bits(scores.numpy(), budget)
+        card, k, v = check_round_trip(desc, K, V, bits, "hop %d budget %.0f" % (hop + 1, budget))
+        K, V = k.view(np.float16), v.view(np.float16)
+
+
+def test_card_survives_a_trip_through_host_memory():
+    L, H, T, D, G = 2, 2, 300, 128, 32
+    desc, K, V = make_problem(L, H, T, D, G, seed=31)
+    bits = qkv_synth.make_bits_uniform_choice(T, 32).numpy()
+    card, k, v = check_round_trip(desc, K, V, bits, "serialise")
+    blob = bytes(card.tobytes())
+    again = torch.from_numpy(np.frombuffer(blob, dtype=np.uint8).copy()).to(DEV)
+    k2, v2, st = gpu_unpack(again, desc)
+    assert st == 0 and np.array_equal(k2, k) and np.array_equal(v2, v)
+
+
+def test_pack_is_deterministic():
+    L, H, T, D, G = 2, 2, 900, 128, 32
+    desc, K, V = make_problem(L, H, T, D, G, seed=41)
+    bits = qkv_synth.make_bits_uniform_choice(T, 42).numpy()
+    counts = [int((bits == w).sum()) for w in (2, 4, 8, 16)]
+    Kd, Vd, bd = torch.from_numpy(K).to(DEV), torch.from_numpy(V).to(DEV), torch.from_numpy(bits).to(DEV)
+    a, _, _ = gpu_card(desc, Kd, Vd, bd, counts)
+    b, _, _ = gpu_card(desc, Kd, Vd, bd, counts)
+    assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------------------ allocator
+
+
+@pytest.mark.parametrize("T", [1, 2, 63, 64, 1000, 1024, 4097, 32768, 100003])
+def test_assign_bits_matches_oracle(T):
+    say("assign_bits T=%d" % T)
+    rng = np.random.default_rng(T)
+    variants = {
+        "uniform": rng.random(T).astype(np.float32),
+        "ties": (np.round(rng.random(T) * 7) / 7).astype(np.float32),
+        "all equal": np.full(T, 0.25, dtype=np.float32),
+        "signed": rng.standard_normal(T).astype(np.float32),
+        "zeros": rng.choice(np.array([0.0, -0.0, 1e-40, -1e-40], dtype=np.float32), size=T),
+        "sorted": np.sort(rng.random(T).astype(np.float32)),
+        "infs": rng.choice(np.array([np.inf, -np.inf, 0.0, 1.0], dtype=np.float32), size=T),
+    }
+    for name, scores in variants.items():
+        sd = torch.from_numpy(scores).to(DEV)
+        for budget in (2.0, 2.001, 3.0, 4.0, 5.0, 7.5, 15.999, 16.0):
+            bits, counts = qkv.assign_bits(sd, budget)
+            torch.cuda.synchronize()
+            wb, wc = ref.assign_bits(scores, budget)
+            assert counts == wc.tolist(), (name, budget)
+            got = bits.cpu().numpy()
+            assert np.array_equal(got, wb), (name, budget, int(np.flatnonzero(got != wb)[0]))
+            assert qkv.count_bits(bits) == counts
+
+
+def test_budget_counts_match_oracle_everywhere():
+    rng = np.random.default_rng(1)
+    for _ in range(3000):
+        T = int(rng.integers(1, 1 << 20))
+        bm = int(rng.integers(2000, 16001))
+        assert qkv.budget_counts(T, bm / 1000.0) == ref.budget_counts(T, bm / 1000.0).tolist()
+
+
+# ------------------------------------------------------------------------------ faults seen on the device
+
+
+def test_status_bad_bits_and_bad_counts_stay_in_bounds():
+    L, H, T, D, G = 1, 2, 200, 128, 32
+    desc, K, V = make_problem(L, H, T, D, G, seed=51)
+    bits = qkv_synth.make_bits_uniform_choice(T, 52).numpy()
+    counts = [int((bits == w).sum()) for w in (2, 4, 8, 16)]
+    Kd, Vd = torch.from_numpy(K).to(DEV), torch.from_numpy(V).to(DEV)
+    bad = bits.copy()
+    bad[17] = 3
+    say("bits value 3")
+    card, canary, card_dev = gpu_card(desc, Kd, Vd, torch.from_numpy(bad).to(DEV), counts, extra=512)
+    assert np.all(canary == 0xA5)
+    assert qkv.card_peek(card_dev, card_nbytes=card.size)[3] & qkv.STATUS_BAD_BITS
+    say("counts that are not the histogram")
+    wrong = [counts[0] + 5, counts[1] - 5, counts[2], counts[3]]
+    card, canary, card_dev = gpu_card(desc, Kd, Vd, torch.from_numpy(bits).to(DEV), wrong, extra=512)
+    assert np.all(canary == 0xA5)
+    assert qkv.card_peek(card_dev, card_nbytes=card.size)[3] & qkv.STATUS_BAD_COUNTS
+
+
+def test_unpack_rejects_foreign_headers_and_bounds_order():
+    L, H, T, D, G = 1, 2, 150, 128, 32
+    desc, K, V = make_problem(L, H, T, D, G, seed=61)
+    bits = qkv_synth.make_bits_uniform_choice(T, 62).numpy()
+    counts = [int((bits == w).sum()) for w in (2, 4, 8, 16)]
+    card, _, card_dev = gpu_card(desc, torch.from_numpy(K).to(DEV), torch.from_numpy(V).to(DEV),
+                                 torch.from_numpy(bits).to(DEV), counts)
+    good_k, good_v, st = gpu_unpack(card_dev, desc)
+    assert st == 0
+    nan = 0x7E00
+
+    def corrupted(offset, value_bytes):
+        c = card.copy()
+        c[offset:offset + len(value_bytes)] = np.frombuffer(value_bytes, dtype=np.uint8)
+        return torch.from_numpy(c).to(DEV)
+
+    say("wrong magic")
+    k, v, st = gpu_unpack(corrupted(0, b"X"), desc)
+    assert st == qkv.STATUS_BAD_HEADER and np.all(k == nan) and np.all(v == nan)
+    say("wrong version")
+    k, v, st = gpu_unpack(corrupted(8, (2).to_bytes(4, "little")), desc)
+    assert st == qkv.STATUS_BAD_HEADER and np.all(k == nan)
+    say("counts not summing to T")
+    k, v, st = gpu_unpack(corrupted(40, (counts[0] + 1).to_bytes(8, "little")), desc)
+    assert st == qkv.STATUS_BAD_HEADER and np.all(k == nan)
+    say("counts moved between classes (offsets no longer match)")
+    moved = card.copy()
+    moved[40:48] = np.frombuffer((counts[0] + 1).to_bytes(8, "little"), dtype=np.uint8)
+    moved[48:56] = np.frombuffer((counts[1] - 1).to_bytes(8, "little"), dtype=np.uint8)
+    k, v, st = gpu_unpack(torch.from_numpy(moved).to(DEV), desc)
+    assert st == qkv.STATUS_BAD_HEADER and np.all(k == nan)
+    say("huge count")
+    k, v, st = gpu_unpack(corrupted(40, (1 << 62).to_bytes(8, "little")), desc)
+    assert st == qkv.STATUS_BAD_HEADER and np.all(k == nan)
+    say("truncated card")
+    k, v, st = gpu_unpack(card_dev, desc, nbytes=card.size - 256)
+    assert st == qkv.STATUS_BAD_HEADER and np.all(k == nan)
+    say("shape other than expected")
+    other = qkv.Desc.make(L, H, T, D, 64)
+    k = torch.zeros((L, H, T, D), dtype=torch.float16, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    qkv.unpack_dequant(card_dev, other, k, k.clone(), status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == qkv.STATUS_BAD_HEADER
+    say("order entry out of range")
+    off_order = int.from_bytes(card[96:104].tobytes(), "little")
+    k, v, st = gpu_unpack(corrupted(off_order + 4 * 7, (T + 1000).to_bytes(4, "little")), desc)
+    assert st == qkv.STATUS_BAD_ORDER
+    tok = int.from_bytes(card[off_order + 28:off_order + 32].tobytes(), "little")
+    keep = np.ones(T, dtype=bool)
+    keep[tok] = False
+    assert np.array_equal(k[:, :, keep, :], good_k[:, :, keep, :]) and np.all(k[:, :, tok, :] == nan)
+    say("status pointer omitted")
+    k = torch.zeros((L, H, T, D), dtype=torch.float16, device=DEV)
+    v = torch.zeros_like(k)
+    qkv.unpack_dequant(card_dev, desc, k, v)
+    torch.cuda.synchronize()
+    assert np.array_equal(k.cpu().numpy().view(np.uint16), good_k)
+
+
+def test_host_side_errors_on_device_pointers():
+    L, H, T, D, G = 1, 1, 32, 128, 32
+    desc = qkv.Desc.make(L, H, T, D, G)
+    K = torch.zeros((L, H, T, D), dtype=torch.float16, device=DEV)
+    bits = torch.full((T,), 4, dtype=torch.uint8, device=DEV)
+    counts = [0, T, 0, 0]
+    n = qkv.card_bytes(desc, counts)
+    small = torch.zeros(n - 1, dtype=torch.uint8, device=DEV)
+    with pytest.raises(qkv.QkvError) as e:
+        qkv.quantize_pack(desc, K, K, bits, counts, small)
+    assert e.value.code == -5
+    big = torch.zeros(n + 256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(qkv.QkvError) as e:
+        qkv.quantize_pack(desc, K, K, bits, counts, big[1:])
+    assert e.value.code == -6
+    with pytest.raises(qkv.QkvError) as e:
+        qkv.quantize_pack(desc, K, K, bits, [1, T, 0, 0], big)
+    assert e.value.code == -7
+    with pytest.raises(qkv.QkvError) as e:
+        qkv.assign_bits(torch.zeros(T, device=DEV), 1.5)
+    assert e.value.code == -4
