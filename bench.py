@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the CacheCard hot path on one MI355X.
+
+One step = one handoff over synthetic Llama-3.1-8B-shaped KV already resident in HBM:
+qkv_assign_bits (scores -> widths) -> qkv_quantize_pack (card creation) -> qkv_unpack_dequant
+(receiver injection).  Prints ONE JSON line: whole-job throughput in GB/s of fp16 KV bytes per
+handoff, the HBM roofline of the slowest call, and the CPU oracle timed on a slice of the same
+workload.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import qkv_synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
+
+
+def make_inputs(cfg, dev):
+    K, V = qkv_synth.make_kv(cfg["layers"], cfg["kv_heads"], cfg["tokens"], cfg["head_dim"], cfg["data_seed"],
+                             cfg["kind"], device=dev)
+    kind = cfg["bits"][0]
+    if kind == "budget":
+        scores = qkv_synth.make_scores(cfg["tokens"], cfg["bits"][1], dev)
+        budget = cfg["bits"][2]
+    elif kind == "hops":
+        scores = qkv_synth.make_scores(cfg["tokens"], cfg["bits"][1][0], dev)
+        budget = cfg["bits"][2][0]
+    else:
+        scores, budget = None, None
+    return K, V, scores, budget
+
+
+def cpu_baseline(cfg, K_dev, V_dev, bits_host, budget, layers):
+    """The oracle, unchanged and single-threaded, on the first `layers` layers of the same tensors."""
+    import numpy as np
+    from oracle import ref
+    T, D, H, G = cfg["tokens"], cfg["head_dim"], cfg["kv_heads"], cfg["group_size"]
+    K = K_dev[:layers].cpu().numpy()
+    V = V_dev[:layers].cpu().numpy()
+    d = ref.make_desc(layers, H, T, D, G)
+    t0 = time.perf_counter()
+    if budget is not None:
+        seed = cfg["bits"][1] if cfg["bits"][0] == "budget" else cfg["bits"][1][0]
+        bits, counts = ref.assign_bits(qkv_synth.make_scores(T, seed).numpy(), budget)
+        assert np.array_equal(bits, bits_host)
+    else:
+        bits = bits_host
+        counts = ref.count_bits(bits)
+    card = ref.quantize_pack(d, K, V, bits, counts)
+    ref.unpack_dequant(card, d)
+    dt = time.perf_counter() - t0
+    kv_bytes = 2 * layers * H * T * D * 2
+    return kv_bytes / dt / 1e9, dt
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama8b_8k_b3", choices=sorted(qkv_synth.CONFIGS))
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--cpu-layers", type=int, default=0,
+                    help="layers of the workload the CPU oracle is timed on (0: about 8192*32 token-layers)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the card is built per GPU; see DESIGN.md on sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library has no CPU path", file=sys.stderr)
+        return 3
+
+    import paper_2605_03884_amd as qkv
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = qkv_synth.CONFIGS[args.workload]
+    L, H, T, D, G = cfg["layers"], cfg["kv_heads"], cfg["tokens"], cfg["head_dim"], cfg["group_size"]
+    desc = qkv.Desc.make(L, H, T, D, G, model_id=0x11A3A8B, sender_id=1)
+    K, V, scores, budget = make_inputs(cfg, dev)
+    if scores is not None:
+        bits, counts = qkv.assign_bits(scores, budget)
+    else:
+        bits = qkv_synth.make_bits_constant(T, cfg["bits"][1], dev)
+        counts = qkv.count_bits(bits)
+    card_bytes = qkv.card_bytes(desc, counts)
+    card = torch.empty(card_bytes, dtype=torch.uint8, device=dev)
+    K_out = torch.empty_like(K)
+    V_out = torch.empty_like(V)
+    kv_bytes = K.numel() * 2 + V.numel() * 2
+    moved = kv_bytes + card_bytes          # algorithmic bytes of either direction
+
+    def step(events=None):
+        if events is not None:
+            events[0].record()
+        if scores is not None:
+            qkv.assign_bits(scores, budget, bits=bits)
+        if events is not None:
+            events[1].record()
+        qkv.quantize_pack(desc, K, V, bits, counts, card)
+        if events is not None:
+            events[2].record()
+        qkv.unpack_dequant(card, desc, K_out, V_out)
+        if events is not None:
+            events[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    def avg_ms(a, b):
+        return sum(e[a].elapsed_time(e[b]) for e in evs) / len(evs)
+
+    assign_ms, pack_ms, unpack_ms = avg_ms(0, 1), avg_ms(1, 2), avg_ms(2, 3)
+
+    # the card just built must be readable and clean
+    _, c2, avg_bits, status = qkv.card_peek(card)
+    assert status == 0 and c2 == counts, (status, c2, counts)
+
+    # plain device copy of the same fp16 bytes: what this machine's HBM gives a kernel with no arithmetic
+    for _ in range(3):
+        K_out.copy_(K)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        K_out.copy_(K)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * K.numel() * 2 / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9
+
+    def roof(name, ms):
+        a = moved / (ms * 1e-3) / 1e9
+        return {"kernel": name, "bound": "hbm", "achieved": round(a, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(a / HBM_PEAK_GBS, 4), "traffic": None, "avg_ms": round(ms, 4),
+                "algorithmic_bytes": moved, "kv_gbs": round(kv_bytes / (ms * 1e-3) / 1e9, 1)}
+
+    legs = [roof("qkv_quantize_pack: classify_kernel + pack_kernel<%d>" % G, pack_ms),
+            roof("qkv_unpack_dequant: unpack_kernel<%d>" % G, unpack_ms)]
+    dominant = max(legs, key=lambda r: r["avg_ms"])
+
+    out = {
+        "metric": "quantize+pack & unpack+dequant GB/s (fp16 KV bytes), % HBM peak, Llama8B-8K",
+        "value": round(kv_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "unit": "GB/s of fp16 KV bytes per handoff (assign_bits + quantize_pack + unpack_dequant)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 in, f32 quantizer arithmetic",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "layers": L, "kv_heads": H, "tokens": T, "head_dim": D, "group_size": G,
+                   "counts_2_4_8_16": counts, "avg_code_bits": round(avg_bits, 4), "kv_bytes": kv_bytes,
+                   "card_bytes": card_bytes},
+        "roofline": dominant,
+        "roofline_all": legs,
+        "stages_ms": {"assign_bits": round(assign_ms, 4), "quantize_pack": round(pack_ms, 4),
+                      "unpack_dequant": round(unpack_ms, 4)},
+        "pct_hbm_peak": {"quantize_pack": round(100 * legs[0]["frac"], 2), "unpack_dequant": round(100 * legs[1]["frac"], 2)},
+        "copy_ceiling_gbs": round(copy_gbs, 1),
+    }
+    if not args.no_cpu:
+        layers = args.cpu_layers if args.cpu_layers > 0 else (L * 8192) // max(T, 8192)
+        layers = max(1, min(layers, L))
+        v, secs = cpu_baseline(cfg, K, V, bits.cpu().numpy(), budget, layers)
+        out["cpu_baseline"] = {"value": round(v, 4), "unit": out["unit"], "cores": 1, "kind": "oracle",
+                               "sample": "first %d of %d layers of the same tensors, all tokens, same widths; %.1f s"
+                                         % (layers, L, secs)}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
