@@ -4,18 +4,32 @@
 // Work decomposition.  Inside the card every width owns a segment that is a flat array of
 // N_c = P * n_c rows (plane-major, then slot).  A wave takes "tiles" of 512 sixteen-byte
 // input chunks (4096 fp16 values = 32 rows at head_dim 128); tile i of a segment covers flat
-// rows [i*R, (i+1)*R), so every tile's code bytes and (scale, zero) pairs are one contiguous,
-// 128-byte aligned run of the card.  The grid is persistent: wave w handles the global tiles
+// rows [i*R, (i+1)*R), so the tile's code bytes and its (scale, zero) pairs are each one
+// contiguous, 128-byte aligned run of the card.  Wave w handles the global tiles
 // w, w + W, w + 2W, ... over the four segments in turn.
 //
-// Inside a tile, lane l of iteration k holds chunk q = 64 k + l: 8 consecutive values of row
-// q / (D/8).  A quantization group of G values is G/8 neighbouring lanes, reduced with DPP.
-// Rows are gathered through order[] (256-byte aligned full rows), codes are staged through
-// LDS so the card is written with 128-bit stores.
+// Inside a tile.
+//   1. Rows are gathered through order[]: whole 256-byte rows, 128-bit loads, 1 KiB per
+//      load instruction (lane l of load k holds chunk 64 k + l).
+//   2. The 8 KiB tile is turned through LDS so that each lane then owns one "span" of 32
+//      consecutive values (64 bytes) - a whole quantization group at group size 32.  The
+//      chunk index is XOR-swizzled so that both the row-major writes and the span-major
+//      reads touch every LDS bank once per pass.
+//   3. Per span: min / max with packed 3-input fp16 instructions and no cross-lane traffic
+//      (one or two DPP steps at group size 64 / 128), scale and reciprocal once per span,
+//      three VALU operations per value (subtract, multiply-round, shift-insert).
+//   4. A lane's packed codes (8 / 16 / 32 bytes) and pair (4 bytes) are contiguous with its
+//      neighbours', so they go straight to the card with coalesced stores.
+// The hardware min / max order -0 below +0 and keep subnormals, so the group extrema do not
+// depend on the reduction order.
 #include "qkv_common.h"
 
 namespace qkv {
 namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(1))) const u32x4 global_u32x4;
 
 struct PackArgs {
   CardGeom g;
@@ -24,40 +38,64 @@ struct PackArgs {
   uint8_t* card;
 };
 
-// ---- cross-lane and packed-half helpers -------------------------------------------------
+// ---- small wrappers around instructions the compiler does not pick by itself ---------------
 
 template <int CTRL>
 __device__ inline uint32_t dpp(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
 }
+constexpr int kQuadXor1 = 0xB1;        // quad_perm:[1,0,3,2]
+constexpr int kQuadXor2 = 0x4E;        // quad_perm:[2,3,0,1]
 
-// min of two packed fp16 pairs.  The hardware instruction orders -0 below +0 and keeps
-// subnormals, so the result does not depend on the reduction order.
+__device__ inline uint32_t pk_min3(uint32_t a, uint32_t b, uint32_t c) {
+  uint32_t r;
+  asm("v_pk_minimum3_f16 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+__device__ inline uint32_t pk_max3(uint32_t a, uint32_t b, uint32_t c) {
+  uint32_t r;
+  asm("v_pk_maximum3_f16 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
 __device__ inline uint32_t pk_min(uint32_t a, uint32_t b) {
   uint32_t r;
   asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
   return r;
 }
-// min(-a, -b) on both halves
-__device__ inline uint32_t pk_min_neg(uint32_t a, uint32_t b) {
+__device__ inline uint32_t pk_max(uint32_t a, uint32_t b) {
   uint32_t r;
-  asm("v_pk_min_f16 %0, %1, %2 neg_lo:[1,1] neg_hi:[1,1]" : "=v"(r) : "v"(a), "v"(b));
+  asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+// both halves <- min / max of the two halves
+__device__ inline uint32_t pk_min_halves(uint32_t a) {
+  uint32_t r;
+  asm("v_pk_min_f16 %0, %1, %1 op_sel:[0,1] op_sel_hi:[1,0]" : "=v"(r) : "v"(a));
+  return r;
+}
+__device__ inline uint32_t pk_max_halves(uint32_t a) {
+  uint32_t r;
+  asm("v_pk_max_f16 %0, %1, %1 op_sel:[0,1] op_sel_hi:[1,0]" : "=v"(r) : "v"(a));
+  return r;
+}
+// f32(low half of w) + c and f32(high half of w) + c: conversion and addition in one
+// instruction, the sum rounded once to fp32
+__device__ inline float lo_plus(uint32_t w, float c) {
+  float r;
+  asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(w), "v"(c));
+  return r;
+}
+__device__ inline float hi_plus(uint32_t w, float c) {
+  float r;
+  asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(w), "v"(c));
   return r;
 }
 
-constexpr int kQuadXor1 = 0xB1;        // quad_perm:[1,0,3,2]
-constexpr int kQuadXor2 = 0x4E;        // quad_perm:[2,3,0,1]
-constexpr int kRowHalfMirror = 0x141;  // lane i <-> 7 - i inside 8 lanes
-constexpr int kRowMirror = 0x140;      // lane i <-> 15 - i inside 16 lanes
-
-// v holds (min, -max) of a lane's 8 values; returns the same pair over the GL lanes of a group.
-template <int GL>
-__device__ inline uint32_t group_reduce(uint32_t v) {
-  v = pk_min(v, dpp<kQuadXor1>(v));
-  v = pk_min(v, dpp<kQuadXor2>(v));
-  if (GL >= 8) v = pk_min(v, dpp<kRowHalfMirror>(v));
-  if (GL >= 16) v = pk_min(v, dpp<kRowMirror>(v));
-  return v;
+// (a << s) + b in one instruction
+__device__ inline uint32_t shl_add(uint32_t a, uint32_t s, uint32_t b) {
+  uint32_t r;
+  asm("v_lshl_add_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "n"(s), "v"(b));
+  return r;
 }
 
 __device__ inline float half_bits_to_float(uint32_t h) {
@@ -70,140 +108,151 @@ __device__ inline uint32_t float_to_half_bits(float f) {
 constexpr float kMagic = 12582912.0f;       // 2^23 + 2^22: adding it rounds to an integer, ties to even
 constexpr uint32_t kMagicBits = 0x4B400000u;
 
-// Sum of kMagicBits << (i*W) over the codes that share one 32-bit accumulator.
+// Sum of kMagicBits << (i*W) over the 32/W codes that share one 32-bit accumulator.
 template <int W>
 __host__ __device__ constexpr uint32_t magic_carry() {
   uint32_t s = 0;
-  const int n = (W == 8) ? 4 : 8;
-  for (int i = 0; i < n; ++i) s += kMagicBits << (i * W);
+  for (int i = 0; i < 32 / W; ++i) s += kMagicBits << (i * W);
   return s;
 }
 
-// Row id (plane * T + token) that lane `lane` of the wave looks up for row `lane` of a tile.
-// 0xFFFFFFFF marks rows past the end of the segment.
-__device__ inline uint32_t tile_row_lookup(const CardGeom& g, const uint32_t* __restrict__ order, int c, uint32_t r0,
-                                           uint32_t n_rows, uint32_t lane, uint32_t tile_rows) {
-  uint32_t rowid = 0xFFFFFFFFu;
+// LDS position (in 16-byte units) of input chunk q of a tile.
+__device__ inline uint32_t swizzle(uint32_t q) { return q ^ ((q >> 3) & 3u); }
+
+// ---- rows of a tile -------------------------------------------------------------------------
+
+// Address of the fp16 row that row `lane` of the tile is made from, 0 past the segment's end.
+__device__ inline uint64_t tile_row_address(const PackArgs& a, int c, uint32_t r0, uint32_t n_rows, uint32_t lane,
+                                            uint32_t tile_rows) {
+  const CardGeom& g = a.g;
+  uint64_t addr = 0;
   const uint32_t r = r0 + lane;
   if (lane < tile_rows && r < n_rows) {
     const uint32_t n = g.n[c];
     const uint32_t p = r / n;
     const uint32_t j = r - p * n;
-    const uint32_t t = order[g.base[c] + j];
-    rowid = p * g.tokens + t;
+    const uint32_t t = reinterpret_cast<const uint32_t*>(a.card + g.off_order)[g.base[c] + j];
+    const uint32_t lh = g.planes >> 1;
+    const uint32_t row_bytes = g.head_dim * 2u;
+    // V rows continue the plane numbering after K's; each address stays inside its own tensor
+    addr = (p < lh) ? reinterpret_cast<uint64_t>(a.k) + ((uint64_t)p * g.tokens + t) * row_bytes
+                    : reinterpret_cast<uint64_t>(a.v) + ((uint64_t)(p - lh) * g.tokens + t) * row_bytes;
   }
-  return rowid;
+  return addr;
 }
 
-__device__ inline const uint8_t* row_address(const PackArgs& a, uint32_t rowid, uint32_t row_bytes) {
-  // V rows continue the numbering after K's; integer arithmetic, so no pointer ever leaves its buffer
-  const uint64_t k_bytes = (uint64_t)a.g.k_rows * row_bytes;
-  const uint64_t off = (uint64_t)rowid * row_bytes;
-  const uint64_t addr = (rowid < a.g.k_rows) ? reinterpret_cast<uint64_t>(a.k) + off
-                                             : reinterpret_cast<uint64_t>(a.v) + (off - k_bytes);
-  return reinterpret_cast<const uint8_t*>(addr);
+// Loads the tile: data[k] = chunk 64 k + lane, zero where the row does not exist.
+__device__ inline void load_tile(uint64_t my_row_addr, uint32_t lane, uint32_t lpr_shift, u32x4 (&data)[kTileIters]) {
+  const uint32_t in_row = (lane & ((1u << lpr_shift) - 1u)) * 16u;
+#pragma unroll
+  for (int k = 0; k < kTileIters; ++k) {
+    const uint32_t src_lane = (k * kWaveSize + lane) >> lpr_shift;
+    const uint32_t lo = __shfl((uint32_t)my_row_addr, src_lane, kWaveSize);
+    const uint32_t hi = __shfl((uint32_t)(my_row_addr >> 32), src_lane, kWaveSize);
+    const uint64_t row = ((uint64_t)hi << 32) | lo;
+    data[k] = (u32x4)(0u);
+    if (row != 0) data[k] = __builtin_nontemporal_load(reinterpret_cast<global_u32x4*>(row + in_row));
+  }
 }
 
-// ---- one tile of a quantized segment ------------------------------------------------------
+// ---- one span of 32 values --------------------------------------------------------------------
+
+template <int W, bool CLAMP>
+__device__ inline void encode_span(const uint32_t (&w)[16], float neg_mn, float inv, uint32_t (&out)[W]) {
+  constexpr uint32_t QMAX = (1u << W) - 1u;
+  constexpr int PER = 32 / W;               // codes per output dword
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    const float d = (i & 1) ? hi_plus(w[i >> 1], neg_mn) : lo_plus(w[i >> 1], neg_mn);
+    const float r = __builtin_fmaf(d, inv, kMagic);       // exact product, one rounding, ties to even
+    uint32_t u = __float_as_uint(r);
+    if (CLAMP) u = min(u, kMagicBits + QMAX);
+    const int o = i / PER, s = (i % PER) * W;
+    out[o] = (s == 0) ? u : shl_add(u, s, out[o]);
+  }
+#pragma unroll
+  for (int o = 0; o < W; ++o) out[o] -= magic_carry<W>();
+}
 
 template <int W, int G>
-__device__ inline void pack_tile(const PackArgs& a, int c, uint32_t r0, uint32_t n_rows, uint32_t lane,
-                                 uint8_t* lds_codes, uint32_t* lds_meta) {
-  constexpr int GL = G / 8;                       // lanes per group
-  constexpr uint32_t QMAX = (1u << W) - 1u;
+__device__ inline void pack_tile(const PackArgs& a, int c, uint32_t r0, uint32_t n_rows, uint32_t lane, u32x4* lds) {
+  constexpr int GS = G / 32;                     // spans (lanes) per group
+  constexpr float QMAXF = (float)((1 << W) - 1);
+  constexpr float RCPQ = 1.0f / QMAXF;           // correctly rounded at compile time
   const CardGeom& g = a.g;
   const uint32_t lpr_shift = g.lpr_shift;
   const uint32_t tile_rows = kTileChunks >> lpr_shift;
-  const uint32_t row_bytes = g.head_dim * 2u;
-  const uint32_t* order = reinterpret_cast<const uint32_t*>(a.card + g.off_order);
+  const uint32_t spr_shift = lpr_shift - 2;      // log2(spans per row)
 
-  const uint32_t my_row = tile_row_lookup(g, order, c, r0, n_rows, lane, tile_rows);
-
-  uint4 data[kTileIters];
+  const uint64_t my_row = tile_row_address(a, c, r0, n_rows, lane, tile_rows);
+  u32x4 data[kTileIters];
+  load_tile(my_row, lane, lpr_shift, data);
+  const uint32_t wslot = swizzle(lane);
 #pragma unroll
-  for (int k = 0; k < kTileIters; ++k) {
-    const uint32_t q = k * kWaveSize + lane;
-    const uint32_t rowid = __shfl(my_row, q >> lpr_shift, kWaveSize);
-    data[k] = make_uint4(0, 0, 0, 0);
-    if (rowid != 0xFFFFFFFFu) {
-      const uint8_t* src = row_address(a, rowid, row_bytes) + (q & ((1u << lpr_shift) - 1u)) * 16u;
-      data[k] = *reinterpret_cast<const uint4*>(src);
+  for (int k = 0; k < kTileIters; ++k) lds[k * kWaveSize + wslot] = data[k];
+
+  const uint32_t x = (lane >> 1) & 3u;           // swizzle term of this lane's spans
+  uint8_t* codes_seg = a.card + g.off_codes[c];
+  uint32_t* meta_seg = reinterpret_cast<uint32_t*>(a.card + g.off_meta[c]);
+  const uint64_t span0 = (uint64_t)r0 << spr_shift;                   // first span of the tile inside the segment
+  const uint64_t seg_spans = (uint64_t)n_rows << spr_shift;
+
+#pragma unroll 1
+  for (int round = 0; round < 2; ++round) {
+    const uint32_t sp = round * kWaveSize + lane;
+    uint32_t w[16];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const u32x4 t = lds[4 * sp + (j ^ x)];
+      w[4 * j + 0] = t.x; w[4 * j + 1] = t.y; w[4 * j + 2] = t.z; w[4 * j + 3] = t.w;
     }
-  }
+    // extrema of the span, then of the group
+    uint32_t m = pk_min(pk_min3(pk_min3(w[0], w[1], w[2]), pk_min3(w[3], w[4], w[5]), pk_min3(w[6], w[7], w[8])),
+                        pk_min3(pk_min3(w[9], w[10], w[11]), pk_min3(w[12], w[13], w[14]), w[15]));
+    uint32_t M = pk_max(pk_max3(pk_max3(w[0], w[1], w[2]), pk_max3(w[3], w[4], w[5]), pk_max3(w[6], w[7], w[8])),
+                        pk_max3(pk_max3(w[9], w[10], w[11]), pk_max3(w[12], w[13], w[14]), w[15]));
+    m = pk_min_halves(m);
+    M = pk_max_halves(M);
+    if (GS >= 2) { m = pk_min(m, dpp<kQuadXor1>(m)); M = pk_max(M, dpp<kQuadXor1>(M)); }
+    if (GS >= 4) { m = pk_min(m, dpp<kQuadXor2>(m)); M = pk_max(M, dpp<kQuadXor2>(M)); }
+    const uint32_t mn_h = m & 0xFFFFu;
 
-#pragma unroll
-  for (int k = 0; k < kTileIters; ++k) {
-    const uint32_t q = k * kWaveSize + lane;
-    const uint32_t w0 = data[k].x, w1 = data[k].y, w2 = data[k].z, w3 = data[k].w;
-    // (min, -max) over the lane's 8 values, then over the group's lanes
-    const uint32_t mn2 = pk_min(pk_min(w0, w1), pk_min(w2, w3));
-    const uint32_t ng2 = pk_min(pk_min_neg(w0, w1), pk_min_neg(w2, w3));
-    const uint32_t lo = __builtin_amdgcn_perm(ng2, mn2, 0x05040100u);   // (mn2.lo, ng2.lo)
-    const uint32_t hi = __builtin_amdgcn_perm(ng2, mn2, 0x07060302u);   // (mn2.hi, ng2.hi)
-    const uint32_t red = group_reduce<GL>(pk_min(lo, hi));
-    const uint32_t mn_h = red & 0xFFFFu;
-    const uint32_t mx_h = (red >> 16) ^ 0x8000u;
-
-    // scale and reciprocal: fp32, this order, IEEE division
+    // scale = fp16(range / qmax), inv = 1 / scale: fp32, correctly rounded.
+    // Quotient: q0 = range * (1/qmax) is within one ulp, its exact residual corrects it.
     const float fmn = half_bits_to_float(mn_h);
-    const float fmx = half_bits_to_float(mx_h);
+    const float fmx = half_bits_to_float(M & 0xFFFFu);
     const float range = fmx - fmn;
-    const float s32 = range / (float)QMAX;
+    const float q0 = range * RCPQ;
+    float s32 = __builtin_fmaf(__builtin_fmaf(-q0, QMAXF, range), RCPQ, q0);
+    // Keep the fp32 quotient and its conversion apart: fused into one fma-and-convert
+    // instruction the value would be rounded once, straight to fp16, which differs from
+    // rounding to fp32 first whenever the fp32 result lands on an fp16 midpoint.
+    asm("" : "+v"(s32));
     const uint32_t s_h = float_to_half_bits(s32);
     const float s = half_bits_to_float(s_h);
-    const float inv = (s > 0.0f) ? 1.0f / s : 0.0f;
+    // Reciprocal: the hardware estimate is within one ulp; s has 11 significant bits, so 1/s
+    // is never closer than 2^-12 ulp to a rounding boundary and one residual step lands on
+    // the correctly rounded value.
+    const float y0 = __builtin_amdgcn_rcpf(s);
+    const float y1 = __builtin_fmaf(__builtin_fmaf(-s, y0, 1.0f), y0, y0);
+    const float inv = (s > 0.0f) ? y1 : 0.0f;
 
-    // codes: RNE of the exact product through the magic-number fma, clamped to QMAX
-    const uint32_t words[4] = {w0, w1, w2, w3};
-    uint32_t acc0 = 0, acc1 = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const uint32_t hbits = (i & 1) ? (words[i >> 1] >> 16) : (words[i >> 1] & 0xFFFFu);
-      const float d = half_bits_to_float(hbits) - fmn;
-      const float r = __builtin_fmaf(d, inv, kMagic);
-      const uint32_t u = min(__float_as_uint(r), kMagicBits + QMAX);
-      if (W == 8) {
-        if (i < 4) acc0 = (u << (8 * i)) + acc0; else acc1 = (u << (8 * (i - 4))) + acc1;
-      } else {
-        acc0 = (u << (W * i)) + acc0;
-      }
-    }
-    acc0 -= magic_carry<W>();
-    if (W == 8) acc1 -= magic_carry<W>();
+    // The clamp to qmax can only act when the stored scale is an fp16 subnormal; otherwise
+    // d * inv <= qmax * (1 + 2^-11 + ...) already rounds to at most qmax.
+    uint32_t out[W];
+    const bool needs_clamp = (s_h - 1u) < 0x3FFu;
+    if (__builtin_amdgcn_ballot_w64(needs_clamp) != 0) encode_span<W, true>(w, -fmn, inv, out);
+    else encode_span<W, false>(w, -fmn, inv, out);
 
-    if (W == 2) reinterpret_cast<uint16_t*>(lds_codes)[q] = (uint16_t)acc0;
-    if (W == 4) reinterpret_cast<uint32_t*>(lds_codes)[q] = acc0;
-    if (W == 8) reinterpret_cast<uint2*>(lds_codes)[q] = make_uint2(acc0, acc1);
-    if ((lane & (GL - 1)) == 0) lds_meta[q / GL] = s_h | (mn_h << 16);   // fp16 scale first, then fp16 zero
-  }
-  __builtin_amdgcn_wave_barrier();
-
-  // codes: tile = 512*W bytes, 16 bytes per lane per store
-  {
-    const uint64_t seg_bytes = (uint64_t)n_rows * (g.head_dim * W / 8);
-    const uint64_t tile_off = (uint64_t)r0 * (g.head_dim * W / 8);
-    uint8_t* dst = a.card + g.off_codes[c];
-#pragma unroll
-    for (int m = 0; m < W / 2; ++m) {
-      const uint32_t idx = m * kWaveSize + lane;
-      const uint4 o = reinterpret_cast<const uint4*>(lds_codes)[idx];
-      const uint64_t off = tile_off + (uint64_t)idx * 16u;
-      if (off < seg_bytes) *reinterpret_cast<uint4*>(dst + off) = o;
+    const uint64_t gsp = span0 + sp;
+    if (gsp < seg_spans) {
+      uint8_t* dst = codes_seg + gsp * (4u * W);
+      if (W == 2) *reinterpret_cast<u32x2*>(dst) = (u32x2){out[0], out[1]};
+      if (W >= 4) *reinterpret_cast<u32x4*>(dst) = (u32x4){out[0], out[1], out[2], out[3]};
+      if (W == 8) *reinterpret_cast<u32x4*>(dst + 16) = (u32x4){out[4], out[5], out[6], out[7]};
+      if ((sp & (GS - 1)) == 0) meta_seg[gsp / GS] = s_h | (mn_h << 16);   // fp16 scale first, then fp16 zero
     }
   }
-  // (scale, zero) pairs: 512/GL dwords per tile
-  {
-    constexpr int kDwords = kTileChunks / GL;
-    const uint64_t seg_dwords = (uint64_t)n_rows * (g.head_dim / G);
-    const uint64_t tile_dw = (uint64_t)r0 * (g.head_dim / G);
-    uint32_t* dst = reinterpret_cast<uint32_t*>(a.card + g.off_meta[c]);
-#pragma unroll
-    for (int m = 0; m < (kDwords + kWaveSize - 1) / kWaveSize; ++m) {
-      const uint32_t idx = m * kWaveSize + lane;
-      if (idx < (uint32_t)kDwords && tile_dw + idx < seg_dwords) dst[tile_dw + idx] = lds_meta[idx];
-    }
-  }
-  __builtin_amdgcn_wave_barrier();
 }
 
 // ---- one tile of the fp16 segment: rows copied bit for bit ---------------------------------
@@ -213,42 +262,29 @@ __device__ inline void copy_tile(const PackArgs& a, uint32_t r0, uint32_t n_rows
   const uint32_t lpr_shift = g.lpr_shift;
   const uint32_t tile_rows = kTileChunks >> lpr_shift;
   const uint32_t row_bytes = g.head_dim * 2u;
-  const uint32_t* order = reinterpret_cast<const uint32_t*>(a.card + g.off_order);
-  const uint32_t my_row = tile_row_lookup(g, order, 3, r0, n_rows, lane, tile_rows);
-  uint4 data[kTileIters];
-  bool valid[kTileIters];
-#pragma unroll
-  for (int k = 0; k < kTileIters; ++k) {
-    const uint32_t q = k * kWaveSize + lane;
-    const uint32_t rowid = __shfl(my_row, q >> lpr_shift, kWaveSize);
-    valid[k] = rowid != 0xFFFFFFFFu;
-    data[k] = make_uint4(0, 0, 0, 0);
-    if (valid[k]) {
-      const uint8_t* src = row_address(a, rowid, row_bytes) + (q & ((1u << lpr_shift) - 1u)) * 16u;
-      data[k] = *reinterpret_cast<const uint4*>(src);
-    }
-  }
+  const uint64_t my_row = tile_row_address(a, 3, r0, n_rows, lane, tile_rows);
+  u32x4 data[kTileIters];
+  load_tile(my_row, lane, lpr_shift, data);
   uint8_t* dst = a.card + g.off_fp16 + (uint64_t)r0 * row_bytes;
+  const uint64_t left = ((uint64_t)n_rows - r0) * row_bytes;     // bytes from the tile start to the segment end
 #pragma unroll
   for (int k = 0; k < kTileIters; ++k) {
-    const uint32_t q = k * kWaveSize + lane;
-    if (valid[k]) *reinterpret_cast<uint4*>(dst + (uint64_t)q * 16u) = data[k];
+    const uint64_t off = (uint64_t)(k * kWaveSize + lane) * 16u;
+    if (off < left) *reinterpret_cast<u32x4*>(dst + off) = data[k];
   }
 }
 
-// ---- persistent kernel ------------------------------------------------------------------------
+// ---- grid ----------------------------------------------------------------------------------------
 
 template <int G>
 __global__ __launch_bounds__(kBlockThreads) void pack_kernel(PackArgs a) {
-  __shared__ __attribute__((aligned(16))) uint8_t lds_codes[kWavesPerBlock][kTileChunks * 8];
-  __shared__ uint32_t lds_meta[kWavesPerBlock][kTileChunks / 4];
+  __shared__ u32x4 lds[kWavesPerBlock][kTileChunks];
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t wave = threadIdx.x >> 6;
   const uint32_t gw = blockIdx.x * kWavesPerBlock + wave;
   const uint32_t n_waves = gridDim.x * kWavesPerBlock;
   const uint32_t tile_rows = kTileChunks >> a.g.lpr_shift;
-  uint8_t* my_codes = lds_codes[wave];
-  uint32_t* my_meta = lds_meta[wave];
+  u32x4* my_lds = lds[wave];
 
   uint32_t cum = 0;   // tiles of the classes already done, modulo n_waves
 #pragma unroll
@@ -259,9 +295,9 @@ __global__ __launch_bounds__(kBlockThreads) void pack_kernel(PackArgs a) {
     const uint32_t first = (gw + n_waves - cum) % n_waves;
     for (uint32_t i = first; i < tiles; i += n_waves) {
       const uint32_t r0 = i * tile_rows;
-      if (c == 0) pack_tile<2, G>(a, 0, r0, n_rows, lane, my_codes, my_meta);
-      if (c == 1) pack_tile<4, G>(a, 1, r0, n_rows, lane, my_codes, my_meta);
-      if (c == 2) pack_tile<8, G>(a, 2, r0, n_rows, lane, my_codes, my_meta);
+      if (c == 0) pack_tile<2, G>(a, 0, r0, n_rows, lane, my_lds);
+      if (c == 1) pack_tile<4, G>(a, 1, r0, n_rows, lane, my_lds);
+      if (c == 2) pack_tile<8, G>(a, 2, r0, n_rows, lane, my_lds);
       if (c == 3) copy_tile(a, r0, n_rows, lane);
     }
     cum = (cum + tiles) % n_waves;

@@ -30,9 +30,6 @@ struct UnpackArgs {
 __device__ inline float half_bits_to_float(uint32_t h) {
   return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
 }
-__device__ inline uint32_t float_to_half_bits(float f) {
-  return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);   // round to nearest even
-}
 
 // True when the header describes a layout-v1 card of the expected shape that fits in
 // card_bytes; fills `g` from the header's class counts.  Uniform over the grid.
@@ -86,11 +83,20 @@ __device__ inline uint8_t* row_address(const UnpackArgs& a, const CardGeom& g, u
   return reinterpret_cast<uint8_t*>(addr);
 }
 
-// decode = fp16( fma(code, scale, zero) ): one fp32 fma, then round to nearest even
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// decode = fp16( fma(code, scale, zero) ): an fp32 fma rounded to fp32, then rounded to
+// fp16, both to nearest even.  The two steps are kept apart on purpose: the fused
+// fma-and-convert instruction rounds the exact sum once, straight to fp16, which gives a
+// different value whenever the fp32 result lands on an fp16 midpoint.
 __device__ inline uint32_t decode_pair(uint32_t q0, uint32_t q1, float s, float z) {
-  const uint32_t lo = float_to_half_bits(__builtin_fmaf((float)q0, s, z));
-  const uint32_t hi = float_to_half_bits(__builtin_fmaf((float)q1, s, z));
-  return lo | (hi << 16);
+  float a = __builtin_fmaf((float)q0, s, z);
+  float b = __builtin_fmaf((float)q1, s, z);
+  asm("" : "+v"(a));
+  asm("" : "+v"(b));
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
 }
 
 template <int W, int G>

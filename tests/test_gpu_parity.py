@@ -181,6 +181,28 @@ def test_special_values_every_width(G):
         check_round_trip(desc, K, V, bits, "special values %d-bit G%d" % (width, G))
 
 
+def test_every_group_range_from_zero_to_each_fp16_value():
+    # group g spans [0, v_g] for every positive finite fp16 v_g (K) and [-v_g, v_g'] (V): walks
+    # the quotient range / qmax and the reciprocal of every reachable stored scale
+    L, H, T, D, G = 1, 1, 8192, 128, 32
+    rng = np.random.default_rng(21)
+    tops = np.arange(1, 0x7C00, dtype=np.uint16)                      # 31743 values
+    tops = np.concatenate([tops, rng.integers(1, 0x7C00, size=T * 4 - tops.size).astype(np.uint16)])
+    top_f = tops.view(np.float16).astype(np.float32).reshape(T, 4, 1)
+    frac = rng.random((T, 4, G)).astype(np.float32)
+    frac[:, :, 0] = 0.0
+    frac[:, :, 1] = 1.0
+    K = (frac * top_f).astype(np.float16).reshape(1, 1, T, D)
+    other = rng.permutation(tops).view(np.float16).astype(np.float32).reshape(T, 4, 1)
+    Vv = (frac * (top_f + other) - other)
+    Vv[:, :, 0] = -other[:, :, 0]
+    Vv[:, :, 1] = top_f[:, :, 0]
+    V = Vv.astype(np.float16).reshape(1, 1, T, D)
+    desc = qkv.Desc.make(L, H, T, D, G)
+    for width in (2, 4, 8):
+        check_round_trip(desc, K, V, np.full(T, width, dtype=np.uint8), "all ranges, %d-bit" % width)
+
+
 def test_raw_rows_carry_nan_and_inf_payloads():
     L, H, T, D, G = 1, 2, 40, 128, 32
     desc, K, V = make_problem(L, H, T, D, G, seed=9)
@@ -191,6 +213,42 @@ def test_raw_rows_carry_nan_and_inf_payloads():
     ku[:, :, ::3, :] = rng.integers(0, 65536, size=ku[:, :, ::3, :].shape).astype(np.uint16)   # any pattern at all
     card, k, v = check_round_trip(desc, K, V, bits, "raw rows with arbitrary bit patterns")
     assert np.array_equal(k[:, :, ::3, :], ku[:, :, ::3, :])
+
+
+def test_unpack_of_arbitrary_card_contents():
+    # Receiver side alone: a card whose code bytes and (scale, zero) pairs are arbitrary finite
+    # patterns, not the output of any quantizer.  Random pairs make the fp32 sum land on fp16
+    # midpoints often enough (about one value in 2^14) to tell two roundings from one.
+    L, H, T, D, G = 2, 4, 1024, 128, 32
+    desc, K, V = make_problem(L, H, T, D, G, seed=71)
+    bits = qkv_synth.make_bits_uniform_choice(T, 72).numpy()
+    counts = [int((bits == w).sum()) for w in (2, 4, 8, 16)]
+    rd = ref_desc(desc)
+    card = ref.quantize_pack(rd, K, V, bits, counts)
+    off = ref.card_offsets(rd, counts)
+    rng = np.random.default_rng(73)
+    P = 2 * L * H
+    for c, w in enumerate((2, 4, 8)):
+        n_code = P * counts[c] * D * w // 8
+        card[off["codes%d" % w]:off["codes%d" % w] + n_code] = rng.integers(0, 256, size=n_code, dtype=np.uint8)
+        n_pair = P * counts[c] * (D // G)
+        pairs = rng.integers(0, 65536, size=(n_pair, 2)).astype(np.uint16)
+        pairs[:, 0] &= 0x7FFF                                   # scale >= 0
+        inf_nan = (pairs & 0x7C00) == 0x7C00
+        pairs[inf_nan] &= 0xBFFF                                # finite
+        if w == 8:   # a hand-made case: 245 * (1070 * 2^-19) + 1024 = 1024.50001...: fp32 gives 1024.5, then the tie goes to 1024
+            pairs[0] = (0x182E, 0x6400)
+            card[off["codes8"]] = 245
+        card[off["meta%d" % w]:off["meta%d" % w] + n_pair * 4] = pairs.view(np.uint8).ravel()
+    say("arbitrary card contents")
+    k, v, st = gpu_unpack(torch.from_numpy(card).to(DEV), desc)
+    assert st == 0
+    wk, wv = ref.unpack_dequant(card, rd)
+    slot, order, _ = ref.compact(bits)
+    t8 = int(order[counts[0] + counts[1]])                       # first 8-bit token, plane 0, element 0
+    assert wk[0, 0, t8, 0] == 0x6400, hex(int(wk[0, 0, t8, 0]))
+    assert first_diff(k.ravel(), wk.ravel()) is None, "K differs: %r" % (first_diff(k.ravel(), wk.ravel()),)
+    assert first_diff(v.ravel(), wv.ravel()) is None, "V differs: %r" % (first_diff(v.ravel(), wv.ravel()),)
 
 
 def test_llama_shape_slice_with_budget_bits():
