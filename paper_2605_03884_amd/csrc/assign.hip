@@ -8,6 +8,10 @@
 // before it; tokens whose key equals the cut key are then admitted by increasing index until
 // the cut is full (a stable block-wide prefix count).  One workgroup does it all: the scores
 // are a few tens of KiB and stay in cache over the five sweeps.
+//
+// The first pass sees every key and real scores share their top byte (sign and exponent), so
+// its histogram is kept in 32 copies, one per lane modulo 32: lanes of one instruction never
+// add to the same word.  The later passes only count keys that match a cut's prefix.
 #include "qkv_common.h"
 
 namespace qkv {
@@ -15,6 +19,7 @@ namespace {
 
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / kWaveSize;
+constexpr int kCopies = 32;
 
 // Key that grows as the rank grows: smaller key = better score.  -0 ranks below +0.
 __device__ inline uint32_t rank_key(float score) {
@@ -32,47 +37,98 @@ __device__ inline uint32_t wave_inclusive_scan(uint32_t v, uint32_t lane) {
   return v;
 }
 
+// One wave finds the bucket that holds rank `left` in a 256-bucket histogram: the first d
+// whose cumulative count exceeds `left`.  Returns d and lowers `left` by the count before it.
+// The histogram's total must exceed `left`.
+__device__ inline uint32_t find_bucket(const uint32_t* hist, uint32_t lane, uint32_t& left) {
+  const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+  const uint32_t inc = wave_inclusive_scan(h0 + h1 + h2 + h3, lane);
+  const uint64_t over = __builtin_amdgcn_ballot_w64(inc > left);
+  const uint32_t owner = (uint32_t)__builtin_ctzll(over | (1ull << 63));
+  const uint32_t before = __shfl(inc - (h0 + h1 + h2 + h3), owner, kWaveSize);
+  const uint32_t a0 = __shfl(h0, owner, kWaveSize), a1 = __shfl(h1, owner, kWaveSize), a2 = __shfl(h2, owner, kWaveSize);
+  uint32_t rest = left - before;
+  uint32_t d = 4 * owner;
+  if (rest >= a0) { rest -= a0; ++d; if (rest >= a1) { rest -= a1; ++d; if (rest >= a2) { rest -= a2; ++d; } } }
+  left = rest;
+  return d;
+}
+
+// KPT > 0: each thread keeps the keys of its KPT consecutive tokens in registers (needs
+// T <= KPT * kThreads); KPT == 0: any T, keys re-read from the scores on every sweep.
+template <int KPT>
 __global__ __launch_bounds__(kThreads) void assign_kernel(const float* __restrict__ scores, uint32_t T, uint32_t cut0,
                                                           uint32_t cut1, uint32_t cut2, uint8_t* __restrict__ bits) {
+  __shared__ uint32_t wide[256 * kCopies];   // first pass: bucket d, copy c at [d * 32 + c]
   __shared__ uint32_t hist[3][256];
-  __shared__ uint32_t sel_prefix[3];     // key bits fixed so far
-  __shared__ uint32_t sel_left[3];       // rank still to descend inside the current bucket
+  __shared__ uint32_t sel_prefix[3];         // key bits fixed so far
+  __shared__ uint32_t sel_left[3];           // rank still to descend inside the current bucket
   __shared__ uint32_t wave_tot[3][kWaves];
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wave = tid >> 6;
   const uint32_t cut[3] = {cut0, cut1, cut2};
 
-  if (tid < 3) { sel_prefix[tid] = 0; sel_left[tid] = cut[tid]; }
+  // thread tid owns the tokens [t0, t1)
+  const uint32_t per = KPT > 0 ? (uint32_t)KPT : (T + kThreads - 1) / kThreads;
+  const uint32_t t0 = min(tid * per, T);
+  const uint32_t t1 = min(t0 + per, T);
+  uint32_t keys[KPT > 0 ? KPT : 1];
+  if (KPT > 0) {
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) keys[i] = (t0 + i < t1) ? rank_key(scores[t0 + i]) : 0u;
+  }
+  // visits every owned token's key
+  auto for_each_key = [&](auto&& f) {
+    if (KPT > 0) {
+#pragma unroll
+      for (int i = 0; i < KPT; ++i) if (t0 + i < t1) f(keys[i], t0 + i);
+    } else {
+#pragma unroll 4
+      for (uint32_t t = t0; t < t1; ++t) f(rank_key(scores[t]), t);
+    }
+  };
 
-  // radix select, most significant byte first.  A cut equal to T has no token at that rank:
-  // every token lies before it, handled below without a key.
-  for (int pass = 0; pass < 4; ++pass) {
+  // ---- pass 0: one histogram of the top byte, shared by the three cuts
+  for (uint32_t i = tid; i < 256 * kCopies; i += kThreads) wide[i] = 0;
+  __syncthreads();
+  for_each_key([&](uint32_t key, uint32_t) { atomicAdd(&wide[(key >> 24) * kCopies + (lane & 31u)], 1u); });
+  __syncthreads();
+  if (tid < 256) {
+    uint32_t s = 0;
+#pragma unroll 8
+    for (int i = 0; i < kCopies; ++i) s += wide[tid * kCopies + ((i + tid) & 31u)];
+    hist[0][tid] = s;
+  }
+  __syncthreads();
+  // A cut equal to T has no token at that rank: every token lies before it, handled below
+  // without a key.
+  if (wave < 3 && cut[wave] < T) {
+    uint32_t left = cut[wave];
+    const uint32_t d = find_bucket(hist[0], lane, left);
+    if (lane == 0) { sel_prefix[wave] = d << 24; sel_left[wave] = left; }
+  }
+  __syncthreads();
+
+  // ---- passes 1..3: per cut, only the keys inside its bucket so far
+  for (int pass = 1; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
-    for (uint32_t i = tid; i < 3 * 256; i += kThreads) hist[i >> 8][i & 255u] = 0;
-    __syncthreads();
+    if (tid < 3 * 256) hist[tid >> 8][tid & 255u] = 0;
     uint32_t pre[3];
 #pragma unroll
     for (int c = 0; c < 3; ++c) pre[c] = sel_prefix[c];
-    const uint32_t high_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
-    for (uint32_t t = tid; t < T; t += kThreads) {
-      const uint32_t key = rank_key(scores[t]);
+    __syncthreads();
+    const uint32_t high_mask = 0xFFFFFFFFu << (shift + 8);
+    for_each_key([&](uint32_t key, uint32_t) {
 #pragma unroll
       for (int c = 0; c < 3; ++c) {
         if (cut[c] < T && ((key ^ pre[c]) & high_mask) == 0) atomicAdd(&hist[c][(key >> shift) & 255u], 1u);
       }
-    }
+    });
     __syncthreads();
-    if (tid < 3 && cut[tid] < T) {
-      uint32_t left = sel_left[tid];
-      uint32_t d = 0;
-      // the bucket that holds rank `left`: first d with cumulative count > left
-      for (; d < 255; ++d) {
-        const uint32_t h = hist[tid][d];
-        if (left < h) break;
-        left -= h;
-      }
-      sel_prefix[tid] |= d << shift;
-      sel_left[tid] = left;
+    if (wave < 3 && cut[wave] < T) {
+      uint32_t left = sel_left[wave];
+      const uint32_t d = find_bucket(hist[wave], lane, left);
+      if (lane == 0) { sel_prefix[wave] |= d << shift; sel_left[wave] = left; }
     }
     __syncthreads();
   }
@@ -83,15 +139,11 @@ __global__ __launch_bounds__(kThreads) void assign_kernel(const float* __restric
 #pragma unroll
   for (int c = 0; c < 3; ++c) { keyc[c] = sel_prefix[c]; quota[c] = sel_left[c]; }
 
-  const uint32_t per = (T + kThreads - 1) / kThreads;
-  const uint32_t t0 = min(tid * per, T);
-  const uint32_t t1 = min(t0 + per, T);
   uint32_t eq[3] = {0, 0, 0};
-  for (uint32_t t = t0; t < t1; ++t) {
-    const uint32_t key = rank_key(scores[t]);
+  for_each_key([&](uint32_t key, uint32_t) {
 #pragma unroll
     for (int c = 0; c < 3; ++c) eq[c] += (key == keyc[c]);
-  }
+  });
   uint32_t run[3];
 #pragma unroll
   for (int c = 0; c < 3; ++c) {
@@ -106,8 +158,7 @@ __global__ __launch_bounds__(kThreads) void assign_kernel(const float* __restric
     for (uint32_t w = 0; w < wave; ++w) before += wave_tot[c][w];
     run[c] += before;
   }
-  for (uint32_t t = t0; t < t1; ++t) {
-    const uint32_t key = rank_key(scores[t]);
+  for_each_key([&](uint32_t key, uint32_t t) {
     bool before[3];
 #pragma unroll
     for (int c = 0; c < 3; ++c) {
@@ -117,7 +168,7 @@ __global__ __launch_bounds__(kThreads) void assign_kernel(const float* __restric
       run[c] += is_eq;
     }
     bits[t] = before[0] ? 16 : before[1] ? 8 : before[2] ? 4 : 2;
-  }
+  });
 }
 
 __global__ __launch_bounds__(256) void count_kernel(const uint8_t* __restrict__ bits, uint64_t T,
@@ -145,8 +196,13 @@ __global__ void zero4_kernel(unsigned long long* p) {
 
 hipError_t launch_assign(const float* scores, uint32_t tokens, const uint32_t cuts[3], uint8_t* bits,
                          hipStream_t stream) {
-  hipLaunchKernelGGL(assign_kernel, dim3(1), dim3(kThreads), 0, stream, scores, tokens, cuts[0], cuts[1], cuts[2],
-                     bits);
+  const dim3 grid(1), block(kThreads);
+  if (tokens <= 8u * kThreads)
+    hipLaunchKernelGGL(assign_kernel<8>, grid, block, 0, stream, scores, tokens, cuts[0], cuts[1], cuts[2], bits);
+  else if (tokens <= 32u * kThreads)
+    hipLaunchKernelGGL(assign_kernel<32>, grid, block, 0, stream, scores, tokens, cuts[0], cuts[1], cuts[2], bits);
+  else
+    hipLaunchKernelGGL(assign_kernel<0>, grid, block, 0, stream, scores, tokens, cuts[0], cuts[1], cuts[2], bits);
   return hipGetLastError();
 }
 

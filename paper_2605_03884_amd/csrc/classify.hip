@@ -33,6 +33,9 @@ __device__ inline int class_of(uint32_t b, uint32_t& bad) {
   }
 }
 
+// KPT > 0: each thread keeps the widths of its KPT consecutive tokens in registers (needs
+// T <= KPT * kThreads); KPT == 0: any T, widths read twice.
+template <int KPT>
 __global__ __launch_bounds__(kThreads) void classify_kernel(const uint8_t* __restrict__ bits, CardGeom g,
                                                            qkv_card_header_t header, uint8_t* __restrict__ card) {
   __shared__ uint32_t wave_tot[4][kWaves];
@@ -40,17 +43,32 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(const uint8_t* __res
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wave = tid >> 6;
   const uint32_t T = g.tokens;
-  const uint32_t per = (T + kThreads - 1) / kThreads;
+  const uint32_t per = KPT > 0 ? (uint32_t)KPT : (T + kThreads - 1) / kThreads;
   const uint32_t t0 = min(tid * per, T);      // tid * per < 2^32: per <= T / 1024 + 1
   const uint32_t t1 = min(t0 + per, T);
   if (tid == 0) bad_any = 0;
 
+  uint32_t held[KPT > 0 ? KPT : 1];
+  if (KPT > 0) {
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) held[i] = (t0 + i < t1) ? bits[t0 + i] : 2u;
+  }
+  auto for_each_token = [&](auto&& f) {
+    if (KPT > 0) {
+#pragma unroll
+      for (int i = 0; i < KPT; ++i) if (t0 + i < t1) f(held[i], t0 + i);
+    } else {
+#pragma unroll 4
+      for (uint32_t t = t0; t < t1; ++t) f((uint32_t)bits[t], t);
+    }
+  };
+
   uint32_t cnt[4] = {0, 0, 0, 0};
   uint32_t bad = 0;
-  for (uint32_t t = t0; t < t1; ++t) {
-    const int c = class_of(bits[t], bad);
+  for_each_token([&](uint32_t b, uint32_t) {
+    const int c = class_of(b, bad);
     cnt[0] += (c == 0); cnt[1] += (c == 1); cnt[2] += (c == 2); cnt[3] += (c == 3);
-  }
+  });
 
   uint32_t run[4];
 #pragma unroll
@@ -65,6 +83,7 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(const uint8_t* __res
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
     uint32_t before = 0, all = 0;
+#pragma unroll
     for (int w = 0; w < kWaves; ++w) {
       const uint32_t x = wave_tot[c][w];
       if ((uint32_t)w < wave) before += x;
@@ -81,15 +100,14 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(const uint8_t* __res
   uint8_t* bits_out = card + g.off_bits;
   uint32_t* slot_out = reinterpret_cast<uint32_t*>(card + g.off_slot);
   uint32_t* order_out = reinterpret_cast<uint32_t*>(card + g.off_order);
-  for (uint32_t t = t0; t < t1; ++t) {
-    const uint32_t b = bits[t];
+  for_each_token([&](uint32_t b, uint32_t t) {
     uint32_t dummy = 0;
     const int c = class_of(b, dummy);
-    const uint32_t s = run[c]++;
+    const uint32_t s = (c == 0) ? run[0]++ : (c == 1) ? run[1]++ : (c == 2) ? run[2]++ : run[3]++;
     bits_out[t] = (uint8_t)b;
     slot_out[t] = s;
     order_out[base[c] + s] = t;
-  }
+  });
   __syncthreads();
 
   // header: 64 dwords, the status word (dword 48) filled in from what the device saw
@@ -127,7 +145,13 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(const uint8_t* __res
 
 hipError_t launch_classify(const uint8_t* bits, const CardGeom& geom, const qkv_card_header_t& header,
                            uint8_t* card, hipStream_t stream) {
-  hipLaunchKernelGGL(classify_kernel, dim3(1), dim3(kThreads), 0, stream, bits, geom, header, card);
+  const dim3 grid(1), block(kThreads);
+  if (geom.tokens <= 8u * kThreads)
+    hipLaunchKernelGGL(classify_kernel<8>, grid, block, 0, stream, bits, geom, header, card);
+  else if (geom.tokens <= 32u * kThreads)
+    hipLaunchKernelGGL(classify_kernel<32>, grid, block, 0, stream, bits, geom, header, card);
+  else
+    hipLaunchKernelGGL(classify_kernel<0>, grid, block, 0, stream, bits, geom, header, card);
   return hipGetLastError();
 }
 

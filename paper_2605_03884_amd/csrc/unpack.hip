@@ -2,12 +2,13 @@
 // unpacked and dequantized into a dense fp16 K/V cache, 16-bit rows are copied back.
 //
 // Mirror image of the packing kernel.  A wave takes a tile of 512 sixteen-byte output
-// chunks (32 rows at head_dim 128) of one width's segment: the tile's code bytes and
-// (scale, zero) pairs are one contiguous run of the card, loaded with 128-bit reads and
-// staged in LDS; lane l of iteration k then owns output chunk q = 64 k + l, picks its 8
-// codes and its group's pair out of LDS, and stores 8 fp16 values with one 128-bit write
-// to the row that order[] names.  Every store instruction of a wave therefore writes whole
-// 256-byte rows.
+// chunks (32 rows at head_dim 128) of one width's segment.  Each lane owns one span of 32
+// consecutive values per round (two rounds per tile): it reads its span's packed codes
+// (8 / 16 / 32 bytes, contiguous with its neighbours') and its group's (scale, zero) pair
+// straight from the card, decodes 32 values, and writes the 64 bytes into LDS.  The tile is
+// then read back row-major (chunk index XOR-swizzled so that both directions touch every
+// bank once per pass) and stored with 128-bit writes to the rows that order[] names: every
+// store instruction of a wave writes whole 256-byte rows.
 //
 // The card is untrusted input: the kernel rebuilds the section offsets from the header's
 // class counts, checks them against the buffer size and the caller's shape, and bounds
@@ -59,110 +60,162 @@ __device__ inline bool load_geometry(const UnpackArgs& a, CardGeom& g) {
   return ok;
 }
 
-// Row id (plane * T + token) of row `lane` of the tile starting at segment row r0, or
-// 0xFFFFFFFF for rows past the segment's end and for corrupt order[] entries.
-__device__ inline uint32_t tile_row_lookup(const CardGeom& g, const uint32_t* __restrict__ order, int c, uint32_t r0,
-                                           uint32_t n_rows, uint32_t lane, uint32_t tile_rows, uint32_t& bad) {
-  uint32_t rowid = 0xFFFFFFFFu;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(1))) u32x4 global_u32x4;
+
+// LDS position (in 16-byte units) of output chunk q of a tile.
+__device__ inline uint32_t swizzle(uint32_t q) { return q ^ ((q >> 3) & 3u); }
+
+// Address of the output row that row `lane` of the tile starting at segment row r0 goes to;
+// 0 for rows past the segment's end and for corrupt order[] entries.
+__device__ inline uint64_t tile_row_address(const UnpackArgs& a, const CardGeom& g, int c, uint32_t r0, uint32_t n_rows,
+                                            uint32_t lane, uint32_t tile_rows, uint32_t& bad) {
+  uint64_t addr = 0;
   const uint32_t r = r0 + lane;
   if (lane < tile_rows && r < n_rows) {
     const uint32_t n = g.n[c];
     const uint32_t p = r / n;
     const uint32_t j = r - p * n;
-    const uint32_t t = order[g.base[c] + j];
-    if (t < g.tokens) rowid = p * g.tokens + t; else bad = 1;
+    const uint32_t t = reinterpret_cast<const uint32_t*>(a.card + g.off_order)[g.base[c] + j];
+    const uint32_t lh = g.planes >> 1;
+    const uint32_t row_bytes = g.head_dim * 2u;
+    if (t < g.tokens) {
+      addr = (p < lh) ? reinterpret_cast<uint64_t>(a.k_out) + ((uint64_t)p * g.tokens + t) * row_bytes
+                      : reinterpret_cast<uint64_t>(a.v_out) + ((uint64_t)(p - lh) * g.tokens + t) * row_bytes;
+    } else {
+      bad = 1;
+    }
   }
-  return rowid;
+  return addr;
 }
 
-__device__ inline uint8_t* row_address(const UnpackArgs& a, const CardGeom& g, uint32_t rowid, uint32_t row_bytes) {
-  const uint64_t k_bytes = (uint64_t)g.k_rows * row_bytes;
-  const uint64_t off = (uint64_t)rowid * row_bytes;
-  const uint64_t addr = (rowid < g.k_rows) ? reinterpret_cast<uint64_t>(a.k_out) + off
-                                           : reinterpret_cast<uint64_t>(a.v_out) + (off - k_bytes);
-  return reinterpret_cast<uint8_t*>(addr);
+// Stores the tile: chunk 64 k + lane goes to its row, rows without an address are skipped.
+__device__ inline void store_tile(uint64_t my_row_addr, uint32_t lane, uint32_t lpr_shift, const u32x4 (&data)[kTileIters]) {
+  const uint32_t in_row = (lane & ((1u << lpr_shift) - 1u)) * 16u;
+#pragma unroll
+  for (int k = 0; k < kTileIters; ++k) {
+    const uint32_t src_lane = (k * kWaveSize + lane) >> lpr_shift;
+    const uint32_t lo = __shfl((uint32_t)my_row_addr, src_lane, kWaveSize);
+    const uint32_t hi = __shfl((uint32_t)(my_row_addr >> 32), src_lane, kWaveSize);
+    const uint64_t row = ((uint64_t)hi << 32) | lo;
+    if (row != 0) *reinterpret_cast<global_u32x4*>(row + in_row) = data[k];
+  }
 }
-
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 // decode = fp16( fma(code, scale, zero) ): an fp32 fma rounded to fp32, then rounded to
 // fp16, both to nearest even.  The two steps are kept apart on purpose: the fused
 // fma-and-convert instruction rounds the exact sum once, straight to fp16, which gives a
 // different value whenever the fp32 result lands on an fp16 midpoint.
-__device__ inline uint32_t decode_pair(uint32_t q0, uint32_t q1, float s, float z) {
-  float a = __builtin_fmaf((float)q0, s, z);
-  float b = __builtin_fmaf((float)q1, s, z);
+__device__ inline uint32_t decode_pair(float q0, float q1, float s, float z) {
+  float a = __builtin_fmaf(q0, s, z);
+  float b = __builtin_fmaf(q1, s, z);
   asm("" : "+v"(a));
   asm("" : "+v"(b));
   const f32x2 v = {a, b};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
 }
 
+// float(byte j of w): one instruction
+__device__ inline float byte_to_float(uint32_t w, int j) {
+  float r;
+  switch (j) {
+    case 0: asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(r) : "v"(w)); break;
+    case 1: asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(r) : "v"(w)); break;
+    case 2: asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(r) : "v"(w)); break;
+    default: asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(r) : "v"(w)); break;
+  }
+  return r;
+}
+
+// The 32 values of one span: W dwords of codes in, 16 dwords of packed fp16 out.
+template <int W>
+__device__ inline void decode_span(const uint32_t (&cw)[W], float s, float z, uint32_t (&out)[16]) {
+  if (W == 8) {
+#pragma unroll
+    for (int d = 0; d < 8; ++d) {          // dword d: codes 4d .. 4d+3, one per byte
+      out[2 * d] = decode_pair(byte_to_float(cw[d], 0), byte_to_float(cw[d], 1), s, z);
+      out[2 * d + 1] = decode_pair(byte_to_float(cw[d], 2), byte_to_float(cw[d], 3), s, z);
+    }
+  } else if (W == 4) {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {          // dword d: codes 8d .. 8d+7; byte j holds codes 2j (low), 2j+1 (high)
+      const uint32_t even = cw[d] & 0x0F0F0F0Fu, odd = (cw[d] >> 4) & 0x0F0F0F0Fu;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) out[4 * d + j] = decode_pair(byte_to_float(even, j), byte_to_float(odd, j), s, z);
+    }
+  } else {
+#pragma unroll
+    for (int d = 0; d < 2; ++d) {          // dword d: codes 16d .. 16d+15; byte j holds codes 4j .. 4j+3
+      const uint32_t c0 = cw[d] & 0x03030303u, c1 = (cw[d] >> 2) & 0x03030303u, c2 = (cw[d] >> 4) & 0x03030303u,
+                     c3 = (cw[d] >> 6) & 0x03030303u;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        out[8 * d + 2 * j] = decode_pair(byte_to_float(c0, j), byte_to_float(c1, j), s, z);
+        out[8 * d + 2 * j + 1] = decode_pair(byte_to_float(c2, j), byte_to_float(c3, j), s, z);
+      }
+    }
+  }
+}
+
 template <int W, int G>
 __device__ inline void unpack_tile(const UnpackArgs& a, const CardGeom& g, int c, uint32_t r0, uint32_t n_rows,
-                                   uint32_t lane, uint8_t* lds_codes, uint32_t* lds_meta, uint32_t& bad) {
-  constexpr int GL = G / 8;
-  constexpr uint32_t MASK = (1u << W) - 1u;
+                                   uint32_t lane, u32x4* lds, uint32_t& bad) {
+  constexpr int GS = G / 32;                     // spans (lanes) per group
   const uint32_t lpr_shift = g.lpr_shift;
   const uint32_t tile_rows = kTileChunks >> lpr_shift;
-  const uint32_t row_bytes = g.head_dim * 2u;
-  const uint32_t* order = reinterpret_cast<const uint32_t*>(a.card + g.off_order);
-  const uint32_t my_row = tile_row_lookup(g, order, c, r0, n_rows, lane, tile_rows, bad);
+  const uint32_t spr_shift = lpr_shift - 2;      // log2(spans per row)
+  const uint64_t my_row = tile_row_address(a, g, c, r0, n_rows, lane, tile_rows, bad);
 
-  // stage the tile's codes and pairs
-  {
-    const uint64_t seg_bytes = (uint64_t)n_rows * (g.head_dim * W / 8);
-    const uint64_t tile_off = (uint64_t)r0 * (g.head_dim * W / 8);
-    const uint8_t* src = a.card + g.off_codes[c];
+  const uint8_t* codes_seg = a.card + g.off_codes[c];
+  const uint32_t* meta_seg = reinterpret_cast<const uint32_t*>(a.card + g.off_meta[c]);
+  const uint64_t span0 = (uint64_t)r0 << spr_shift;
+  const uint64_t seg_spans = (uint64_t)n_rows << spr_shift;
+
+  // both rounds' codes and pairs first, so the loads overlap
+  uint32_t cw[2][W];
+  uint32_t pair[2];
 #pragma unroll
-    for (int m = 0; m < W / 2; ++m) {
-      const uint32_t idx = m * kWaveSize + lane;
-      const uint64_t off = tile_off + (uint64_t)idx * 16u;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (off < seg_bytes) v = *reinterpret_cast<const uint4*>(src + off);
-      reinterpret_cast<uint4*>(lds_codes)[idx] = v;
-    }
-    constexpr int kDwords = kTileChunks / GL;
-    const uint64_t seg_dwords = (uint64_t)n_rows * (g.head_dim / G);
-    const uint64_t tile_dw = (uint64_t)r0 * (g.head_dim / G);
-    const uint32_t* msrc = reinterpret_cast<const uint32_t*>(a.card + g.off_meta[c]);
+  for (int round = 0; round < 2; ++round) {
+    const uint64_t gsp = span0 + round * kWaveSize + lane;
 #pragma unroll
-    for (int m = 0; m < (kDwords + kWaveSize - 1) / kWaveSize; ++m) {
-      const uint32_t idx = m * kWaveSize + lane;
-      if (idx < (uint32_t)kDwords) lds_meta[idx] = (tile_dw + idx < seg_dwords) ? msrc[tile_dw + idx] : 0u;
+    for (int i = 0; i < W; ++i) cw[round][i] = 0;
+    pair[round] = 0;
+    if (gsp < seg_spans) {
+      const uint8_t* src = codes_seg + gsp * (4u * W);
+      if (W == 2) {
+        const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src));
+        cw[round][0] = t.x; cw[round][1] = t.y;
+      } else {
+#pragma unroll
+        for (int h = 0; h < W / 4; ++h) {
+          const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + 16 * h));
+          cw[round][4 * h] = t.x; cw[round][4 * h + 1] = t.y; cw[round][4 * h + 2] = t.z; cw[round][4 * h + 3] = t.w;
+        }
+      }
+      pair[round] = __builtin_nontemporal_load(meta_seg + gsp / GS);
     }
   }
-  __builtin_amdgcn_wave_barrier();
 
+  const uint32_t x = (lane >> 1) & 3u;           // swizzle term of this lane's spans
 #pragma unroll
-  for (int k = 0; k < kTileIters; ++k) {
-    const uint32_t q = k * kWaveSize + lane;
-    const uint32_t rowid = __shfl(my_row, q >> lpr_shift, kWaveSize);
-    const uint32_t pair = lds_meta[q / GL];
-    const float s = half_bits_to_float(pair & 0xFFFFu);
-    const float z = half_bits_to_float(pair >> 16);
-    uint32_t lo = 0, hi = 0;      // the chunk's 8 codes, W bits each, little end first
-    if (W == 2) lo = reinterpret_cast<const uint16_t*>(lds_codes)[q];
-    if (W == 4) lo = reinterpret_cast<const uint32_t*>(lds_codes)[q];
-    if (W == 8) { const uint2 t = reinterpret_cast<const uint2*>(lds_codes)[q]; lo = t.x; hi = t.y; }
-    uint32_t code[8];
+  for (int round = 0; round < 2; ++round) {
+    const uint32_t sp = round * kWaveSize + lane;
+    const float s = half_bits_to_float(pair[round] & 0xFFFFu);
+    const float z = half_bits_to_float(pair[round] >> 16);
+    uint32_t out[16];
+    decode_span<W>(cw[round], s, z, out);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      if (W == 8) code[i] = ((i < 4 ? lo : hi) >> (8 * (i & 3))) & MASK;
-      else code[i] = (lo >> (W * i)) & MASK;
-    }
-    uint4 out;
-    out.x = decode_pair(code[0], code[1], s, z);
-    out.y = decode_pair(code[2], code[3], s, z);
-    out.z = decode_pair(code[4], code[5], s, z);
-    out.w = decode_pair(code[6], code[7], s, z);
-    if (rowid != 0xFFFFFFFFu) {
-      uint8_t* dst = row_address(a, g, rowid, row_bytes) + (q & ((1u << lpr_shift) - 1u)) * 16u;
-      *reinterpret_cast<uint4*>(dst) = out;
-    }
+    for (int j = 0; j < 4; ++j) lds[4 * sp + (j ^ x)] = (u32x4){out[4 * j], out[4 * j + 1], out[4 * j + 2], out[4 * j + 3]};
   }
-  __builtin_amdgcn_wave_barrier();
+
+  u32x4 data[kTileIters];
+  const uint32_t rslot = swizzle(lane);
+#pragma unroll
+  for (int k = 0; k < kTileIters; ++k) data[k] = lds[k * kWaveSize + rslot];
+  store_tile(my_row, lane, lpr_shift, data);
 }
 
 __device__ inline void copy_tile(const UnpackArgs& a, const CardGeom& g, uint32_t r0, uint32_t n_rows, uint32_t lane,
@@ -170,26 +223,17 @@ __device__ inline void copy_tile(const UnpackArgs& a, const CardGeom& g, uint32_
   const uint32_t lpr_shift = g.lpr_shift;
   const uint32_t tile_rows = kTileChunks >> lpr_shift;
   const uint32_t row_bytes = g.head_dim * 2u;
-  const uint32_t* order = reinterpret_cast<const uint32_t*>(a.card + g.off_order);
-  const uint32_t my_row = tile_row_lookup(g, order, 3, r0, n_rows, lane, tile_rows, bad);
+  const uint64_t my_row = tile_row_address(a, g, 3, r0, n_rows, lane, tile_rows, bad);
   const uint8_t* src = a.card + g.off_fp16 + (uint64_t)r0 * row_bytes;
   const uint64_t seg_left = ((uint64_t)n_rows - r0) * row_bytes;   // bytes from the tile start to the segment end
-  uint4 data[kTileIters];
+  u32x4 data[kTileIters];
 #pragma unroll
   for (int k = 0; k < kTileIters; ++k) {
-    const uint32_t q = k * kWaveSize + lane;
-    data[k] = make_uint4(0, 0, 0, 0);
-    if ((uint64_t)q * 16u < seg_left) data[k] = *reinterpret_cast<const uint4*>(src + (uint64_t)q * 16u);
+    const uint64_t off = (uint64_t)(k * kWaveSize + lane) * 16u;
+    data[k] = (u32x4)(0u);
+    if (off < seg_left) data[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + off));
   }
-#pragma unroll
-  for (int k = 0; k < kTileIters; ++k) {
-    const uint32_t q = k * kWaveSize + lane;
-    const uint32_t rowid = __shfl(my_row, q >> lpr_shift, kWaveSize);
-    if (rowid != 0xFFFFFFFFu) {
-      uint8_t* dst = row_address(a, g, rowid, row_bytes) + (q & ((1u << lpr_shift) - 1u)) * 16u;
-      *reinterpret_cast<uint4*>(dst) = data[k];
-    }
-  }
+  store_tile(my_row, lane, lpr_shift, data);
 }
 
 // Writes the header verdict; runs before the unpacking grid on the same stream.
@@ -201,8 +245,7 @@ __global__ void unpack_status_kernel(UnpackArgs a) {
 
 template <int G>
 __global__ __launch_bounds__(kBlockThreads) void unpack_kernel(UnpackArgs a) {
-  __shared__ __attribute__((aligned(16))) uint8_t lds_codes[kWavesPerBlock][kTileChunks * 8];
-  __shared__ uint32_t lds_meta[kWavesPerBlock][kTileChunks / 4];
+  __shared__ u32x4 lds[kWavesPerBlock][kTileChunks];
   CardGeom g;
   if (!load_geometry(a, g)) return;          // uniform over the grid: every wave leaves
   const uint32_t lane = threadIdx.x & 63u;
@@ -210,8 +253,7 @@ __global__ __launch_bounds__(kBlockThreads) void unpack_kernel(UnpackArgs a) {
   const uint32_t gw = blockIdx.x * kWavesPerBlock + wave;
   const uint32_t n_waves = gridDim.x * kWavesPerBlock;
   const uint32_t tile_rows = kTileChunks >> g.lpr_shift;
-  uint8_t* my_codes = lds_codes[wave];
-  uint32_t* my_meta = lds_meta[wave];
+  u32x4* my_lds = lds[wave];
 
   uint32_t bad = 0;
   uint32_t cum = 0;
@@ -223,9 +265,9 @@ __global__ __launch_bounds__(kBlockThreads) void unpack_kernel(UnpackArgs a) {
     const uint32_t first = (gw + n_waves - cum) % n_waves;
     for (uint32_t i = first; i < tiles; i += n_waves) {
       const uint32_t r0 = i * tile_rows;
-      if (c == 0) unpack_tile<2, G>(a, g, 0, r0, n_rows, lane, my_codes, my_meta, bad);
-      if (c == 1) unpack_tile<4, G>(a, g, 1, r0, n_rows, lane, my_codes, my_meta, bad);
-      if (c == 2) unpack_tile<8, G>(a, g, 2, r0, n_rows, lane, my_codes, my_meta, bad);
+      if (c == 0) unpack_tile<2, G>(a, g, 0, r0, n_rows, lane, my_lds, bad);
+      if (c == 1) unpack_tile<4, G>(a, g, 1, r0, n_rows, lane, my_lds, bad);
+      if (c == 2) unpack_tile<8, G>(a, g, 2, r0, n_rows, lane, my_lds, bad);
       if (c == 3) copy_tile(a, g, r0, n_rows, lane, bad);
     }
     cum = (cum + tiles) % n_waves;
