@@ -28,21 +28,12 @@ __device__ inline uint32_t rank_key(float score) {
   return ~up;
 }
 
-__device__ inline uint32_t wave_inclusive_scan(uint32_t v, uint32_t lane) {
-#pragma unroll
-  for (int d = 1; d < kWaveSize; d <<= 1) {
-    const uint32_t o = __shfl_up(v, d, kWaveSize);
-    if (lane >= (uint32_t)d) v += o;
-  }
-  return v;
-}
-
 // One wave finds the bucket that holds rank `left` in a 256-bucket histogram: the first d
 // whose cumulative count exceeds `left`.  Returns d and lowers `left` by the count before it.
 // The histogram's total must exceed `left`.
 __device__ inline uint32_t find_bucket(const uint32_t* hist, uint32_t lane, uint32_t& left) {
   const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
-  const uint32_t inc = wave_inclusive_scan(h0 + h1 + h2 + h3, lane);
+  const uint32_t inc = wave_inclusive_scan(h0 + h1 + h2 + h3);
   const uint64_t over = __builtin_amdgcn_ballot_w64(inc > left);
   const uint32_t owner = (uint32_t)__builtin_ctzll(over | (1ull << 63));
   const uint32_t before = __shfl(inc - (h0 + h1 + h2 + h3), owner, kWaveSize);
@@ -58,7 +49,8 @@ __device__ inline uint32_t find_bucket(const uint32_t* hist, uint32_t lane, uint
 // T <= KPT * kThreads); KPT == 0: any T, keys re-read from the scores on every sweep.
 template <int KPT>
 __global__ __launch_bounds__(kThreads) void assign_kernel(const float* __restrict__ scores, uint32_t T, uint32_t cut0,
-                                                          uint32_t cut1, uint32_t cut2, uint8_t* __restrict__ bits) {
+                                                          uint32_t cut1, uint32_t cut2, uint8_t* __restrict__ bits,
+                                                          bool aligned) {
   __shared__ uint32_t wide[256 * kCopies];   // first pass: bucket d, copy c at [d * 32 + c]
   __shared__ uint32_t hist[3][256];
   __shared__ uint32_t sel_prefix[3];         // key bits fixed so far
@@ -74,8 +66,16 @@ __global__ __launch_bounds__(kThreads) void assign_kernel(const float* __restric
   const uint32_t t1 = min(t0 + per, T);
   uint32_t keys[KPT > 0 ? KPT : 1];
   if (KPT > 0) {
+    if (aligned && t0 + KPT <= T) {      // 128-bit loads
 #pragma unroll
-    for (int i = 0; i < KPT; ++i) keys[i] = (t0 + i < t1) ? rank_key(scores[t0 + i]) : 0u;
+      for (int i = 0; i < KPT; i += 4) {
+        const float4 f = *reinterpret_cast<const float4*>(scores + t0 + i);
+        keys[i] = rank_key(f.x); keys[i + 1] = rank_key(f.y); keys[i + 2] = rank_key(f.z); keys[i + 3] = rank_key(f.w);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < KPT; ++i) keys[i] = (t0 + i < t1) ? rank_key(scores[t0 + i]) : 0u;
+    }
   }
   // visits every owned token's key
   auto for_each_key = [&](auto&& f) {
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kThreads) void assign_kernel(const float* __restric
   uint32_t run[3];
 #pragma unroll
   for (int c = 0; c < 3; ++c) {
-    const uint32_t inc = wave_inclusive_scan(eq[c], lane);
+    const uint32_t inc = wave_inclusive_scan(eq[c]);
     run[c] = inc - eq[c];
     if (lane == 63) wave_tot[c][wave] = inc;
   }
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(kThreads) void assign_kernel(const float* __restric
     for (uint32_t w = 0; w < wave; ++w) before += wave_tot[c][w];
     run[c] += before;
   }
-  for_each_key([&](uint32_t key, uint32_t t) {
+  auto width_of = [&](uint32_t key) -> uint32_t {
     bool before[3];
 #pragma unroll
     for (int c = 0; c < 3; ++c) {
@@ -167,8 +167,19 @@ __global__ __launch_bounds__(kThreads) void assign_kernel(const float* __restric
       before[c] = key < keyc[c] || (is_eq && run[c] < quota[c]);
       run[c] += is_eq;
     }
-    bits[t] = before[0] ? 16 : before[1] ? 8 : before[2] ? 4 : 2;
-  });
+    return before[0] ? 16u : before[1] ? 8u : before[2] ? 4u : 2u;
+  };
+  if (KPT > 0 && aligned && t0 + KPT <= T) {       // 8 widths per 64-bit store
+#pragma unroll
+    for (int i = 0; i < KPT; i += 8) {
+      uint64_t w = 0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) w |= (uint64_t)width_of(keys[i + j]) << (8 * j);
+      *reinterpret_cast<uint64_t*>(bits + t0 + i) = w;
+    }
+  } else {
+    for_each_key([&](uint32_t key, uint32_t t) { bits[t] = (uint8_t)width_of(key); });
+  }
 }
 
 __global__ __launch_bounds__(256) void count_kernel(const uint8_t* __restrict__ bits, uint64_t T,
@@ -197,12 +208,13 @@ __global__ void zero4_kernel(unsigned long long* p) {
 hipError_t launch_assign(const float* scores, uint32_t tokens, const uint32_t cuts[3], uint8_t* bits,
                          hipStream_t stream) {
   const dim3 grid(1), block(kThreads);
+  const bool aligned = reinterpret_cast<uintptr_t>(scores) % 16 == 0 && reinterpret_cast<uintptr_t>(bits) % 8 == 0;
   if (tokens <= 8u * kThreads)
-    hipLaunchKernelGGL(assign_kernel<8>, grid, block, 0, stream, scores, tokens, cuts[0], cuts[1], cuts[2], bits);
+    hipLaunchKernelGGL(assign_kernel<8>, grid, block, 0, stream, scores, tokens, cuts[0], cuts[1], cuts[2], bits, aligned);
   else if (tokens <= 32u * kThreads)
-    hipLaunchKernelGGL(assign_kernel<32>, grid, block, 0, stream, scores, tokens, cuts[0], cuts[1], cuts[2], bits);
+    hipLaunchKernelGGL(assign_kernel<32>, grid, block, 0, stream, scores, tokens, cuts[0], cuts[1], cuts[2], bits, aligned);
   else
-    hipLaunchKernelGGL(assign_kernel<0>, grid, block, 0, stream, scores, tokens, cuts[0], cuts[1], cuts[2], bits);
+    hipLaunchKernelGGL(assign_kernel<0>, grid, block, 0, stream, scores, tokens, cuts[0], cuts[1], cuts[2], bits, aligned);
   return hipGetLastError();
 }
 

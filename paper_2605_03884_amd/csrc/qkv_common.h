@@ -82,6 +82,19 @@ inline int check_counts(int64_t T, const int64_t counts[4]) {
   return sum == T ? QKV_OK : QKV_ERR_COUNTS;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave, in data-parallel-primitive moves only:
+// shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of row 0 / 2 is added
+// to row 1 / 3 and the last lane of row 1 to rows 2 and 3.
+__device__ inline uint32_t wave_inclusive_scan(uint32_t v) {
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, true);    // row_shr:1
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, true);    // row_shr:2
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, true);    // row_shr:4
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, true);    // row_shr:8
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);   // row_bcast:15 -> rows 1, 3
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);   // row_bcast:31 -> rows 2, 3
+  return v;
+}
+
 // Number of persistent workgroups for a streaming kernel with `tiles` wave-tiles of work.
 int persistent_blocks(uint64_t tiles);
 

@@ -115,6 +115,41 @@ def test_shapes_mixed_widths(L, H, T, D, G):
     check_round_trip(desc, K, V, bits, "mixed L%d H%d T%d D%d G%d" % (L, H, T, D, G))
 
 
+@pytest.mark.parametrize("T", [8191, 8192, 8193, 20000, 40003])
+def test_long_sequences_cross_compaction_chunks(T):
+    # the compaction kernel walks the tokens in chunks of 8192
+    L, H, D, G = 1, 1, 64, 32
+    desc, K, V = make_problem(L, H, T, D, G, seed=500 + T % 97)
+    rng = np.random.default_rng(T)
+    bits = rng.choice(np.array([2, 4, 8, 16], dtype=np.uint8), size=T, p=(0.6, 0.2, 0.15, 0.05))
+    bits[T // 3: T // 3 + 3000] = 8          # a long run of one class across thread boundaries
+    check_round_trip(desc, K, V, bits, "long T=%d" % T)
+
+
+def test_unaligned_bits_and_scores_pointers():
+    L, H, T, D, G = 1, 2, 1003, 128, 32
+    desc, K, V = make_problem(L, H, T, D, G, seed=91)
+    scores = qkv_synth.make_scores(T, 92)
+    want_bits, want_counts = ref.assign_bits(scores.numpy(), 4.0)
+    for shift in (1, 3, 4):
+        say("pointers shifted by %d elements" % shift)
+        sbuf = torch.zeros(T + 8, dtype=torch.float32, device=DEV)
+        sbuf[shift:shift + T] = scores.to(DEV)
+        bbuf = torch.zeros(T + 16, dtype=torch.uint8, device=DEV)
+        bits_view = bbuf[shift:shift + T]
+        _, counts = qkv.assign_bits(sbuf[shift:shift + T], 4.0, bits=bits_view)
+        torch.cuda.synchronize()
+        assert counts == want_counts.tolist()
+        assert np.array_equal(bits_view.cpu().numpy(), want_bits)
+        assert int(bbuf[:shift].sum()) == 0 and int(bbuf[shift + T:].sum()) == 0
+        n = qkv.card_bytes(desc, counts)
+        card = torch.zeros(n, dtype=torch.uint8, device=DEV)
+        qkv.quantize_pack(desc, torch.from_numpy(K).to(DEV), torch.from_numpy(V).to(DEV), bits_view, counts, card)
+        torch.cuda.synchronize()
+        want = ref.quantize_pack(ref_desc(desc), K, V, want_bits, want_counts)
+        assert first_diff(card.cpu().numpy(), want) is None
+
+
 @pytest.mark.parametrize("width", [2, 4, 8, 16])
 @pytest.mark.parametrize("G", [32, 64])
 def test_uniform_cards(width, G):
