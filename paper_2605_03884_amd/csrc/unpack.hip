@@ -101,7 +101,7 @@ __device__ inline void store_tile(uint64_t my_row_addr, uint32_t lane, uint32_t 
     const uint32_t lo = __shfl((uint32_t)my_row_addr, src_lane, kWaveSize);
     const uint32_t hi = __shfl((uint32_t)(my_row_addr >> 32), src_lane, kWaveSize);
     const uint64_t row = ((uint64_t)hi << 32) | lo;
-    if (row != 0) *reinterpret_cast<global_u32x4*>(row + in_row) = data[k];
+    if (row != 0) __builtin_nontemporal_store(data[k], reinterpret_cast<global_u32x4*>(row + in_row));
   }
 }
 
@@ -255,16 +255,18 @@ __global__ __launch_bounds__(kBlockThreads) void unpack_kernel(UnpackArgs a) {
   const uint32_t tile_rows = kTileChunks >> g.lpr_shift;
   u32x4* my_lds = lds[wave];
 
+  // The card is walked from its end to its start: when it was written a moment ago, its
+  // tail is the part most likely still held by the memory-side cache.
   uint32_t bad = 0;
   uint32_t cum = 0;
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
+  for (int c = 3; c >= 0; --c) {
     const uint32_t n_rows = g.planes * g.n[c];
     if (n_rows == 0) continue;
     const uint32_t tiles = (n_rows + tile_rows - 1) / tile_rows;
     const uint32_t first = (gw + n_waves - cum) % n_waves;
     for (uint32_t i = first; i < tiles; i += n_waves) {
-      const uint32_t r0 = i * tile_rows;
+      const uint32_t r0 = (tiles - 1 - i) * tile_rows;
       if (c == 0) unpack_tile<2, G>(a, g, 0, r0, n_rows, lane, my_lds, bad);
       if (c == 1) unpack_tile<4, G>(a, g, 1, r0, n_rows, lane, my_lds, bad);
       if (c == 2) unpack_tile<8, G>(a, g, 2, r0, n_rows, lane, my_lds, bad);
