@@ -186,16 +186,16 @@ __device__ inline void unpack_tile(const UnpackArgs& a, const CardGeom& g, int c
     if (gsp < seg_spans) {
       const uint8_t* src = codes_seg + gsp * (4u * W);
       if (W == 2) {
-        const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src));
+        const u32x2 t = *reinterpret_cast<const u32x2*>(src);
         cw[round][0] = t.x; cw[round][1] = t.y;
       } else {
 #pragma unroll
         for (int h = 0; h < W / 4; ++h) {
-          const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + 16 * h));
+          const u32x4 t = *reinterpret_cast<const u32x4*>(src + 16 * h);
           cw[round][4 * h] = t.x; cw[round][4 * h + 1] = t.y; cw[round][4 * h + 2] = t.z; cw[round][4 * h + 3] = t.w;
         }
       }
-      pair[round] = __builtin_nontemporal_load(meta_seg + gsp / GS);
+      pair[round] = meta_seg[gsp / GS];
     }
   }
 
@@ -231,7 +231,7 @@ __device__ inline void copy_tile(const UnpackArgs& a, const CardGeom& g, uint32_
   for (int k = 0; k < kTileIters; ++k) {
     const uint64_t off = (uint64_t)(k * kWaveSize + lane) * 16u;
     data[k] = (u32x4)(0u);
-    if (off < seg_left) data[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + off));
+    if (off < seg_left) data[k] = *reinterpret_cast<const u32x4*>(src + off);
   }
   store_tile(my_row, lane, lpr_shift, data);
 }
