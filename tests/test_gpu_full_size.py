@@ -1,0 +1,151 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+8K and 1K workloads: the whole card and the whole dequantized cache against the oracle.
+32K four-hop workload: the GPU runs all layers and heads; the oracle runs the same four hops
+on sampled (layer, head) pairs only (planes are independent given the widths), and the
+sampled planes' card rows and dequantized rows are compared byte for byte at every hop,
+together with the complete bits / slot / order tables and header.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_03884_amd as qkv
+import qkv_synth
+from oracle import ref
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def widths_for(cfg, dev):
+    kind = cfg["bits"][0]
+    T = cfg["tokens"]
+    if kind == "budget":
+        scores = qkv_synth.make_scores(T, cfg["bits"][1], dev)
+        bits, counts = qkv.assign_bits(scores, cfg["bits"][2])
+        want_bits, want_counts = ref.assign_bits(qkv_synth.make_scores(T, cfg["bits"][1]).numpy(), cfg["bits"][2])
+        assert counts == want_counts.tolist()
+        assert np.array_equal(bits.cpu().numpy(), want_bits)
+        return bits, counts
+    if kind == "constant":
+        bits = qkv_synth.make_bits_constant(T, cfg["bits"][1], dev)
+        return bits, qkv.count_bits(bits)
+    raise ValueError(kind)
+
+
+@pytest.mark.parametrize("name", ["llama8b_1k_b5", "llama8b_1k_b4", "llama8b_8k_b3", "llama8b_8k_u4_g64",
+                                  "llama8b_8k_u2_g64"])
+def test_benchmark_workload_whole_card_and_cache(name):
+    cfg = qkv_synth.CONFIGS[name]
+    L, H, T, D, G = cfg["layers"], cfg["kv_heads"], cfg["tokens"], cfg["head_dim"], cfg["group_size"]
+    say("%s: generating" % name)
+    K, V = qkv_synth.make_kv(L, H, T, D, cfg["data_seed"], cfg["kind"], device=DEV)
+    bits, counts = widths_for(cfg, DEV)
+    desc = qkv.Desc.make(L, H, T, D, G, model_id=8, sender_id=1, position_offset=5)
+    n = qkv.card_bytes(desc, counts)
+    card = torch.full((n + 256,), 0x5A, dtype=torch.uint8, device=DEV)
+    say("%s: pack" % name)
+    qkv.quantize_pack(desc, K, V, bits, counts, card)
+    K_out = torch.empty_like(K)
+    V_out = torch.empty_like(V)
+    status = torch.ones(1, dtype=torch.int32, device=DEV)
+    say("%s: unpack" % name)
+    qkv.unpack_dequant(card, desc, K_out, V_out, status=status, card_nbytes=n)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    assert int((card[n:] != 0x5A).sum()) == 0, "bytes behind the card were written"
+
+    say("%s: oracle" % name)
+    rd = ref.make_desc(L, H, T, D, G, 8, 1, 5)
+    bits_h = bits.cpu().numpy()
+    want = ref.quantize_pack(rd, K.cpu().numpy(), V.cpu().numpy(), bits_h, counts)
+    got = card[:n].cpu().numpy()
+    diff = np.flatnonzero(got != want)
+    assert diff.size == 0, "card differs at %d bytes, first offset %d" % (diff.size, int(diff[0]))
+    wk, wv = ref.unpack_dequant(want, rd)
+    assert np.array_equal(K_out.cpu().numpy().view(np.uint16), wk)
+    assert np.array_equal(V_out.cpu().numpy().view(np.uint16), wv)
+    # the decoded cache stays within scale/2 (+ output rounding) of the input for quantized tokens: spot check
+    t = int(np.flatnonzero(bits_h != 16)[0])
+    x = K[0, 0, t].float().cpu().numpy()
+    y = K_out[0, 0, t].float().cpu().numpy()
+    assert np.all(np.abs(x - y) <= (x.reshape(-1, G).max(1) - x.reshape(-1, G).min(1)).repeat(G) / ((1 << int(bits_h[t])) - 1) * 0.51 + 0.05)
+
+
+def plane_rows(card, off, counts, P, p, D, G):
+    """The byte ranges of plane p inside every section of a card (dict name -> array)."""
+    out = {}
+    for c, w in enumerate((2, 4, 8)):
+        rb = D * w // 8
+        out["codes%d" % w] = card[off["codes%d" % w] + p * counts[c] * rb: off["codes%d" % w] + (p + 1) * counts[c] * rb]
+        mb = (D // G) * 4
+        out["meta%d" % w] = card[off["meta%d" % w] + p * counts[c] * mb: off["meta%d" % w] + (p + 1) * counts[c] * mb]
+    out["fp16"] = card[off["fp16"] + p * counts[3] * D * 2: off["fp16"] + (p + 1) * counts[3] * D * 2]
+    return out
+
+
+def test_32k_four_hops_sampled_planes():
+    cfg = qkv_synth.CONFIGS["llama8b_32k_hops"]
+    L, H, T, D, G = cfg["layers"], cfg["kv_heads"], cfg["tokens"], cfg["head_dim"], cfg["group_size"]
+    seeds, budgets = cfg["bits"][1], cfg["bits"][2]
+    sampled = [(0, 0), (7, 3), (19, 6), (31, 7)]
+    say("32K: generating")
+    K, V = qkv_synth.make_kv(L, H, T, D, cfg["data_seed"], cfg["kind"], device=DEV)
+    # the oracle's own chain on the sampled planes: host copies of the seeded input, never of a GPU result
+    ok = {lh: K[lh[0], lh[1]].cpu().numpy().reshape(1, 1, T, D).copy() for lh in sampled}
+    ov = {lh: V[lh[0], lh[1]].cpu().numpy().reshape(1, 1, T, D).copy() for lh in sampled}
+    desc = qkv.Desc.make(L, H, T, D, G, model_id=8, sender_id=2)
+    K_out = torch.empty_like(K)
+    V_out = torch.empty_like(V)
+    P = 2 * L * H
+    for hop, (seed, budget) in enumerate(zip(seeds, budgets)):
+        say("32K hop %d budget %.0f" % (hop + 1, budget))
+        scores = qkv_synth.make_scores(T, seed, DEV)
+        bits, counts = qkv.assign_bits(scores, budget)
+        want_bits, want_counts = ref.assign_bits(qkv_synth.make_scores(T, seed).numpy(), budget)
+        assert counts == want_counts.tolist() and np.array_equal(bits.cpu().numpy(), want_bits)
+        n = qkv.card_bytes(desc, counts)
+        card = torch.empty(n, dtype=torch.uint8, device=DEV)
+        qkv.quantize_pack(desc, K, V, bits, counts, card)
+        status = torch.ones(1, dtype=torch.int32, device=DEV)
+        qkv.unpack_dequant(card, desc, K_out, V_out, status=status)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        d2, c2, avg, st = qkv.card_peek(card)
+        assert st == 0 and c2 == counts and d2.tokens == T
+        full_off = ref.card_offsets(ref.make_desc(L, H, T, D, G), counts)
+        assert n == full_off["total"]
+        head = card[:full_off["codes2"]].cpu().numpy()          # header and the three tables
+        slot, order, _ = ref.compact(want_bits)
+        assert np.array_equal(head[full_off["bits"]:full_off["bits"] + T], want_bits)
+        assert np.array_equal(head[full_off["slot"]:full_off["slot"] + 4 * T].view(np.uint32), slot)
+        assert np.array_equal(head[full_off["order"]:full_off["order"] + 4 * T].view(np.uint32), order)
+        for (l, h) in sampled:
+            sd = ref.make_desc(1, 1, T, D, G, 8, 2, 0)
+            sub = ref.quantize_pack(sd, ok[(l, h)], ov[(l, h)], want_bits, counts)
+            sub_off = ref.card_offsets(sd, counts)
+            for kv, plane in ((0, l * H + h), (1, L * H + l * H + h)):
+                want_rows = plane_rows(sub, sub_off, counts, 2, kv, D, G)
+                for name, want in want_rows.items():
+                    if want.size == 0:
+                        continue
+                    start = full_off[name] + (want.size * plane)
+                    got = card[start:start + want.size].cpu().numpy()
+                    assert np.array_equal(got, want), (hop, l, h, kv, name)
+            wk, wv = ref.unpack_dequant(sub, sd)
+            assert np.array_equal(K_out[l, h].cpu().numpy().view(np.uint16), wk[0, 0]), (hop, l, h, "K")
+            assert np.array_equal(V_out[l, h].cpu().numpy().view(np.uint16), wv[0, 0]), (hop, l, h, "V")
+            ok[(l, h)] = wk.view(np.float16)
+            ov[(l, h)] = wv.view(np.float16)
+        # raw rows survive every hop unchanged
+        t16 = np.flatnonzero(want_bits == 16)
+        if t16.size:
+            t = int(t16[0])
+            assert torch.equal(K_out[:, :, t], K[:, :, t])
+        K, K_out = K_out, K
+        V, V_out = V_out, V
