@@ -25,18 +25,21 @@ int compute_units() {
 }
 }  // namespace
 
-// Grid size for the streaming kernels: one wave per tile while that stays within the
-// resident set, else a persistent grid of QKV_BLOCKS_PER_CU (default 8) workgroups per
-// compute unit whose waves stride over the tiles.
-int persistent_blocks(uint64_t tiles) {
+// Grid size for the streaming kernels: one wave per tile (measured faster than a persistent
+// grid: 216 vs 226 us packing, 191 vs 206 us unpacking at 8K tokens).  QKV_BLOCKS_PER_CU = n
+// caps the grid at n workgroups per compute unit, whose waves then stride over the tiles.
+int grid_blocks(uint64_t tiles) {
   static const int per_cu = [] {
     const char* e = std::getenv("QKV_BLOCKS_PER_CU");
     const int v = e ? std::atoi(e) : 0;
-    return (v >= 1 && v <= 4096) ? v : 8;
+    return (v >= 1 && v <= 4096) ? v : 0;
   }();
-  const uint64_t want = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-  const uint64_t cap = (uint64_t)compute_units() * (uint64_t)per_cu;
-  const uint64_t n = want < cap ? want : cap;
+  uint64_t n = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+  if (per_cu > 0) {
+    const uint64_t cap = (uint64_t)compute_units() * (uint64_t)per_cu;
+    if (n > cap) n = cap;
+  }
+  if (n > 0x7FFFFFFFull) n = 0x7FFFFFFFull;
   return n < 1 ? 1 : (int)n;
 }
 

@@ -2,36 +2,43 @@
 // paper Sec. 4.2.1: the card carries the token-level bit-width vector; tokens are bucketed
 // by width so that every width owns one contiguous segment of the card).
 //
-// One workgroup of 1024 threads walks the tokens in chunks of 8192: thread i owns the 8
-// consecutive tokens 8 i .. 8 i + 7 of the chunk.  A first sweep counts the four classes
-// over all tokens (that fixes where each class starts inside order[]).  The second sweep
-// takes a block-wide exclusive scan of the per-thread class counters per chunk, which gives
-// every token its slot: the bucketing is stable (increasing token index inside a class).
-// slot[] and the copy of bits[] leave as 128- and 64-bit stores; the chunk's piece of
-// order[] is scattered into LDS first and leaves as coalesced stores, one contiguous range
-// per class.  The same kernel writes the header and zeroes the pad bytes of every section.
+// Workgroup b of 256 threads owns the 2048 tokens [2048 b, 2048 b + 2048), 8 consecutive
+// tokens (one 64-bit word of widths) per thread.  No workgroup talks to another: each one
+// first counts the classes over the whole bits vector by itself (a few words per thread,
+// byte-parallel arithmetic), which yields both the class totals - where each class starts
+// inside order[] - and the counts in front of its own tokens.  A packed DPP scan over the
+// per-thread counters then gives every token its slot, so the bucketing is stable
+// (increasing token index inside a class).  The work is bound by instruction issue, not by
+// memory, which is why it is spread over several compute units instead of one.
+// Workgroup 0 also writes the header and zeroes the pad bytes of every section.
 #include "qkv_common.h"
 
 namespace qkv {
 namespace {
 
-constexpr int kThreads = 1024;
+constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWaveSize;
 constexpr uint32_t kPerThread = 8;
-constexpr uint32_t kChunk = kThreads * kPerThread;
+constexpr uint32_t kPerBlock = kThreads * kPerThread;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// class of a width; anything else is flagged and treated as 2-bit so that order[] stays a permutation
-__device__ inline uint32_t class_of(uint32_t b, uint32_t& bad) {
-  const uint32_t c = (b == 4) ? 1u : (b == 8) ? 2u : (b == 16) ? 3u : 0u;
-  bad |= (c == 0 && b != 2);
-  return c;
+// Class of a width: 4 -> 1, 8 -> 2, 16 -> 3, everything else 0 (2, and also invalid widths, which
+// are flagged in the header: order[] stays a permutation and every index stays in range).
+__device__ inline uint32_t class_of(uint32_t b) { return (b == 4) ? 1u : (b == 8) ? 2u : (b == 16) ? 3u : 0u; }
+
+// Number of bytes of w equal to the byte replicated in `pattern` (exact, no carries between bytes).
+__device__ inline uint32_t count_bytes_equal(uint64_t w, uint64_t pattern) {
+  const uint64_t low7 = 0x7F7F7F7F7F7F7F7Full;
+  const uint64_t x = w ^ pattern;
+  const uint64_t zero = ~(((x & low7) + low7) | x | low7);      // 0x80 in every byte of x that is 0
+  return (uint32_t)__builtin_popcountll(zero);
 }
 
 // The widths of tokens t0 .. t0+7 as the 8 bytes of a word (first token lowest); tokens at or
-// past T read as 0.
+// past T read as 0 (no class pattern, so they are never counted).
 __device__ inline uint64_t load_widths(const uint8_t* __restrict__ bits, uint32_t t0, uint32_t T, bool aligned) {
+  if (t0 >= T) return 0;
   if (aligned && t0 + kPerThread <= T) return *reinterpret_cast<const uint64_t*>(bits + t0);
   uint64_t w = 0;
 #pragma unroll
@@ -40,134 +47,120 @@ __device__ inline uint64_t load_widths(const uint8_t* __restrict__ bits, uint32_
   return w;
 }
 
-struct BlockScan {
-  uint32_t before[4];   // tokens of each class owned by lower threads
-  uint32_t total[4];    // tokens of each class in the whole block
-};
-
-// Exclusive block-wide scan of four per-thread counters.  Two barriers; wave_tot is scratch.
-__device__ inline BlockScan block_scan4(const uint32_t (&cnt)[4], uint32_t lane, uint32_t wave,
-                                        uint32_t (*wave_tot)[kWaves]) {
-  BlockScan r;
+// Sums of N values over the workgroup with one barrier.  `slots` is LDS scratch.
+template <int N>
+__device__ inline void block_sums(uint32_t (&v)[N], uint32_t lane, uint32_t wave, uint32_t (*slots)[kWaves]) {
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    const uint32_t inc = wave_inclusive_scan(cnt[c]);
-    r.before[c] = inc - cnt[c];
-    if (lane == 63) wave_tot[c][wave] = inc;
+  for (int n = 0; n < N; ++n) {
+    const uint32_t inc = wave_inclusive_scan(v[n]);
+    if (lane == 63) slots[n][wave] = inc;
   }
   __syncthreads();
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    uint32_t before = 0, all = 0;
+  for (int n = 0; n < N; ++n) {
+    uint32_t s = 0;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const uint32_t x = wave_tot[c][w];
-      before += ((uint32_t)w < wave) ? x : 0u;
-      all += x;
-    }
-    r.before[c] += before;
-    r.total[c] = all;
+    for (int w = 0; w < kWaves; ++w) s += slots[n][w];
+    v[n] = s;
   }
-  __syncthreads();
-  return r;
-}
-
-__device__ inline uint32_t pick4(uint32_t c, uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3) {
-  return (c == 0) ? a0 : (c == 1) ? a1 : (c == 2) ? a2 : a3;
 }
 
 __global__ __launch_bounds__(kThreads) void classify_kernel(const uint8_t* __restrict__ bits, CardGeom g,
                                                            qkv_card_header_t header, uint8_t* __restrict__ card,
                                                            bool aligned) {
-  __shared__ uint32_t order_lds[kChunk];
-  __shared__ uint32_t wave_tot[4][kWaves];
-  __shared__ uint32_t bad_any;
+  __shared__ uint32_t sum_slots[7][kWaves];
+  __shared__ uint32_t slots[kWaves];
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wave = tid >> 6;
   const uint32_t T = g.tokens;
-  const uint32_t n_chunks = (T + kChunk - 1) / kChunk;
-  if (tid == 0) bad_any = 0;
+  const uint32_t block_t0 = blockIdx.x * kPerBlock;       // < T for every launched workgroup
+  const uint32_t t0 = block_t0 + tid * kPerThread;
 
-  // ---- sweep 1: class totals over all tokens
-  uint32_t cnt[4] = {0, 0, 0, 0};
-  uint32_t bad = 0;
-  uint64_t first_widths = 0;
-  for (uint32_t k = 0; k < n_chunks; ++k) {
-    const uint32_t t0 = k * kChunk + tid * kPerThread;
-    const uint64_t w = load_widths(bits, min(t0, T), T, aligned);
-    if (k == 0) first_widths = w;
-#pragma unroll
-    for (uint32_t i = 0; i < kPerThread; ++i) {
-      if (t0 + i < T) {
-        const uint32_t c = class_of((uint32_t)(w >> (8 * i)) & 0xFFu, bad);
-        cnt[0] += (c == 0); cnt[1] += (c == 1); cnt[2] += (c == 2); cnt[3] += (c == 3);
-      }
-    }
+  // ---- counts over the whole vector: totals, and what lies in front of this workgroup.
+  // Thread tid visits the words tid, tid + 256, ...: its own word is one of them.
+  const uint64_t p2 = 0x0202020202020202ull, p4 = p2 << 1, p8 = p2 << 2, p16 = p2 << 3;
+  uint32_t tot1 = 0, tot2 = 0, tot3 = 0, valid = 0;       // classes 1..3, and all four valid widths
+  uint32_t pre1 = 0, pre2 = 0, pre3 = 0;                  // classes 1..3 among the tokens below block_t0
+  uint64_t mine = 0;
+  const uint32_t n_words = (T + kPerThread - 1) / kPerThread;
+  for (uint32_t i = tid; i < n_words; i += kThreads) {
+    const uint64_t w = load_widths(bits, i * kPerThread, T, aligned);
+    const uint32_t c1 = count_bytes_equal(w, p4), c2 = count_bytes_equal(w, p8), c3 = count_bytes_equal(w, p16);
+    tot1 += c1; tot2 += c2; tot3 += c3;
+    valid += c1 + c2 + c3 + count_bytes_equal(w, p2);
+    const bool before = i * kPerThread < block_t0;
+    pre1 += before ? c1 : 0u; pre2 += before ? c2 : 0u; pre3 += before ? c3 : 0u;
+    if (i * kPerThread == t0) mine = w;
   }
-  const BlockScan all = block_scan4(cnt, lane, wave, wave_tot);
-  if (bad) atomicOr(&bad_any, 1u);
+  {
+    uint32_t v[7] = {tot1, tot2, tot3, valid, pre1, pre2, pre3};
+    block_sums<7>(v, lane, wave, sum_slots);
+    tot1 = v[0]; tot2 = v[1]; tot3 = v[2]; valid = v[3]; pre1 = v[4]; pre2 = v[5]; pre3 = v[6];
+  }
+  const uint32_t tot0 = T - tot1 - tot2 - tot3;
+  const uint32_t pre0 = block_t0 - pre1 - pre2 - pre3;
   // class bases from the histogram the device saw: order[] is then a permutation of 0..T-1
   // whatever the host passed as counts
-  const uint32_t base1 = all.total[0], base2 = base1 + all.total[1], base3 = base2 + all.total[2];
+  const uint32_t base1 = tot0, base2 = base1 + tot1, base3 = base2 + tot2;
+
+  // ---- slots of this workgroup's tokens: a scan of the per-thread counts of classes 1..3,
+  // 10 bits each in one word (a wave holds at most 512 tokens); class 0 is what remains
+  uint32_t cls[kPerThread];
+  uint32_t packed = 0;
+  uint32_t n_mine = 0;
+#pragma unroll
+  for (uint32_t i = 0; i < kPerThread; ++i) {
+    cls[i] = class_of((uint32_t)(mine >> (8 * i)) & 0xFFu);
+    if (t0 + i < T) {
+      ++n_mine;
+      packed += (cls[i] == 1) ? 1u : (cls[i] == 2) ? (1u << 10) : (cls[i] == 3) ? (1u << 20) : 0u;
+    }
+  }
+  const uint32_t inc = wave_inclusive_scan(packed);
+  const uint32_t inc_n = wave_inclusive_scan(n_mine);
+  if (lane == 63) slots[wave] = inc;
+  __syncthreads();
+  uint32_t w1 = 0, w2 = 0, w3 = 0;                        // classes 1..3 in the lower waves of this workgroup
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    const uint32_t x = ((uint32_t)w < wave) ? slots[w] : 0u;
+    w1 += x & 1023u; w2 += (x >> 10) & 1023u; w3 += x >> 20;
+  }
+  const uint32_t ex = inc - packed;                       // lower lanes of this wave
+  const uint32_t e1 = ex & 1023u, e2 = (ex >> 10) & 1023u, e3 = ex >> 20;
+  const uint32_t tokens_below = wave * (kWaveSize * kPerThread) + (inc_n - n_mine);   // inside the workgroup
+  uint32_t run1 = pre1 + w1 + e1, run2 = pre2 + w2 + e2, run3 = pre3 + w3 + e3;
+  uint32_t run0 = pre0 + tokens_below - (w1 + e1) - (w2 + e2) - (w3 + e3);
 
   uint8_t* bits_out = card + g.off_bits;
   uint32_t* slot_out = reinterpret_cast<uint32_t*>(card + g.off_slot);
   uint32_t* order_out = reinterpret_cast<uint32_t*>(card + g.off_order);
-
-  // ---- sweep 2: slots, chunk by chunk
-  uint32_t carry[4] = {0, 0, 0, 0};            // tokens of each class in the chunks already done
-  for (uint32_t k = 0; k < n_chunks; ++k) {
-    const uint32_t t0 = k * kChunk + tid * kPerThread;
-    const uint64_t w = (k == 0) ? first_widths : load_widths(bits, min(t0, T), T, aligned);
-    uint32_t cls[kPerThread];
-    uint32_t mine[4] = {0, 0, 0, 0};
-    uint32_t ignore = 0;
+  uint32_t slot[kPerThread];
 #pragma unroll
-    for (uint32_t i = 0; i < kPerThread; ++i) {
-      cls[i] = class_of((uint32_t)(w >> (8 * i)) & 0xFFu, ignore);
-      if (t0 + i < T) { mine[0] += (cls[i] == 0); mine[1] += (cls[i] == 1); mine[2] += (cls[i] == 2); mine[3] += (cls[i] == 3); }
-    }
-    const BlockScan sc = block_scan4(mine, lane, wave, wave_tot);
-    // where each class's run of this chunk starts inside the LDS staging array
-    const uint32_t reg1 = sc.total[0], reg2 = reg1 + sc.total[1], reg3 = reg2 + sc.total[2];
-    uint32_t run0 = sc.before[0], run1 = sc.before[1], run2 = sc.before[2], run3 = sc.before[3];
-    uint32_t slot[kPerThread];
-#pragma unroll
-    for (uint32_t i = 0; i < kPerThread; ++i) {
-      const uint32_t c = cls[i];
-      const uint32_t in_chunk = pick4(c, run0, run1, run2, run3);
-      run0 += (c == 0); run1 += (c == 1); run2 += (c == 2); run3 += (c == 3);
-      slot[i] = pick4(c, carry[0], carry[1], carry[2], carry[3]) + in_chunk;
-      if (t0 + i < T) order_lds[pick4(c, 0u, reg1, reg2, reg3) + in_chunk] = t0 + i;
-    }
-    if (t0 + kPerThread <= T) {
-      *reinterpret_cast<u32x4*>(slot_out + t0) = (u32x4){slot[0], slot[1], slot[2], slot[3]};
-      *reinterpret_cast<u32x4*>(slot_out + t0 + 4) = (u32x4){slot[4], slot[5], slot[6], slot[7]};
-      *reinterpret_cast<uint64_t*>(bits_out + t0) = w;
-    } else {
-#pragma unroll
-      for (uint32_t i = 0; i < kPerThread; ++i) {
-        if (t0 + i < T) { slot_out[t0 + i] = slot[i]; bits_out[t0 + i] = (uint8_t)(w >> (8 * i)); }
-      }
-    }
-    __syncthreads();
-    const uint32_t chunk_n = min(kChunk, T - k * kChunk);
-    for (uint32_t p = tid; p < chunk_n; p += kThreads) {
-      const uint32_t c = (p >= reg3) ? 3u : (p >= reg2) ? 2u : (p >= reg1) ? 1u : 0u;
-      const uint32_t dst = pick4(c, 0u, base1, base2, base3) + pick4(c, carry[0], carry[1], carry[2], carry[3]) +
-                           (p - pick4(c, 0u, reg1, reg2, reg3));
-      order_out[dst] = order_lds[p];
-    }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) carry[c] += sc.total[c];
-    __syncthreads();
+  for (uint32_t i = 0; i < kPerThread; ++i) {
+    const uint32_t c = cls[i];
+    const uint32_t s = (c == 0) ? run0 : (c == 1) ? run1 : (c == 2) ? run2 : run3;
+    run0 += (c == 0); run1 += (c == 1); run2 += (c == 2); run3 += (c == 3);
+    slot[i] = s;
+    if (t0 + i < T) order_out[((c == 0) ? 0u : (c == 1) ? base1 : (c == 2) ? base2 : base3) + s] = t0 + i;
   }
+  if (t0 + kPerThread <= T) {
+    *reinterpret_cast<u32x4*>(slot_out + t0) = (u32x4){slot[0], slot[1], slot[2], slot[3]};
+    *reinterpret_cast<u32x4*>(slot_out + t0 + 4) = (u32x4){slot[4], slot[5], slot[6], slot[7]};
+    *reinterpret_cast<uint64_t*>(bits_out + t0) = mine;
+  } else {
+#pragma unroll
+    for (uint32_t i = 0; i < kPerThread; ++i) {
+      if (t0 + i < T) { slot_out[t0 + i] = slot[i]; bits_out[t0 + i] = (uint8_t)(mine >> (8 * i)); }
+    }
+  }
+
+  if (blockIdx.x != 0) return;
 
   // header: 64 dwords, the status word (dword 48) filled in from what the device saw
   if (tid < 64) {
-    uint32_t status = bad_any ? QKV_STATUS_BAD_BITS : 0u;
-    if (all.total[0] != g.n[0] || all.total[1] != g.n[1] || all.total[2] != g.n[2] || all.total[3] != g.n[3])
-      status |= QKV_STATUS_BAD_COUNTS;
+    uint32_t status = (valid != T) ? QKV_STATUS_BAD_BITS : 0u;
+    if (tot0 != g.n[0] || tot1 != g.n[1] || tot2 != g.n[2] || tot3 != g.n[3]) status |= QKV_STATUS_BAD_COUNTS;
     const uint32_t* h = reinterpret_cast<const uint32_t*>(&header);
     uint32_t v = h[tid];
     if (tid == 48) v = status;
@@ -175,8 +168,7 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(const uint8_t* __res
   }
 
   // pad bytes behind every section (each less than 256 bytes)
-  if (tid >= 256 && tid < 512) {
-    const uint32_t i = tid - 256;
+  {
     const uint64_t P = g.planes, D = g.head_dim, M = (uint64_t)(g.head_dim / g.group_size) * 4;
     uint64_t start[10], used[10];
     start[0] = g.off_bits;  used[0] = T;
@@ -191,7 +183,7 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(const uint8_t* __res
 #pragma unroll
     for (int s = 0; s < 10; ++s) {
       const uint64_t pad = align256(used[s]) - used[s];
-      if (i < pad) card[start[s] + used[s] + i] = 0;
+      if (tid < pad) card[start[s] + used[s] + tid] = 0;
     }
   }
 }
@@ -201,7 +193,8 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(const uint8_t* __res
 hipError_t launch_classify(const uint8_t* bits, const CardGeom& geom, const qkv_card_header_t& header,
                            uint8_t* card, hipStream_t stream) {
   const bool aligned = reinterpret_cast<uintptr_t>(bits) % 8 == 0;
-  hipLaunchKernelGGL(classify_kernel, dim3(1), dim3(kThreads), 0, stream, bits, geom, header, card, aligned);
+  const uint32_t blocks = (geom.tokens + kPerBlock - 1) / kPerBlock;
+  hipLaunchKernelGGL(classify_kernel, dim3(blocks), dim3(kThreads), 0, stream, bits, geom, header, card, aligned);
   return hipGetLastError();
 }
 

@@ -319,7 +319,7 @@ hipError_t launch_pack(const CardGeom& geom, const void* k, const void* v, uint8
     tiles += (rows + tile_rows - 1) / tile_rows;
   }
   if (tiles == 0) return hipSuccess;
-  const dim3 grid(persistent_blocks(tiles)), block(kBlockThreads);
+  const dim3 grid(grid_blocks(tiles)), block(kBlockThreads);
   switch (geom.group_size) {
     case 32: hipLaunchKernelGGL(pack_kernel<32>, grid, block, 0, stream, a); break;
     case 64: hipLaunchKernelGGL(pack_kernel<64>, grid, block, 0, stream, a); break;

@@ -12,7 +12,10 @@ namespace qkv {
 constexpr int kWaveSize = 64;
 constexpr int kTileChunks = 512;        // 16-byte fp16 chunks one wave handles per tile (8 per lane)
 constexpr int kTileIters = kTileChunks / kWaveSize;
-constexpr int kBlockThreads = 256;      // 4 independent waves per workgroup
+#ifndef QKV_BLOCK_THREADS
+#define QKV_BLOCK_THREADS 256
+#endif
+constexpr int kBlockThreads = QKV_BLOCK_THREADS;      // independent waves, 4 per workgroup
 constexpr int kWavesPerBlock = kBlockThreads / kWaveSize;
 
 // Everything a kernel needs to find its way around a card.  Built on the host for the
@@ -95,8 +98,8 @@ __device__ inline uint32_t wave_inclusive_scan(uint32_t v) {
   return v;
 }
 
-// Number of persistent workgroups for a streaming kernel with `tiles` wave-tiles of work.
-int persistent_blocks(uint64_t tiles);
+// Number of workgroups for a streaming kernel with `tiles` wave-tiles of work.
+int grid_blocks(uint64_t tiles);
 
 // Kernel launchers (one per source file).  All enqueue on `stream` and return a hipError_t.
 hipError_t launch_classify(const uint8_t* bits, const CardGeom& geom, const qkv_card_header_t& header,

@@ -296,7 +296,7 @@ hipError_t launch_unpack(const uint8_t* card, uint64_t card_bytes, const CardGeo
   const uint32_t tile_rows = kTileChunks >> expect.lpr_shift;
   const uint64_t rows = (uint64_t)expect.planes * expect.tokens;
   const uint64_t tiles = (rows + tile_rows - 1) / tile_rows + 3;
-  const dim3 grid(persistent_blocks(tiles)), block(kBlockThreads);
+  const dim3 grid(grid_blocks(tiles)), block(kBlockThreads);
   switch (expect.group_size) {
     case 32: hipLaunchKernelGGL(unpack_kernel<32>, grid, block, 0, stream, a); break;
     case 64: hipLaunchKernelGGL(unpack_kernel<64>, grid, block, 0, stream, a); break;
