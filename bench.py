@@ -123,14 +123,24 @@ def main():
 
     for _ in range(args.warmup):
         step()
+    # timed region: exactly K steps, nothing else on the stream
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # the same K steps again with HIP events around every call (the events cost a few
+    # microseconds per step themselves, which is why the figure above is taken without them)
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(evs[i])
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
+    ms_per_step_events = (time.perf_counter() - t0) / args.steps * 1e3
 
     def avg_ms(a, b):
         return sum(e[a].elapsed_time(e[b]) for e in evs) / len(evs)
@@ -179,6 +189,7 @@ def main():
         "stages_ms": {"assign_bits": round(assign_ms, 4), "quantize_pack": round(pack_ms, 4),
                       "unpack_dequant": round(unpack_ms, 4)},
         "pct_hbm_peak": {"quantize_pack": round(100 * legs[0]["frac"], 2), "unpack_dequant": round(100 * legs[1]["frac"], 2)},
+        "ms_per_step_with_events": round(ms_per_step_events, 4),
         "copy_ceiling_gbs": round(copy_gbs, 1),
     }
     if not args.no_cpu:
