@@ -170,8 +170,8 @@ def main():
                 "avg_ms": round(ms, 4),
                 "algorithmic_bytes": moved, "kv_gbs": round(kv_bytes / (ms * 1e-3) / 1e9, 1)}
 
-    legs = [roof("qkv_quantize_pack: classify_kernel + pack_kernel<%d>" % G, pack_ms, "pack"),
-            roof("qkv_unpack_dequant: unpack_kernel<%d>" % G, unpack_ms, "unpack")]
+    legs = [roof("qkv_quantize_pack: classify_kernel + pack_kernel<%d, keep>" % G, pack_ms, "pack"),
+            roof("qkv_unpack_dequant: unpack_kernel<%d, keep>" % G, unpack_ms, "unpack")]
     dominant = max(legs, key=lambda r: r["avg_ms"])
 
     out = {

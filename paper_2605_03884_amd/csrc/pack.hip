@@ -116,6 +116,13 @@ __host__ __device__ constexpr uint32_t magic_carry() {
   return s;
 }
 
+// Card stores.  KEEP: plain stores, the card stays in the memory-side cache for a receiver
+// that unpacks it next; otherwise nontemporal, for cards far larger than that cache.
+template <bool KEEP, typename V>
+__device__ inline void card_store(V* p, V v) {
+  if (KEEP) *p = v; else __builtin_nontemporal_store(v, p);
+}
+
 // LDS position (in 16-byte units) of input chunk q of a tile.
 __device__ inline uint32_t swizzle(uint32_t q) { return q ^ ((q >> 3) & 3u); }
 
@@ -174,7 +181,7 @@ __device__ inline void encode_span(const uint32_t (&w)[16], float neg_mn, float 
   for (int o = 0; o < W; ++o) out[o] -= magic_carry<W>();
 }
 
-template <int W, int G>
+template <int W, int G, bool KEEP>
 __device__ inline void pack_tile(const PackArgs& a, int c, uint32_t r0, uint32_t n_rows, uint32_t lane, u32x4* lds) {
   constexpr int GS = G / 32;                     // spans (lanes) per group
   constexpr float QMAXF = (float)((1 << W) - 1);
@@ -247,16 +254,17 @@ __device__ inline void pack_tile(const PackArgs& a, int c, uint32_t r0, uint32_t
     const uint64_t gsp = span0 + sp;
     if (gsp < seg_spans) {
       uint8_t* dst = codes_seg + gsp * (4u * W);
-      if (W == 2) *reinterpret_cast<u32x2*>(dst) = (u32x2){out[0], out[1]};
-      if (W >= 4) *reinterpret_cast<u32x4*>(dst) = (u32x4){out[0], out[1], out[2], out[3]};
-      if (W == 8) *reinterpret_cast<u32x4*>(dst + 16) = (u32x4){out[4], out[5], out[6], out[7]};
-      if ((sp & (GS - 1)) == 0) meta_seg[gsp / GS] = s_h | (mn_h << 16);   // fp16 scale first, then fp16 zero
+      if (W == 2) card_store<KEEP>(reinterpret_cast<u32x2*>(dst), (u32x2){out[0], out[1]});
+      if (W >= 4) card_store<KEEP>(reinterpret_cast<u32x4*>(dst), (u32x4){out[0], out[1], out[2], out[3]});
+      if (W == 8) card_store<KEEP>(reinterpret_cast<u32x4*>(dst + 16), (u32x4){out[4], out[5], out[6], out[7]});
+      if ((sp & (GS - 1)) == 0) card_store<KEEP>(&meta_seg[gsp / GS], s_h | (mn_h << 16));   // fp16 scale first, then fp16 zero
     }
   }
 }
 
 // ---- one tile of the fp16 segment: rows copied bit for bit ---------------------------------
 
+template <bool KEEP>
 __device__ inline void copy_tile(const PackArgs& a, uint32_t r0, uint32_t n_rows, uint32_t lane) {
   const CardGeom& g = a.g;
   const uint32_t lpr_shift = g.lpr_shift;
@@ -270,13 +278,13 @@ __device__ inline void copy_tile(const PackArgs& a, uint32_t r0, uint32_t n_rows
 #pragma unroll
   for (int k = 0; k < kTileIters; ++k) {
     const uint64_t off = (uint64_t)(k * kWaveSize + lane) * 16u;
-    if (off < left) *reinterpret_cast<u32x4*>(dst + off) = data[k];
+    if (off < left) card_store<KEEP>(reinterpret_cast<u32x4*>(dst + off), data[k]);
   }
 }
 
 // ---- grid ----------------------------------------------------------------------------------------
 
-template <int G>
+template <int G, bool KEEP>
 __global__ __launch_bounds__(kBlockThreads) void pack_kernel(PackArgs a) {
   __shared__ u32x4 lds[kWavesPerBlock][kTileChunks];
   const uint32_t lane = threadIdx.x & 63u;
@@ -295,10 +303,10 @@ __global__ __launch_bounds__(kBlockThreads) void pack_kernel(PackArgs a) {
     const uint32_t first = (gw + n_waves - cum) % n_waves;
     for (uint32_t i = first; i < tiles; i += n_waves) {
       const uint32_t r0 = i * tile_rows;
-      if (c == 0) pack_tile<2, G>(a, 0, r0, n_rows, lane, my_lds);
-      if (c == 1) pack_tile<4, G>(a, 1, r0, n_rows, lane, my_lds);
-      if (c == 2) pack_tile<8, G>(a, 2, r0, n_rows, lane, my_lds);
-      if (c == 3) copy_tile(a, r0, n_rows, lane);
+      if (c == 0) pack_tile<2, G, KEEP>(a, 0, r0, n_rows, lane, my_lds);
+      if (c == 1) pack_tile<4, G, KEEP>(a, 1, r0, n_rows, lane, my_lds);
+      if (c == 2) pack_tile<8, G, KEEP>(a, 2, r0, n_rows, lane, my_lds);
+      if (c == 3) copy_tile<KEEP>(a, r0, n_rows, lane);
     }
     cum = (cum + tiles) % n_waves;
   }
@@ -320,10 +328,14 @@ hipError_t launch_pack(const CardGeom& geom, const void* k, const void* v, uint8
   }
   if (tiles == 0) return hipSuccess;
   const dim3 grid(grid_blocks(tiles)), block(kBlockThreads);
-  switch (geom.group_size) {
-    case 32: hipLaunchKernelGGL(pack_kernel<32>, grid, block, 0, stream, a); break;
-    case 64: hipLaunchKernelGGL(pack_kernel<64>, grid, block, 0, stream, a); break;
-    default: hipLaunchKernelGGL(pack_kernel<128>, grid, block, 0, stream, a); break;
+  const bool keep = geom.total <= kCacheResidentCardBytes;
+  switch (geom.group_size * 2 + (keep ? 1 : 0)) {
+    case 65: hipLaunchKernelGGL((pack_kernel<32, true>), grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((pack_kernel<32, false>), grid, block, 0, stream, a); break;
+    case 129: hipLaunchKernelGGL((pack_kernel<64, true>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((pack_kernel<64, false>), grid, block, 0, stream, a); break;
+    case 257: hipLaunchKernelGGL((pack_kernel<128, true>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((pack_kernel<128, false>), grid, block, 0, stream, a); break;
   }
   return hipGetLastError();
 }

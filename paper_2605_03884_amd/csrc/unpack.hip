@@ -66,6 +66,13 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(1))) u32x4 global_u32x4;
 
+// Card loads.  KEEP: plain loads, which find a card that was packed a moment ago in the
+// memory-side cache; otherwise nontemporal, for cards far larger than that cache.
+template <bool KEEP, typename V>
+__device__ inline V card_load(const V* p) {
+  return KEEP ? *p : __builtin_nontemporal_load(p);
+}
+
 // LDS position (in 16-byte units) of output chunk q of a tile.
 __device__ inline uint32_t swizzle(uint32_t q) { return q ^ ((q >> 3) & 3u); }
 
@@ -160,7 +167,7 @@ __device__ inline void decode_span(const uint32_t (&cw)[W], float s, float z, ui
   }
 }
 
-template <int W, int G>
+template <int W, int G, bool KEEP>
 __device__ inline void unpack_tile(const UnpackArgs& a, const CardGeom& g, int c, uint32_t r0, uint32_t n_rows,
                                    uint32_t lane, u32x4* lds, uint32_t& bad) {
   constexpr int GS = G / 32;                     // spans (lanes) per group
@@ -186,16 +193,16 @@ __device__ inline void unpack_tile(const UnpackArgs& a, const CardGeom& g, int c
     if (gsp < seg_spans) {
       const uint8_t* src = codes_seg + gsp * (4u * W);
       if (W == 2) {
-        const u32x2 t = *reinterpret_cast<const u32x2*>(src);
+        const u32x2 t = card_load<KEEP>(reinterpret_cast<const u32x2*>(src));
         cw[round][0] = t.x; cw[round][1] = t.y;
       } else {
 #pragma unroll
         for (int h = 0; h < W / 4; ++h) {
-          const u32x4 t = *reinterpret_cast<const u32x4*>(src + 16 * h);
+          const u32x4 t = card_load<KEEP>(reinterpret_cast<const u32x4*>(src + 16 * h));
           cw[round][4 * h] = t.x; cw[round][4 * h + 1] = t.y; cw[round][4 * h + 2] = t.z; cw[round][4 * h + 3] = t.w;
         }
       }
-      pair[round] = meta_seg[gsp / GS];
+      pair[round] = card_load<KEEP>(meta_seg + gsp / GS);
     }
   }
 
@@ -218,6 +225,7 @@ __device__ inline void unpack_tile(const UnpackArgs& a, const CardGeom& g, int c
   store_tile(my_row, lane, lpr_shift, data);
 }
 
+template <bool KEEP>
 __device__ inline void copy_tile(const UnpackArgs& a, const CardGeom& g, uint32_t r0, uint32_t n_rows, uint32_t lane,
                                  uint32_t& bad) {
   const uint32_t lpr_shift = g.lpr_shift;
@@ -231,7 +239,7 @@ __device__ inline void copy_tile(const UnpackArgs& a, const CardGeom& g, uint32_
   for (int k = 0; k < kTileIters; ++k) {
     const uint64_t off = (uint64_t)(k * kWaveSize + lane) * 16u;
     data[k] = (u32x4)(0u);
-    if (off < seg_left) data[k] = *reinterpret_cast<const u32x4*>(src + off);
+    if (off < seg_left) data[k] = card_load<KEEP>(reinterpret_cast<const u32x4*>(src + off));
   }
   store_tile(my_row, lane, lpr_shift, data);
 }
@@ -243,7 +251,7 @@ __global__ void unpack_status_kernel(UnpackArgs a) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *a.status = ok ? 0u : QKV_STATUS_BAD_HEADER;
 }
 
-template <int G>
+template <int G, bool KEEP>
 __global__ __launch_bounds__(kBlockThreads) void unpack_kernel(UnpackArgs a) {
   __shared__ u32x4 lds[kWavesPerBlock][kTileChunks];
   CardGeom g;
@@ -268,10 +276,10 @@ __global__ __launch_bounds__(kBlockThreads) void unpack_kernel(UnpackArgs a) {
     const uint32_t first = (gw + n_waves - cum) % n_waves;
     for (uint32_t i = first; i < tiles; i += n_waves) {
       const uint32_t r0 = (tiles - 1 - i) * tile_rows;
-      if (c == 0) unpack_tile<2, G>(a, g, 0, r0, n_rows, lane, my_lds, bad);
-      if (c == 1) unpack_tile<4, G>(a, g, 1, r0, n_rows, lane, my_lds, bad);
-      if (c == 2) unpack_tile<8, G>(a, g, 2, r0, n_rows, lane, my_lds, bad);
-      if (c == 3) copy_tile(a, g, r0, n_rows, lane, bad);
+      if (c == 0) unpack_tile<2, G, KEEP>(a, g, 0, r0, n_rows, lane, my_lds, bad);
+      if (c == 1) unpack_tile<4, G, KEEP>(a, g, 1, r0, n_rows, lane, my_lds, bad);
+      if (c == 2) unpack_tile<8, G, KEEP>(a, g, 2, r0, n_rows, lane, my_lds, bad);
+      if (c == 3) copy_tile<KEEP>(a, g, r0, n_rows, lane, bad);
     }
     cum = (cum + tiles) % n_waves;
   }
@@ -300,10 +308,14 @@ hipError_t launch_unpack(const uint8_t* card, uint64_t card_bytes, const CardGeo
   const uint64_t rows = (uint64_t)expect.planes * expect.tokens;
   const uint64_t tiles = (rows + tile_rows - 1) / tile_rows + 3;
   const dim3 grid(grid_blocks(tiles)), block(kBlockThreads);
-  switch (expect.group_size) {
-    case 32: hipLaunchKernelGGL(unpack_kernel<32>, grid, block, 0, stream, a); break;
-    case 64: hipLaunchKernelGGL(unpack_kernel<64>, grid, block, 0, stream, a); break;
-    default: hipLaunchKernelGGL(unpack_kernel<128>, grid, block, 0, stream, a); break;
+  const bool keep = card_bytes <= kCacheResidentCardBytes;
+  switch (expect.group_size * 2 + (keep ? 1 : 0)) {
+    case 65: hipLaunchKernelGGL((unpack_kernel<32, true>), grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((unpack_kernel<32, false>), grid, block, 0, stream, a); break;
+    case 129: hipLaunchKernelGGL((unpack_kernel<64, true>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((unpack_kernel<64, false>), grid, block, 0, stream, a); break;
+    case 257: hipLaunchKernelGGL((unpack_kernel<128, true>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((unpack_kernel<128, false>), grid, block, 0, stream, a); break;
   }
   return hipGetLastError();
 }
