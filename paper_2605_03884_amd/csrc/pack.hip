@@ -205,7 +205,7 @@ __device__ inline void pack_tile(const PackArgs& a, int c, uint32_t r0, uint32_t
   const uint64_t seg_spans = (uint64_t)n_rows << spr_shift;
 
 #pragma unroll 1
-  for (int round = 0; round < 2; ++round) {
+  for (int round = 0; round < kTileRounds; ++round) {
     const uint32_t sp = round * kWaveSize + lane;
     uint32_t w[16];
 #pragma unroll

@@ -10,8 +10,14 @@
 namespace qkv {
 
 constexpr int kWaveSize = 64;
-constexpr int kTileChunks = 512;        // 16-byte fp16 chunks one wave handles per tile (8 per lane)
+#ifndef QKV_TILE_CHUNKS
+#define QKV_TILE_CHUNKS 512
+#endif
+constexpr int kTileChunks = QKV_TILE_CHUNKS;   // 16-byte fp16 chunks one wave handles per tile (8 per lane)
 constexpr int kTileIters = kTileChunks / kWaveSize;
+constexpr int kTileRounds = kTileChunks / (4 * kWaveSize);   // spans of 32 values per lane and tile
+static_assert(kTileChunks % (4 * kWaveSize) == 0 && kTileChunks >= 256 && kTileChunks <= 512,
+              "a tile is a whole number of 64-span rounds and at most 64 rows at head_dim 64");
 #ifndef QKV_BLOCK_THREADS
 #define QKV_BLOCK_THREADS 256
 #endif

@@ -182,10 +182,10 @@ __device__ inline void unpack_tile(const UnpackArgs& a, const CardGeom& g, int c
   const uint64_t seg_spans = (uint64_t)n_rows << spr_shift;
 
   // both rounds' codes and pairs first, so the loads overlap
-  uint32_t cw[2][W];
-  uint32_t pair[2];
+  uint32_t cw[kTileRounds][W];
+  uint32_t pair[kTileRounds];
 #pragma unroll
-  for (int round = 0; round < 2; ++round) {
+  for (int round = 0; round < kTileRounds; ++round) {
     const uint64_t gsp = span0 + round * kWaveSize + lane;
 #pragma unroll
     for (int i = 0; i < W; ++i) cw[round][i] = 0;
@@ -208,7 +208,7 @@ __device__ inline void unpack_tile(const UnpackArgs& a, const CardGeom& g, int c
 
   const uint32_t x = (lane >> 1) & 3u;           // swizzle term of this lane's spans
 #pragma unroll
-  for (int round = 0; round < 2; ++round) {
+  for (int round = 0; round < kTileRounds; ++round) {
     const uint32_t sp = round * kWaveSize + lane;
     const float s = half_bits_to_float(pair[round] & 0xFFFFu);
     const float z = half_bits_to_float(pair[round] >> 16);
