@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 # Bytes between L2 and the memory fabric per launch, from the FETCH_SIZE and WRITE_SIZE counters
 # scaled by what a plain 512 MiB copy reads on them (profiles/pack_unpack_llama8b_8k_b3_hbm_traffic.txt).
 MEASURED_TRAFFIC = {
-    "llama8b_8k_b3": {"pack": 1341668864, "unpack": 1342011495},
+    "llama8b_8k_b3": {"pack": 1341457101, "unpack": 1342215680},
 }
 
 
@@ -81,7 +81,7 @@ def main():
                     help="layers of the workload the CPU oracle is timed on (0: about 8192*32 token-layers)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (the card is built per GPU; see DESIGN.md on sharding); "
+        print("bench.py: this build runs on one GPU only (a card is built and unpacked per GPU, planes shard without exchange); "
               "run with --gpus 1", file=sys.stderr)
         return 2
     if not torch.cuda.is_available():
@@ -179,7 +179,7 @@ def main():
         "value": round(kv_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "unit": "GB/s of fp16 KV bytes per handoff (assign_bits + quantize_pack + unpack_dequant)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 in, f32 quantizer arithmetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": args.workload, "layers": L, "kv_heads": H, "tokens": T, "head_dim": D, "group_size": G,
                    "counts_2_4_8_16": counts, "avg_code_bits": round(avg_bits, 4), "kv_bytes": kv_bytes,
