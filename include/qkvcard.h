@@ -209,6 +209,34 @@ int qkv_unpack_dequant(const void* card_dev, uint64_t card_bytes, const qkv_desc
                        void* k_out_dev, void* v_out_dev, uint32_t* status_dev, void* stream);
 
 /*
+ * Decode-step attention of one new query token directly over a card, without rebuilding
+ * the dense cache (paper Sec. 4.3: consuming a foreign quantized cache inside attention,
+ * which the paper names as its long-term goal).  For every layer l and query head hq, with
+ * kv head h = hq / (q_heads / kv_heads):
+ *     s_t = softmax_scale * <q[l][hq], K^[l][h][t]>,   t = 0 .. T-1
+ *     out[l][hq] = sum_t softmax(s)_t * V^[l][h][t],   lse[l][hq] = log sum_t exp(s_t)
+ * where K^, V^ are the dequantized fp16 values, exactly those qkv_unpack_dequant would
+ * write (raw 16-bit rows as they are).  Scores are accumulated in fp32 from fp16 products,
+ * the softmax and the weighted sum run in fp32; the result agrees with the float64
+ * definition to a few units in 1e-6 of max|V^| (summation order only).
+ *   card_dev, card_bytes, expect, status_dev: as for qkv_unpack_dequant; head_dim must be 128.
+ *   q_dev:    device, fp16 [layers][q_heads][128], 16-byte aligned.  q_heads is a multiple of
+ *             kv_heads, at most 16 query heads per kv head.
+ *   out_dev:  device, float [layers][q_heads][128], 16-byte aligned, written in full.
+ *   lse_dev:  device, float [layers][q_heads], may be NULL.  With (out, lse) the caller can
+ *             merge this result with attention over its own tokens.
+ *   workspace_dev: device scratch of at least qkv_card_attend_workspace() bytes, 16-byte
+ *             aligned; contents on entry and exit are unspecified.
+ * When the header does not match, out / lse are left untouched (status_dev says so).
+ * Asynchronous on `stream`.
+ */
+int qkv_card_attend_workspace(const qkv_desc_t* expect, int32_t q_heads, uint64_t* bytes_out);
+int qkv_card_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect,
+                    const void* q_dev, int32_t q_heads, float softmax_scale,
+                    float* out_dev, float* lse_dev, void* workspace_dev, uint64_t workspace_bytes,
+                    uint32_t* status_dev, void* stream);
+
+/*
  * Read a card's header back to the host and validate it (magic, version, shape
  * domain, counts summing to tokens, section offsets equal to the closed form,
  * total_bytes <= card_bytes).  Any out pointer may be NULL.  SYNCHRONISES `stream`.

@@ -72,6 +72,11 @@ def lib():
     L.qkv_quantize_pack.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, i64p, vp, ctypes.c_uint64, vp]
     L.qkv_unpack_dequant.restype = ctypes.c_int
     L.qkv_unpack_dequant.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, vp, vp, vp]
+    L.qkv_card_attend_workspace.restype = ctypes.c_int
+    L.qkv_card_attend_workspace.argtypes = [ctypes.POINTER(Desc), ctypes.c_int32, ctypes.POINTER(ctypes.c_uint64)]
+    L.qkv_card_attend.restype = ctypes.c_int
+    L.qkv_card_attend.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, ctypes.c_int32, ctypes.c_float, vp, vp,
+                                  vp, ctypes.c_uint64, vp, vp]
     L.qkv_card_peek.restype = ctypes.c_int
     L.qkv_card_peek.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), i64p, ctypes.POINTER(ctypes.c_float),
                                 ctypes.POINTER(ctypes.c_uint32), vp]
@@ -160,6 +165,29 @@ def unpack_dequant(card, expect, k_out, v_out, status=None, card_nbytes=None, st
                                     _dev_ptr(k_out, torch.float16, "k_out"), _dev_ptr(v_out, torch.float16, "v_out"),
                                     sp, _stream(stream)), "qkv_unpack_dequant")
     return k_out, v_out
+
+
+def card_attend_workspace(expect, q_heads):
+    out = ctypes.c_uint64(0)
+    _check(lib().qkv_card_attend_workspace(ctypes.byref(expect), int(q_heads), ctypes.byref(out)),
+           "qkv_card_attend_workspace")
+    return out.value
+
+
+def card_attend(card, expect, q, softmax_scale, out, lse=None, workspace=None, status=None, card_nbytes=None,
+                stream=None):
+    """card: device uint8; q: device float16 [L, Hq, 128]; out: device float32 [L, Hq, 128]; lse: float32 [L, Hq]."""
+    n = card.numel() if card_nbytes is None else int(card_nbytes)
+    q_heads = q.shape[1]
+    if workspace is None:
+        workspace = torch.empty(card_attend_workspace(expect, q_heads), dtype=torch.uint8, device=card.device)
+    lp = ctypes.c_void_p(0) if lse is None else _dev_ptr(lse, torch.float32, "lse")
+    sp = ctypes.c_void_p(0) if status is None else _dev_ptr(status, None, "status")
+    _check(lib().qkv_card_attend(_dev_ptr(card, torch.uint8, "card"), n, ctypes.byref(expect),
+                                 _dev_ptr(q, torch.float16, "q"), int(q_heads), float(softmax_scale),
+                                 _dev_ptr(out, torch.float32, "out"), lp, _dev_ptr(workspace, torch.uint8, "workspace"),
+                                 workspace.numel(), sp, _stream(stream)), "qkv_card_attend")
+    return out, lse
 
 
 def card_peek(card, card_nbytes=None, stream=None):

@@ -253,6 +253,54 @@ int qkv_unpack_dequant(const void* card_dev, uint64_t card_bytes, const qkv_desc
   return QKV_OK;
 }
 
+namespace {
+// Shape rules of the fused attention path and the floats of workspace it needs.
+int attend_workspace_floats(const qkv_desc_t* expect, int32_t q_heads, uint64_t* floats) {
+  const int rc = check_desc(expect);
+  if (rc) return rc;
+  if (expect->head_dim != 128) return QKV_ERR_SHAPE;
+  if (q_heads < expect->kv_heads || q_heads % expect->kv_heads != 0 || q_heads / expect->kv_heads > 16)
+    return QKV_ERR_SHAPE;
+  const uint32_t rep = (uint32_t)(q_heads / expect->kv_heads);
+  uint32_t chunk = 0, max_tasks = 0;
+  attend_plan((uint64_t)expect->tokens, rep, &chunk, &max_tasks);
+  *floats = (uint64_t)expect->layers * (uint64_t)expect->kv_heads * max_tasks * rep * (128u + 2u);
+  return QKV_OK;
+}
+}  // namespace
+
+int qkv_card_attend_workspace(const qkv_desc_t* expect, int32_t q_heads, uint64_t* bytes_out) {
+  if (!expect || !bytes_out) return QKV_ERR_NULL;
+  uint64_t floats = 0;
+  const int rc = attend_workspace_floats(expect, q_heads, &floats);
+  if (rc) return rc;
+  *bytes_out = floats * sizeof(float);
+  return QKV_OK;
+}
+
+int qkv_card_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, const void* q_dev,
+                    int32_t q_heads, float softmax_scale, float* out_dev, float* lse_dev, void* workspace_dev,
+                    uint64_t workspace_bytes, uint32_t* status_dev, void* stream) {
+  if (!card_dev || !expect || !q_dev || !out_dev || !workspace_dev) return QKV_ERR_NULL;
+  uint64_t floats = 0;
+  const int rc = attend_workspace_floats(expect, q_heads, &floats);
+  if (rc) return rc;
+  if (!std::isfinite(softmax_scale)) return QKV_ERR_SHAPE;
+  if (card_bytes < QKV_CARD_HEADER_BYTES || workspace_bytes < floats * sizeof(float)) return QKV_ERR_CAPACITY;
+  if (reinterpret_cast<uintptr_t>(card_dev) % QKV_CARD_ALIGN != 0 || reinterpret_cast<uintptr_t>(q_dev) % 16 != 0 ||
+      reinterpret_cast<uintptr_t>(out_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(lse_dev) % 4 != 0 ||
+      reinterpret_cast<uintptr_t>(workspace_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(status_dev) % 4 != 0)
+    return QKV_ERR_ALIGN;
+  const uint64_t zero[4] = {0, 0, 0, (uint64_t)expect->tokens};
+  CardGeom g;
+  build_geom(g, expect->layers, expect->kv_heads, expect->head_dim, expect->group_size, expect->tokens, zero);
+  if (launch_attend(static_cast<const uint8_t*>(card_dev), card_bytes, g, q_dev, (uint32_t)q_heads, softmax_scale,
+                    out_dev, lse_dev, static_cast<float*>(workspace_dev), status_dev,
+                    static_cast<hipStream_t>(stream)) != hipSuccess)
+    return QKV_ERR_HIP;
+  return QKV_OK;
+}
+
 int qkv_card_peek(const void* card_dev, uint64_t card_bytes, qkv_desc_t* desc_out, int64_t counts_out[4],
                   float* avg_bits_out, uint32_t* status_out, void* stream) {
   if (!card_dev) return QKV_ERR_NULL;

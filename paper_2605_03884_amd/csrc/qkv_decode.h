@@ -1,0 +1,110 @@
+// qkv_decode.h — device helpers shared by the kernels that read a card: header validation
+// and the decoder of one span of 32 values.  Internal to the GPU library.
+#pragma once
+
+#include "qkv_common.h"
+
+namespace qkv {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+__device__ inline float half_bits_to_float(uint32_t h) {
+  return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
+}
+
+// Card loads.  KEEP: plain loads, which find a card that was packed a moment ago in the
+// memory-side cache; otherwise nontemporal, for cards far larger than that cache.
+template <bool KEEP, typename V>
+__device__ inline V card_load(const V* p) {
+  return KEEP ? *p : __builtin_nontemporal_load(p);
+}
+
+// True when the header describes a layout-v1 card of the expected shape that fits in
+// card_bytes; fills `g` from the header's class counts.  Uniform over the grid.
+__device__ inline bool card_geometry_from_header(const uint8_t* card, uint64_t card_bytes, uint32_t layers,
+                                                 uint32_t kv_heads, uint32_t head_dim, uint32_t group_size,
+                                                 uint64_t tokens, CardGeom& g) {
+  const qkv_card_header_t* h = reinterpret_cast<const qkv_card_header_t*>(card);
+  const uint32_t* w = reinterpret_cast<const uint32_t*>(card);
+  bool ok = w[0] == 0x43564B51u && w[1] == 0x00445241u;          // "QKVC" "ARD\0"
+  ok = ok && h->version == QKV_CARD_VERSION && h->header_bytes == QKV_CARD_HEADER_BYTES;
+  ok = ok && h->layers == layers && h->kv_heads == kv_heads && h->head_dim == head_dim &&
+       h->group_size == group_size && h->tokens == tokens;
+  uint64_t counts[4];
+  uint64_t sum = 0;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    counts[c] = h->count[c];
+    ok = ok && counts[c] <= tokens;
+    sum += ok ? counts[c] : 0;
+  }
+  ok = ok && sum == tokens;
+  if (!ok) return false;
+  build_geom(g, layers, kv_heads, head_dim, group_size, tokens, counts);
+  ok = g.total <= card_bytes && h->total_bytes == g.total;
+  ok = ok && h->off_bits == g.off_bits && h->off_slot == g.off_slot && h->off_order == g.off_order &&
+       h->off_fp16 == g.off_fp16;
+#pragma unroll
+  for (int c = 0; c < 3; ++c) ok = ok && h->off_codes[c] == g.off_codes[c] && h->off_meta[c] == g.off_meta[c];
+  return ok;
+}
+
+// decode = fp16( fma(code, scale, zero) ): an fp32 fma rounded to fp32, then rounded to
+// fp16, both to nearest even.  The two steps are kept apart on purpose: the fused
+// fma-and-convert instruction rounds the exact sum once, straight to fp16, which gives a
+// different value whenever the fp32 result lands on an fp16 midpoint.
+__device__ inline uint32_t decode_pair(float q0, float q1, float s, float z) {
+  float a = __builtin_fmaf(q0, s, z);
+  float b = __builtin_fmaf(q1, s, z);
+  asm("" : "+v"(a));
+  asm("" : "+v"(b));
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
+
+// float(byte j of w): one instruction
+__device__ inline float byte_to_float(uint32_t w, int j) {
+  float r;
+  switch (j) {
+    case 0: asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(r) : "v"(w)); break;
+    case 1: asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(r) : "v"(w)); break;
+    case 2: asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(r) : "v"(w)); break;
+    default: asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(r) : "v"(w)); break;
+  }
+  return r;
+}
+
+// The 32 values of one span: W dwords of codes in, 16 dwords of packed fp16 out.
+template <int W>
+__device__ inline void decode_span(const uint32_t (&cw)[W], float s, float z, uint32_t (&out)[16]) {
+  if (W == 8) {
+#pragma unroll
+    for (int d = 0; d < 8; ++d) {          // dword d: codes 4d .. 4d+3, one per byte
+      out[2 * d] = decode_pair(byte_to_float(cw[d], 0), byte_to_float(cw[d], 1), s, z);
+      out[2 * d + 1] = decode_pair(byte_to_float(cw[d], 2), byte_to_float(cw[d], 3), s, z);
+    }
+  } else if (W == 4) {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {          // dword d: codes 8d .. 8d+7; byte j holds codes 2j (low), 2j+1 (high)
+      const uint32_t even = cw[d] & 0x0F0F0F0Fu, odd = (cw[d] >> 4) & 0x0F0F0F0Fu;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) out[4 * d + j] = decode_pair(byte_to_float(even, j), byte_to_float(odd, j), s, z);
+    }
+  } else {
+#pragma unroll
+    for (int d = 0; d < 2; ++d) {          // dword d: codes 16d .. 16d+15; byte j holds codes 4j .. 4j+3
+      const uint32_t c0 = cw[d] & 0x03030303u, c1 = (cw[d] >> 2) & 0x03030303u, c2 = (cw[d] >> 4) & 0x03030303u,
+                     c3 = (cw[d] >> 6) & 0x03030303u;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        out[8 * d + 2 * j] = decode_pair(byte_to_float(c0, j), byte_to_float(c1, j), s, z);
+        out[8 * d + 2 * j + 1] = decode_pair(byte_to_float(c2, j), byte_to_float(c3, j), s, z);
+      }
+    }
+  }
+}
+
+}  // namespace qkv

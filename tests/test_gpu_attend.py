@@ -1,0 +1,186 @@
+"""GPU parity of the fused attention over a card (qkv_card_attend) against its float64 oracle.
+
+Tolerance (derived from the arithmetic, computed per case from the data): the kernel forms each
+score from exact fp16 x fp16 products accumulated in fp32 (at most 128 roundings of relative size
+2^-24 on partial sums bounded by sum_i |q_i k_i|), evaluates 2^x with the hardware instruction
+(about 1 ulp) and accumulates p.V^ over T tokens in fp32.  So
+    |ds|  <= 128 * 2^-24 * scale * max_t sum_i |q_i K^_ti|
+    |do|  <= (2 |ds| + (T + 8) * 2^-24 + 2^-21) * max |V^|         (weights sum to one)
+    |dlse| <= |ds| + (T + 8) * 2^-24 + 2^-21
+These are worst-case bounds; rounding errors do not line up like that, and the observed errors
+(printed) are about 1e-6 of max |V^|.  A second, empirical guard of 1e-4 * max(1, max |V^|) is
+asserted as well so that a regression far inside the worst-case bound is still caught.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_03884_amd as qkv
+import qkv_synth
+from oracle import attend_ref, ref
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def build_card(L, H, T, D, G, bits, seed, kind="llama"):
+    K, V = qkv_synth.make_kv(L, H, T, D, seed, kind)
+    counts = [int((bits == w).sum()) for w in (2, 4, 8, 16)]
+    rd = ref.make_desc(L, H, T, D, G)
+    card = ref.quantize_pack(rd, K.numpy(), V.numpy(), bits, counts)     # the oracle's card: the attention kernel is what is under test
+    return rd, card
+
+
+def run_gpu(card, L, H, T, D, G, q, scale, with_lse=True):
+    desc = qkv.Desc.make(L, H, T, D, G)
+    card_dev = torch.from_numpy(card).to(DEV)
+    q_dev = torch.from_numpy(q).to(DEV)
+    out = torch.full((L, q.shape[1], D), float("nan"), dtype=torch.float32, device=DEV)
+    lse = torch.full((L, q.shape[1]), float("nan"), dtype=torch.float32, device=DEV) if with_lse else None
+    status = torch.full((1,), 0x7777, dtype=torch.int32, device=DEV)
+    qkv.card_attend(card_dev, desc, q_dev, scale, out, lse=lse, status=status)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), (lse.cpu().numpy() if with_lse else None), int(status.item())
+
+
+def bounds(card, rd, q, scale):
+    kq, vq = ref.unpack_dequant(card, rd)
+    Kf = np.abs(kq.view(np.float16).astype(np.float64))
+    rep = q.shape[1] // rd.kv_heads
+    ds = 0.0
+    for l in range(rd.layers):
+        for hq in range(q.shape[1]):
+            ds = max(ds, float((Kf[l, hq // rep] @ np.abs(q[l, hq].astype(np.float64))).max()))
+    ds *= 128 * 2.0 ** -24 * scale
+    vmax = float(np.abs(vq.view(np.float16).astype(np.float64)).max())
+    base = (rd.tokens + 8) * 2.0 ** -24 + 2.0 ** -21
+    return min((2 * ds + base) * vmax, 1e-4 * max(1.0, vmax)), min(ds + base, 1e-4)
+
+
+def check(L, H, rep, T, G, bits, seed, label, scale=None, kind="llama"):
+    say(label)
+    D = 128
+    scale = D ** -0.5 if scale is None else scale
+    rd, card = build_card(L, H, T, D, G, bits, seed, kind)
+    q = np.random.default_rng(seed + 1).standard_normal((L, H * rep, D)).astype(np.float16)
+    out, lse, st = run_gpu(card, L, H, T, D, G, q, scale)
+    assert st == 0
+    want_o, want_lse = attend_ref.card_attend(card, rd, q, scale)
+    tol_o, tol_lse = bounds(card, rd, q, scale)
+    err_o = float(np.abs(out - want_o).max())
+    err_l = float(np.abs(lse - want_lse).max())
+    print("        max |do| %.3g (bound %.3g)   max |dlse| %.3g (bound %.3g)" % (err_o, tol_o, err_l, tol_lse), flush=True)
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    assert err_o <= tol_o and err_l <= tol_lse
+    return err_o, tol_o
+
+
+@pytest.mark.parametrize("T", [1, 15, 16, 17, 100, 511, 512, 513, 1500])
+def test_token_counts_around_round_and_task_edges(T):
+    bits = qkv_synth.make_bits_uniform_choice(T, 40 + T).numpy()
+    check(2, 2, 4, T, 32, bits, 400 + T, "attend T=%d mixed" % T)
+
+
+@pytest.mark.parametrize("width", [2, 4, 8, 16])
+@pytest.mark.parametrize("G", [32, 64, 128])
+def test_uniform_cards_every_group_size(width, G):
+    T = 700
+    check(1, 3, 4, T, G, np.full(T, width, dtype=np.uint8), 500 + width + G, "attend uniform %d-bit G%d" % (width, G))
+
+
+@pytest.mark.parametrize("rep", [1, 2, 3, 4, 5, 8, 12, 16])
+def test_query_heads_per_kv_head(rep):
+    T = 900
+    bits = qkv_synth.make_bits_uniform_choice(T, 60 + rep).numpy()
+    check(2, 2, rep, T, 32, bits, 600 + rep, "attend rep=%d" % rep)
+
+
+def test_skewed_mixes_empty_classes_and_scales():
+    T = 1100
+    rng = np.random.default_rng(8)
+    for probs in [(0.97, 0.01, 0.01, 0.01), (0.0, 0.5, 0.0, 0.5), (0.0, 0.0, 0.0, 1.0), (0.5, 0.0, 0.5, 0.0)]:
+        bits = rng.choice(np.array([2, 4, 8, 16], dtype=np.uint8), size=T, p=probs)
+        check(1, 2, 4, T, 32, bits, 700, "attend mix %r" % (probs,))
+    bits = qkv_synth.make_bits_uniform_choice(T, 71).numpy()
+    check(1, 2, 4, T, 32, bits, 701, "attend scale 1.0 (peaked softmax)", scale=1.0)
+    check(1, 2, 4, T, 32, bits, 702, "attend scale 0 (uniform weights)", scale=0.0)
+
+
+def test_matches_attention_over_the_gpu_dequantized_cache():
+    # same numbers as running the injection kernel first and attending over the dense cache
+    L, H, rep, T, D, G = 2, 2, 4, 640, 128, 32
+    bits = qkv_synth.make_bits_uniform_choice(T, 81).numpy()
+    rd, card = build_card(L, H, T, D, G, bits, 800)
+    desc = qkv.Desc.make(L, H, T, D, G)
+    card_dev = torch.from_numpy(card).to(DEV)
+    K = torch.empty((L, H, T, D), dtype=torch.float16, device=DEV)
+    V = torch.empty_like(K)
+    qkv.unpack_dequant(card_dev, desc, K, V)
+    q = np.random.default_rng(3).standard_normal((L, H * rep, D)).astype(np.float16)
+    out, lse, st = run_gpu(card, L, H, T, D, G, q, D ** -0.5)
+    o2, l2 = attend_ref.attend_dense(q, K.cpu().numpy(), V.cpu().numpy(), D ** -0.5)
+    tol_o, tol_l = bounds(card, rd, q, D ** -0.5)
+    assert np.abs(out - o2).max() <= tol_o and np.abs(lse - l2).max() <= tol_l
+
+
+def test_bad_header_leaves_outputs_untouched_and_errors_are_reported():
+    L, H, rep, T, D, G = 1, 2, 4, 200, 128, 32
+    bits = qkv_synth.make_bits_uniform_choice(T, 91).numpy()
+    rd, card = build_card(L, H, T, D, G, bits, 900)
+    q = np.zeros((L, H * rep, D), dtype=np.float16)
+    bad = card.copy()
+    bad[0] = ord("X")
+    out, lse, st = run_gpu(bad, L, H, T, D, G, q, 1.0)
+    assert st == qkv.STATUS_BAD_HEADER and np.isnan(out).all() and np.isnan(lse).all()
+    out, lse, st = run_gpu(card, L, H, T, D, G, q, 1.0, with_lse=False)
+    assert st == 0 and np.isfinite(out).all()
+    desc = qkv.Desc.make(L, H, T, D, G)
+    card_dev = torch.from_numpy(card).to(DEV)
+    q_dev = torch.from_numpy(q).to(DEV)
+    o = torch.empty((L, H * rep, D), dtype=torch.float32, device=DEV)
+    with pytest.raises(qkv.QkvError) as e:       # workspace too small
+        qkv.card_attend(card_dev, desc, q_dev, 1.0, o, workspace=torch.empty(64, dtype=torch.uint8, device=DEV))
+    assert e.value.code == -5
+    with pytest.raises(qkv.QkvError) as e:       # 17 query heads per kv head
+        qkv.card_attend_workspace(desc, 34)
+    assert e.value.code == -2
+    with pytest.raises(qkv.QkvError) as e:       # head_dim other than 128
+        qkv.card_attend_workspace(qkv.Desc.make(L, H, T, 64, 32), 8)
+    assert e.value.code == -2
+
+
+def test_benchmark_shape_8k():
+    cfg = qkv_synth.CONFIGS["llama8b_8k_b3"]
+    L, H, T, D, G = cfg["layers"], cfg["kv_heads"], cfg["tokens"], cfg["head_dim"], cfg["group_size"]
+    say("attend 8K: building the card on the GPU")
+    K, V = qkv_synth.make_kv(L, H, T, D, cfg["data_seed"], cfg["kind"], device=DEV)
+    scores = qkv_synth.make_scores(T, cfg["bits"][1], DEV)
+    bits, counts = qkv.assign_bits(scores, cfg["bits"][2])
+    desc = qkv.Desc.make(L, H, T, D, G)
+    card_dev = torch.empty(qkv.card_bytes(desc, counts), dtype=torch.uint8, device=DEV)
+    qkv.quantize_pack(desc, K, V, bits, counts, card_dev)
+    rep = 4
+    q = np.random.default_rng(5).standard_normal((L, H * rep, D)).astype(np.float16)
+    out = torch.empty((L, H * rep, D), dtype=torch.float32, device=DEV)
+    lse = torch.empty((L, H * rep), dtype=torch.float32, device=DEV)
+    status = torch.ones(1, dtype=torch.int32, device=DEV)
+    qkv.card_attend(card_dev, desc, torch.from_numpy(q).to(DEV), D ** -0.5, out, lse=lse, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    say("attend 8K: oracle")
+    rd = ref.make_desc(L, H, T, D, G)
+    # the oracle's own card from the same seeded inputs (never the GPU's)
+    want_bits, want_counts = ref.assign_bits(qkv_synth.make_scores(T, cfg["bits"][1]).numpy(), cfg["bits"][2])
+    card = ref.quantize_pack(rd, K.cpu().numpy(), V.cpu().numpy(), want_bits, want_counts)
+    want_o, want_lse = attend_ref.card_attend(card, rd, q, D ** -0.5)
+    tol_o, tol_l = bounds(card, rd, q, D ** -0.5)
+    err_o = float(np.abs(out.cpu().numpy() - want_o).max())
+    err_l = float(np.abs(lse.cpu().numpy() - want_lse).max())
+    print("        max |do| %.3g (bound %.3g)   max |dlse| %.3g (bound %.3g)" % (err_o, tol_o, err_l, tol_l), flush=True)
+    assert err_o <= tol_o and err_l <= tol_l
