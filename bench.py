@@ -151,6 +151,32 @@ def main():
     _, c2, avg_bits, status = qkv.card_peek(card)
     assert status == 0 and c2 == counts, (status, c2, counts)
 
+    # beyond the handoff itself: one decode step's attention taken directly over the card
+    # (32 query heads on 8 kv heads as in Llama-3.1-8B), timed on its own
+    attend = None
+    if D == 128:
+        rep = 4
+        qv = qkv_synth.normal(cfg["data_seed"] + 17, 9, 0, L * H * rep * D, dev).view(L, H * rep, D).to(torch.float16)
+        a_out = torch.empty((L, H * rep, D), dtype=torch.float32, device=dev)
+        a_lse = torch.empty((L, H * rep), dtype=torch.float32, device=dev)
+        ws = torch.empty(qkv.card_attend_workspace(desc, H * rep), dtype=torch.uint8, device=dev)
+        for _ in range(max(3, args.warmup // 4)):
+            qkv.card_attend(card, desc, qv, D ** -0.5, a_out, lse=a_lse, workspace=ws)
+        n_att = max(10, args.steps // 4)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(n_att):
+            qkv.card_attend(card, desc, qv, D ** -0.5, a_out, lse=a_lse, workspace=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        att_ms = e0.elapsed_time(e1) / n_att
+        att_bytes = card_bytes + qv.numel() * 2 + a_out.numel() * 4 + a_lse.numel() * 4
+        attend = {"call": "qkv_card_attend", "q_heads": H * rep, "avg_ms": round(att_ms, 4), "calls": n_att,
+                  "algorithmic_bytes": att_bytes, "achieved_gbs": round(att_bytes / (att_ms * 1e-3) / 1e9, 1),
+                  "frac_hbm_peak": round(att_bytes / (att_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                  "dense_cache_gbs_equivalent": round(kv_bytes / (att_ms * 1e-3) / 1e9, 1)}
+
     # plain device copy of the same fp16 bytes: what this machine's HBM gives a kernel with no arithmetic
     for _ in range(3):
         K_out.copy_(K)
@@ -191,6 +217,7 @@ def main():
         "pct_hbm_peak": {"quantize_pack": round(100 * legs[0]["frac"], 2), "unpack_dequant": round(100 * legs[1]["frac"], 2)},
         "ms_per_step_with_events": round(ms_per_step_events, 4),
         "copy_ceiling_gbs": round(copy_gbs, 1),
+        "card_attend": attend,
     }
     if not args.no_cpu:
         layers = args.cpu_layers if args.cpu_layers > 0 else (L * 8192) // max(T, 8192)

@@ -31,6 +31,13 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRoundTokens = 16;
+#ifndef QKV_ATTEND_HEADS_PER_PASS
+#define QKV_ATTEND_HEADS_PER_PASS 2
+#endif
+constexpr int kHeadsPerPass = QKV_ATTEND_HEADS_PER_PASS;   // 1, 2 or 4
+// Rounds whose loads are in flight ahead of the arithmetic: as many as the registers allow
+// (a fetched span is 3 / 5 / 9 / 16 registers at 2 / 4 / 8 / 16 bits).
+template <int W> struct Prefetch { static constexpr int kRounds = (W == 2) ? 4 : (W == 4) ? 3 : (W == 8) ? 2 : 1; };
 constexpr int kLdsFloatsPerWave = 2048;      // scores of one task: chunk tokens x padded query heads
 
 struct AttendArgs {
@@ -143,6 +150,7 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   const uint64_t v_row0 = (uint64_t)(lh + pair) * n_c;
   const uint32_t cnt = j1 - j0;
   const uint32_t rounds = (cnt + kRoundTokens - 1) / kRoundTokens;
+  constexpr int kPrefetch = Prefetch<W>::kRounds;
 
   // ---- q as MFMA A operands: row m = lane % 16 is query head m of this kv head, the lane holds
   // q[m][32 kq .. 32 kq + 31]; operand j is q[m][32 kq + 4 j .. + 3]
@@ -164,31 +172,42 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
     }
   }
 
-  // ---- scores: lds[token * R4 + head] in log2 units, -inf for tokens past the task's end
+  // ---- scores: lds[token * R4 + head] in log2 units, -inf for tokens past the task's end.
+  // The loads of the next kPrefetch rounds are always in flight.
   {
-    SpanData<W, G> cur = fetch_span<W, G>(a.card, g, c, k_row0 + j0 + n, kq, n < cnt);
-    for (uint32_t rd = 0; rd < rounds; ++rd) {
-      const uint32_t tn = (rd + 1) * kRoundTokens + n;
-      SpanData<W, G> nxt = fetch_span<W, G>(a.card, g, c, k_row0 + j0 + tn, kq, tn < cnt);   // next round's loads in flight
-      uint32_t kb[16];
-      decode_fetched<W, G>(cur, kb);
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    SpanData<W, G> buf[kPrefetch];
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        acc = __builtin_amdgcn_mfma_f32_16x16x16f16(qa[j], __builtin_bit_cast(f16x4, (u32x2){kb[2 * j], kb[2 * j + 1]}),
-                                                    acc, 0, 0, 0);
-      // the lane holds heads 4 kq .. 4 kq + 3 of token n
-      const uint32_t t = rd * kRoundTokens + n;
-      if (4u * kq < R4) {
-        const bool live = t < cnt;
-        f32x4 sc;
-        sc.x = live ? acc.x * a.scale_log2 : -INFINITY;
-        sc.y = live ? acc.y * a.scale_log2 : -INFINITY;
-        sc.z = live ? acc.z * a.scale_log2 : -INFINITY;
-        sc.w = live ? acc.w * a.scale_log2 : -INFINITY;
-        *reinterpret_cast<f32x4*>(lds + t * R4 + 4u * kq) = sc;
+    for (int u = 0; u < kPrefetch; ++u) {
+      const uint32_t t = u * kRoundTokens + n;
+      buf[u] = fetch_span<W, G>(a.card, g, c, k_row0 + j0 + t, kq, t < cnt);
+    }
+    for (uint32_t rd0 = 0; rd0 < rounds; rd0 += kPrefetch) {
+#pragma unroll
+      for (int u = 0; u < kPrefetch; ++u) {
+        const uint32_t rd = rd0 + u;
+        if (rd < rounds) {                         // uniform over the wave
+          uint32_t kb[16];
+          decode_fetched<W, G>(buf[u], kb);
+          const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
+          buf[u] = fetch_span<W, G>(a.card, g, c, k_row0 + j0 + tn, kq, tn < cnt);
+          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            acc = __builtin_amdgcn_mfma_f32_16x16x16f16(qa[j], __builtin_bit_cast(f16x4, (u32x2){kb[2 * j], kb[2 * j + 1]}),
+                                                        acc, 0, 0, 0);
+          // the lane holds heads 4 kq .. 4 kq + 3 of token n
+          const uint32_t t = rd * kRoundTokens + n;
+          if (4u * kq < R4) {
+            const bool live = t < cnt;
+            f32x4 sc;
+            sc.x = live ? acc.x * a.scale_log2 : -INFINITY;
+            sc.y = live ? acc.y * a.scale_log2 : -INFINITY;
+            sc.z = live ? acc.z * a.scale_log2 : -INFINITY;
+            sc.w = live ? acc.w * a.scale_log2 : -INFINITY;
+            *reinterpret_cast<f32x4*>(lds + t * R4 + 4u * kq) = sc;
+          }
+        }
       }
-      cur = nxt;
     }
   }
 
@@ -211,34 +230,46 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
     }
   }
 
-  // ---- values: four query heads at a time
-  for (uint32_t hg = 0; hg < R4; hg += 4) {
-    float acc[4][32];
+  // ---- values: kHeadsPerPass query heads at a time (their 32 x kHeadsPerPass accumulators
+  // are what limits the number of waves per SIMD)
+  for (uint32_t hg = 0; hg < R; hg += kHeadsPerPass) {
+    float acc[kHeadsPerPass][32];
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
+    for (int r = 0; r < kHeadsPerPass; ++r)
 #pragma unroll
       for (int i = 0; i < 32; ++i) acc[r][i] = 0.f;
-    SpanData<W, G> cur = fetch_span<W, G>(a.card, g, c, v_row0 + j0 + n, kq, n < cnt);
-    for (uint32_t rd = 0; rd < rounds; ++rd) {
-      const uint32_t tn = (rd + 1) * kRoundTokens + n;
-      SpanData<W, G> nxt = fetch_span<W, G>(a.card, g, c, v_row0 + j0 + tn, kq, tn < cnt);
-      uint32_t vb[16];
-      decode_fetched<W, G>(cur, vb);
-      const f32x4 p = *reinterpret_cast<const f32x4*>(lds + (rd * kRoundTokens + n) * R4 + hg);
-      const float pr[4] = {p.x, p.y, p.z, p.w};
+    SpanData<W, G> buf[kPrefetch];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
+    for (int u = 0; u < kPrefetch; ++u) {
+      const uint32_t t = u * kRoundTokens + n;
+      buf[u] = fetch_span<W, G>(a.card, g, c, v_row0 + j0 + t, kq, t < cnt);
+    }
+    for (uint32_t rd0 = 0; rd0 < rounds; rd0 += kPrefetch) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          fma_lo(acc[r][2 * i], vb[i], pr[r]);
-          fma_hi(acc[r][2 * i + 1], vb[i], pr[r]);
+      for (int u = 0; u < kPrefetch; ++u) {
+        const uint32_t rd = rd0 + u;
+        if (rd < rounds) {
+          uint32_t vb[16];
+          decode_fetched<W, G>(buf[u], vb);
+          const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
+          buf[u] = fetch_span<W, G>(a.card, g, c, v_row0 + j0 + tn, kq, tn < cnt);
+          float pr[kHeadsPerPass];
+#pragma unroll
+          for (int r = 0; r < kHeadsPerPass; ++r) pr[r] = lds[(rd * kRoundTokens + n) * R4 + hg + r];   // hg + r < R4
+#pragma unroll
+          for (int r = 0; r < kHeadsPerPass; ++r) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              fma_lo(acc[r][2 * i], vb[i], pr[r]);
+              fma_hi(acc[r][2 * i + 1], vb[i], pr[r]);
+            }
+          }
         }
       }
-      cur = nxt;
     }
     // sum over the 16 token lanes of each quarter, then lane n = 0 of the quarter writes 32 dims
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < kHeadsPerPass; ++r) {
 #pragma unroll
       for (int i = 0; i < 32; ++i) {
         float v = acc[r][i];
@@ -251,7 +282,7 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
     }
     if (n == 0) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
+      for (int r = 0; r < kHeadsPerPass; ++r) {
         if (hg + r < R) {
           f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + hg + r) * 128u + 32u * kq);
 #pragma unroll
@@ -263,7 +294,8 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
 }
 
 template <int G>
-__global__ __launch_bounds__(kBlockThreads) void attend_kernel(AttendArgs a) {
+__global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2)))
+void attend_kernel(AttendArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[kWavesPerBlock][kLdsFloatsPerWave];
   CardGeom g;
   if (!card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, g))
