@@ -18,9 +18,10 @@
 //            (the k index of the MFMA is a fixed permutation of the head dimension, applied to
 //            q and K^ alike).  Scores go to LDS.
 //   softmax  one maximum per head over the task's tokens, p = exp2(s - m) back into LDS.
-//   values   the lane decodes its span of V^ and accumulates p.V^ for 4 query heads in 128
-//            fp32 registers (fp16 operand read in place by v_fma_mix_f32); at the end the 16
-//            token lanes of each quarter are summed with DPP moves.
+//   values   the round's packed V rows are regrouped through LDS (still packed) so that a lane
+//            holds 4 consecutive tokens x 8 dimensions, decodes them into 8 MFMA B operands,
+//            and 2 x 8 MFMAs (softmax weights split into a high and a low fp16 part)
+//            accumulate p.V^ for 16 tokens x up to 16 query heads.
 #include "qkv_common.h"
 #include "qkv_decode.h"
 
@@ -31,14 +32,13 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRoundTokens = 16;
-#ifndef QKV_ATTEND_HEADS_PER_PASS
-#define QKV_ATTEND_HEADS_PER_PASS 2
-#endif
-constexpr int kHeadsPerPass = QKV_ATTEND_HEADS_PER_PASS;   // 1, 2 or 4
 // Rounds whose loads are in flight ahead of the arithmetic: as many as the registers allow
 // (a fetched span is 3 / 5 / 9 / 16 registers at 2 / 4 / 8 / 16 bits).
 template <int W> struct Prefetch { static constexpr int kRounds = (W == 2) ? 4 : (W == 4) ? 3 : (W == 8) ? 2 : 1; };
-constexpr int kLdsFloatsPerWave = 2048;      // scores of one task: chunk tokens x padded query heads
+#ifndef QKV_ATTEND_LDS_FLOATS
+#define QKV_ATTEND_LDS_FLOATS 2048
+#endif
+constexpr int kLdsFloatsPerWave = QKV_ATTEND_LDS_FLOATS;   // scores of one task: chunk tokens x padded query heads
 
 struct AttendArgs {
   const uint8_t* card;
@@ -57,19 +57,6 @@ struct AttendArgs {
   float* lse;              // fp32 [L][Hq] or null
   uint32_t* status;        // or null
 };
-
-template <int CTRL>
-__device__ inline float dpp_f(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
-}
-
-// acc += f32(low / high half of w) * p
-__device__ inline void fma_lo(float& acc, uint32_t w, float p) {
-  asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "+v"(acc) : "v"(w), "v"(p));
-}
-__device__ inline void fma_hi(float& acc, uint32_t w, float p) {
-  asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "+v"(acc) : "v"(w), "v"(p));
-}
 
 __device__ inline float wave_max(float v) {
 #pragma unroll
@@ -138,12 +125,64 @@ __device__ inline void decode_fetched(const SpanData<W, G>& d, uint32_t (&out)[1
   }
 }
 
+// ---- value pass helpers -----------------------------------------------------------------------
+//
+// For the weighted sum the MFMA contracts over tokens, so a lane must hold, for one output
+// dimension, the values of four consecutive tokens.  The round's 16 rows are therefore loaded
+// as they lie (lane (n, kq) = token n, quarter kq), dropped into LDS still packed, and picked
+// up again by lane (a, kt) as the pieces "token 4 kt + i, dimensions 8 a .. 8 a + 7", i = 0..3.
+// Operand e of the round is then B_e[token][a] = V^[token][8 a + e], and eight MFMAs give
+// out[head][8 a + e] for 16 heads at once.  Only packed codes cross LDS, never decoded values.
+
+template <int W> struct Piece { uint32_t w[W == 16 ? 4 : (W == 8 ? 2 : 1)]; };
+
+// float values of the 8 codes of pieces i0 and i0+1 (W = 2: two 16-bit pieces share the masks)
+template <int W>
+__device__ inline void piece_codes(const Piece<W>& p0, const Piece<W>& p1, float (&c0)[8], float (&c1)[8]) {
+  if constexpr (W == 2) {
+    const uint32_t both = (p0.w[0] & 0xFFFFu) | (p1.w[0] << 16);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {                       // byte layout of m: [p0 code k, p0 code 4+k, p1 code k, p1 code 4+k]
+      const uint32_t m = (both >> (2 * k)) & 0x03030303u;
+      c0[k] = byte_to_float(m, 0); c0[4 + k] = byte_to_float(m, 1);
+      c1[k] = byte_to_float(m, 2); c1[4 + k] = byte_to_float(m, 3);
+    }
+  } else if constexpr (W == 4) {
+    const uint32_t e0 = p0.w[0] & 0x0F0F0F0Fu, o0 = (p0.w[0] >> 4) & 0x0F0F0F0Fu;
+    const uint32_t e1 = p1.w[0] & 0x0F0F0F0Fu, o1 = (p1.w[0] >> 4) & 0x0F0F0F0Fu;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      c0[2 * j] = byte_to_float(e0, j); c0[2 * j + 1] = byte_to_float(o0, j);
+      c1[2 * j] = byte_to_float(e1, j); c1[2 * j + 1] = byte_to_float(o1, j);
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      c0[j] = byte_to_float(p0.w[0], j); c0[4 + j] = byte_to_float(p0.w[1], j);
+      c1[j] = byte_to_float(p1.w[0], j); c1[4 + j] = byte_to_float(p1.w[1], j);
+    }
+  }
+}
+
+// fp16(fma(c0, s0, z0)) | fp16(fma(c1, s1, z1)) << 16: the two roundings of the decoder, two tokens at once
+__device__ inline uint32_t decode_two_tokens(float c0, float s0, float z0, float c1, float s1, float z1) {
+  float x = __builtin_fmaf(c0, s0, z0);
+  float y = __builtin_fmaf(c1, s1, z1);
+  asm("" : "+v"(x));
+  asm("" : "+v"(y));
+  const f32x2 v = {x, y};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
+
 // One task: rows [j0, j1) of class c for the pair (layer, kv head) = pair.
+// lds: scores / weights as [head][chunk] floats (R4 * chunk <= kLdsFloatsPerWave);
+// tile: the round's packed rows (16 tokens x up to 256 bytes) followed by 16 x 4 pairs.
 template <int W, int G>
 __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c, uint32_t pair, uint32_t j0, uint32_t j1,
-                                   uint32_t lane, float* lds, uint64_t part) {
-  const uint32_t n = lane & 15u, kq = lane >> 4;
+                                   uint32_t lane, float* lds, uint8_t* tile, uint64_t part) {
+  const uint32_t n = lane & 15u, kq = lane >> 4;          // also (a, kt) of the value pass and (m, k group) of the MFMAs
   const uint32_t R = a.rep, R4 = (R + 3u) & ~3u;
+  const uint32_t chunk = a.chunk;
   const uint32_t lh = g.planes >> 1;
   const uint32_t n_c = g.n[c];
   const uint64_t k_row0 = (uint64_t)pair * n_c;            // K plane p = pair, V plane p = L*H + pair
@@ -172,7 +211,7 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
     }
   }
 
-  // ---- scores: lds[token * R4 + head] in log2 units, -inf for tokens past the task's end.
+  // ---- scores: lds[head * chunk + token] in log2 units, -inf for tokens past the task's end.
   // The loads of the next kPrefetch rounds are always in flight.
   {
     SpanData<W, G> buf[kPrefetch];
@@ -199,45 +238,44 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
           const uint32_t t = rd * kRoundTokens + n;
           if (4u * kq < R4) {
             const bool live = t < cnt;
-            f32x4 sc;
-            sc.x = live ? acc.x * a.scale_log2 : -INFINITY;
-            sc.y = live ? acc.y * a.scale_log2 : -INFINITY;
-            sc.z = live ? acc.z * a.scale_log2 : -INFINITY;
-            sc.w = live ? acc.w * a.scale_log2 : -INFINITY;
-            *reinterpret_cast<f32x4*>(lds + t * R4 + 4u * kq) = sc;
+            float* dst = lds + (4u * kq) * chunk + t;
+            dst[0] = live ? acc.x * a.scale_log2 : -INFINITY;
+            dst[chunk] = live ? acc.y * a.scale_log2 : -INFINITY;
+            dst[2 * chunk] = live ? acc.z * a.scale_log2 : -INFINITY;
+            dst[3 * chunk] = live ? acc.w * a.scale_log2 : -INFINITY;
           }
         }
       }
     }
   }
 
-  // ---- softmax over the task's tokens, head by head (the wave's own LDS writes are in order)
+  // ---- softmax over the task's tokens, head by head (the wave's own LDS accesses are in order)
   const uint32_t slots = rounds * kRoundTokens;
-  for (uint32_t r = 0; r < R; ++r) {
+  for (uint32_t r = 0; r < R4; ++r) {
+    float* row = lds + r * chunk;
     float m = -INFINITY;
-    for (uint32_t t = lane; t < slots; t += kWaveSize) m = fmaxf(m, lds[t * R4 + r]);
+    for (uint32_t t = lane; t < slots; t += kWaveSize) m = fmaxf(m, row[t]);
     m = wave_max(m);
     float l = 0.f;
     for (uint32_t t = lane; t < slots; t += kWaveSize) {
-      const float p = __builtin_amdgcn_exp2f(lds[t * R4 + r] - m);
-      lds[t * R4 + r] = p;
+      const float p = __builtin_amdgcn_exp2f(row[t] - m);
+      row[t] = p;
       l += p;
     }
     l = wave_sum(l);
-    if (lane == 0) {
+    if (lane == 0 && r < R) {
       a.part_ml[(part * R + r) * 2] = m;
       a.part_ml[(part * R + r) * 2 + 1] = l;
     }
   }
 
-  // ---- values: kHeadsPerPass query heads at a time (their 32 x kHeadsPerPass accumulators
-  // are what limits the number of waves per SIMD)
-  for (uint32_t hg = 0; hg < R; hg += kHeadsPerPass) {
-    float acc[kHeadsPerPass][32];
+  // ---- values
+  constexpr uint32_t kRowBytes = 16u * W;                 // one token's packed row
+  uint32_t* pairs_lds = reinterpret_cast<uint32_t*>(tile + 16u * 256u);
+  f32x4 acc_hi[8], acc_lo[8];
 #pragma unroll
-    for (int r = 0; r < kHeadsPerPass; ++r)
-#pragma unroll
-      for (int i = 0; i < 32; ++i) acc[r][i] = 0.f;
+  for (int e = 0; e < 8; ++e) { acc_hi[e] = (f32x4){0.f, 0.f, 0.f, 0.f}; acc_lo[e] = (f32x4){0.f, 0.f, 0.f, 0.f}; }
+  {
     SpanData<W, G> buf[kPrefetch];
 #pragma unroll
     for (int u = 0; u < kPrefetch; ++u) {
@@ -249,46 +287,90 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
       for (int u = 0; u < kPrefetch; ++u) {
         const uint32_t rd = rd0 + u;
         if (rd < rounds) {
-          uint32_t vb[16];
-          decode_fetched<W, G>(buf[u], vb);
+          // rows into LDS as they were loaded: token n, quarter kq
+          {
+            uint8_t* dst = tile + n * kRowBytes + kq * (4u * W);
+            if constexpr (W == 2) {
+              *reinterpret_cast<u32x2*>(dst) = (u32x2){buf[u].cw[0], buf[u].cw[1]};
+            } else {
+#pragma unroll
+              for (int h = 0; h < (W == 16 ? 16 : W) / 4; ++h)
+                reinterpret_cast<u32x4*>(dst)[h] = (u32x4){buf[u].cw[4 * h], buf[u].cw[4 * h + 1], buf[u].cw[4 * h + 2], buf[u].cw[4 * h + 3]};
+            }
+            if constexpr (W != 16) pairs_lds[n * 4u + kq] = buf[u].pair;
+          }
           const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
           buf[u] = fetch_span<W, G>(a.card, g, c, v_row0 + j0 + tn, kq, tn < cnt);
-          float pr[kHeadsPerPass];
+
+          // pieces of lane (a, kt) = (n, kq): tokens 4 kt + i, dimensions 8 a .. 8 a + 7
+          Piece<W> pc[4];
+          uint32_t pr[4];
 #pragma unroll
-          for (int r = 0; r < kHeadsPerPass; ++r) pr[r] = lds[(rd * kRoundTokens + n) * R4 + hg + r];   // hg + r < R4
+          for (int i = 0; i < 4; ++i) {
+            const uint8_t* src = tile + (4u * kq + i) * kRowBytes + n * W;
+            if constexpr (W == 2) pc[i].w[0] = *reinterpret_cast<const uint16_t*>(src);
+            else if constexpr (W == 4) pc[i].w[0] = *reinterpret_cast<const uint32_t*>(src);
+            else if constexpr (W == 8) { const u32x2 t = *reinterpret_cast<const u32x2*>(src); pc[i].w[0] = t.x; pc[i].w[1] = t.y; }
+            else { const u32x4 t = *reinterpret_cast<const u32x4*>(src); pc[i].w[0] = t.x; pc[i].w[1] = t.y; pc[i].w[2] = t.z; pc[i].w[3] = t.w; }
+            pr[i] = (W != 16) ? pairs_lds[(4u * kq + i) * 4u + (n >> 2)] : 0u;
+          }
+          // B operands: b[e] = {V^[4kt][8a+e], V^[4kt+1][8a+e], V^[4kt+2][8a+e], V^[4kt+3][8a+e]}
+          u32x2 b[8];
+          if constexpr (W == 16) {
 #pragma unroll
-          for (int r = 0; r < kHeadsPerPass; ++r) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              fma_lo(acc[r][2 * i], vb[i], pr[r]);
-              fma_hi(acc[r][2 * i + 1], vb[i], pr[r]);
+            for (int e = 0; e < 8; ++e) {
+              const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;      // high or low halves of two words
+              b[e].x = __builtin_amdgcn_perm(pc[1].w[e >> 1], pc[0].w[e >> 1], sel);
+              b[e].y = __builtin_amdgcn_perm(pc[3].w[e >> 1], pc[2].w[e >> 1], sel);
             }
+          } else {
+            float c0[8], c1[8], c2[8], c3[8];
+            piece_codes<W>(pc[0], pc[1], c0, c1);
+            piece_codes<W>(pc[2], pc[3], c2, c3);
+            const float s0 = half_bits_to_float(pr[0] & 0xFFFFu), z0 = half_bits_to_float(pr[0] >> 16);
+            const float s1 = half_bits_to_float(pr[1] & 0xFFFFu), z1 = half_bits_to_float(pr[1] >> 16);
+            const float s2 = half_bits_to_float(pr[2] & 0xFFFFu), z2 = half_bits_to_float(pr[2] >> 16);
+            const float s3 = half_bits_to_float(pr[3] & 0xFFFFu), z3 = half_bits_to_float(pr[3] >> 16);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              b[e].x = decode_two_tokens(c0[e], s0, z0, c1[e], s1, z1);
+              b[e].y = decode_two_tokens(c2[e], s2, z2, c3[e], s3, z3);
+            }
+          }
+          // A operands: the weights of head m = n for tokens 4 kt .. 4 kt + 3, scaled by 2^14 so that
+          // fp16 holds them as normal numbers, split into a high part and a low part scaled by 2^11
+          f32x4 pw = {0.f, 0.f, 0.f, 0.f};
+          if (n < R4) pw = *reinterpret_cast<const f32x4*>(lds + n * chunk + rd * kRoundTokens + 4u * kq);
+          pw *= 16384.0f;
+          const f16x2 h01 = __builtin_convertvector((f32x2){pw.x, pw.y}, f16x2);
+          const f16x2 h23 = __builtin_convertvector((f32x2){pw.z, pw.w}, f16x2);
+          const f32x2 r01 = (f32x2){pw.x, pw.y} - __builtin_convertvector(h01, f32x2);
+          const f32x2 r23 = (f32x2){pw.z, pw.w} - __builtin_convertvector(h23, f32x2);
+          const f16x2 l01 = __builtin_convertvector(r01 * 2048.0f, f16x2);
+          const f16x2 l23 = __builtin_convertvector(r23 * 2048.0f, f16x2);
+          const f16x4 a_hi = {h01.x, h01.y, h23.x, h23.y};
+          const f16x4 a_lo = {l01.x, l01.y, l23.x, l23.y};
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const f16x4 be = __builtin_bit_cast(f16x4, b[e]);
+            acc_hi[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(a_hi, be, acc_hi[e], 0, 0, 0);
+            acc_lo[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(a_lo, be, acc_lo[e], 0, 0, 0);
           }
         }
       }
     }
-    // sum over the 16 token lanes of each quarter, then lane n = 0 of the quarter writes 32 dims
+  }
+  // the lane holds out[heads 4 kq .. 4 kq + 3][dimensions 8 n .. 8 n + 7]
 #pragma unroll
-    for (int r = 0; r < kHeadsPerPass; ++r) {
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t r = 4u * kq + i;
+    if (r < R) {
+      float o[8];
 #pragma unroll
-      for (int i = 0; i < 32; ++i) {
-        float v = acc[r][i];
-        v += dpp_f<0xB1>(v);      // quad_perm [1,0,3,2]
-        v += dpp_f<0x4E>(v);      // quad_perm [2,3,0,1]
-        v += dpp_f<0x141>(v);     // row_half_mirror
-        v += dpp_f<0x140>(v);     // row_mirror
-        acc[r][i] = v;
-      }
-    }
-    if (n == 0) {
-#pragma unroll
-      for (int r = 0; r < kHeadsPerPass; ++r) {
-        if (hg + r < R) {
-          f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + hg + r) * 128u + 32u * kq);
-#pragma unroll
-          for (int i = 0; i < 8; ++i) dst[i] = (f32x4){acc[r][4 * i], acc[r][4 * i + 1], acc[r][4 * i + 2], acc[r][4 * i + 3]};
-        }
-      }
+      for (int e = 0; e < 8; ++e) o[e] = (acc_hi[e][i] + acc_lo[e][i] * (1.0f / 2048.0f)) * (1.0f / 16384.0f);
+      f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + r) * 128u + 8u * n);
+      dst[0] = (f32x4){o[0], o[1], o[2], o[3]};
+      dst[1] = (f32x4){o[4], o[5], o[6], o[7]};
     }
   }
 }
@@ -297,6 +379,7 @@ template <int G>
 __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2)))
 void attend_kernel(AttendArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[kWavesPerBlock][kLdsFloatsPerWave];
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[kWavesPerBlock][16 * 256 + 16 * 16];
   CardGeom g;
   if (!card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, g))
     return;                                   // uniform over the grid
@@ -333,10 +416,11 @@ void attend_kernel(AttendArgs a) {
     return;
   }
   float* my_lds = lds[wave];
-  if (cls == 0) attend_task<2, G>(a, g, 0, pair, j0, j1, lane, my_lds, part);
-  if (cls == 1) attend_task<4, G>(a, g, 1, pair, j0, j1, lane, my_lds, part);
-  if (cls == 2) attend_task<8, G>(a, g, 2, pair, j0, j1, lane, my_lds, part);
-  if (cls == 3) attend_task<16, G>(a, g, 3, pair, j0, j1, lane, my_lds, part);
+  uint8_t* my_tile = tiles[wave];
+  if (cls == 0) attend_task<2, G>(a, g, 0, pair, j0, j1, lane, my_lds, my_tile, part);
+  if (cls == 1) attend_task<4, G>(a, g, 1, pair, j0, j1, lane, my_lds, my_tile, part);
+  if (cls == 2) attend_task<8, G>(a, g, 2, pair, j0, j1, lane, my_lds, my_tile, part);
+  if (cls == 3) attend_task<16, G>(a, g, 3, pair, j0, j1, lane, my_lds, my_tile, part);
 }
 
 // Merges the partials of one (layer, query head): thread d owns output dimension d.

@@ -112,6 +112,32 @@ def test_skewed_mixes_empty_classes_and_scales():
     check(1, 2, 4, T, 32, bits, 702, "attend scale 0 (uniform weights)", scale=0.0)
 
 
+def test_many_tiny_weights_still_count():
+    # one dominant token and thousands of tokens whose weights span 1e-4 .. 1e-11 but whose values are
+    # large: the small weights must not be lost (they pass through fp16 operands inside the kernel)
+    L, H, rep, T, D, G = 1, 1, 4, 4096, 128, 32
+    rng = np.random.default_rng(12)
+    K = np.zeros((L, H, T, D), dtype=np.float16)
+    V = (rng.standard_normal((L, H, T, D)) * 500).astype(np.float16)
+    K[0, 0, 1:, 0] = -rng.uniform(9.0, 25.0, size=T - 1).astype(np.float16)      # scores -9 .. -25 against token 0's 0
+    V[0, 0, 0] = 1.0
+    q = np.zeros((L, H * rep, D), dtype=np.float16)
+    q[:, :, 0] = 1.0
+    bits = np.full(T, 16, dtype=np.uint8)                                        # raw rows: K^ = K exactly
+    rd = ref.make_desc(L, H, T, D, G)
+    card = ref.quantize_pack(rd, K, V, bits, [0, 0, 0, T])
+    say("attend: many tiny weights")
+    out, lse, st = run_gpu(card, L, H, T, D, G, q, 1.0)
+    want_o, want_lse = attend_ref.card_attend(card, rd, q, 1.0)
+    assert st == 0
+    # the tail carries a visible share of the result
+    assert np.abs(want_o[0, 0] - 1.0).max() > 1e-2
+    err = float(np.abs(out - want_o).max())
+    print("        max |do| %.3g, |o| up to %.3g" % (err, float(np.abs(want_o).max())), flush=True)
+    assert err <= 2e-5 * float(np.abs(want_o).max()) + 1e-6
+    assert np.abs(lse - want_lse).max() <= 1e-5
+
+
 def test_matches_attention_over_the_gpu_dequantized_cache():
     # same numbers as running the injection kernel first and attending over the dense cache
     L, H, rep, T, D, G = 2, 2, 4, 640, 128, 32
