@@ -56,6 +56,7 @@ struct AttendArgs {
   float* out;              // fp32 [L][Hq][D]
   float* lse;              // fp32 [L][Hq] or null
   uint32_t* status;        // or null
+  uint32_t* valid;         // one word of the workspace: 1 when the header was accepted
 };
 
 __device__ inline float wave_max(float v) {
@@ -423,39 +424,59 @@ void attend_kernel(AttendArgs a) {
   if (cls == 3) attend_task<16, G>(a, g, 3, pair, j0, j1, lane, my_lds, my_tile, part);
 }
 
-// Merges the partials of one (layer, query head): thread d owns output dimension d.
+// Merges the partials of one (layer, query head): thread d owns output dimension d.  The
+// (m, l) pairs of all tasks are first gathered into LDS by parallel loads, so that the
+// weights cost no chain of dependent global loads.
+constexpr int kMergeBatch = 256;             // tasks whose (m, l) are held in LDS at a time
+
 __global__ __launch_bounds__(128) void attend_merge_kernel(AttendArgs a) {
-  CardGeom g;
-  if (!card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, g))
-    return;
+  __shared__ float ml_m[kMergeBatch], ml_l[kMergeBatch];
+  if (*a.valid == 0) return;                           // header refused: outputs stay untouched
   const uint32_t d = threadIdx.x;
   const uint32_t lq = blockIdx.x;                      // l * Hq + hq
   const uint32_t l = lq / a.q_heads, hq = lq - l * a.q_heads;
   const uint32_t h = hq / a.rep, r = hq - h * a.rep;
   const uint64_t part0 = (uint64_t)(l * a.kv_heads + h) * a.max_tasks;
-  float M = -INFINITY;
-  for (uint32_t t = 0; t < a.max_tasks; ++t) {
-    const float* ml = a.part_ml + ((part0 + t) * a.rep + r) * 2;
-    if (ml[1] > 0.f) M = fmaxf(M, ml[0]);
-  }
-  float den = 0.f, num = 0.f;
-  for (uint32_t t = 0; t < a.max_tasks; ++t) {
-    const float* ml = a.part_ml + ((part0 + t) * a.rep + r) * 2;
-    if (ml[1] > 0.f) {
-      const float w = __builtin_amdgcn_exp2f(ml[0] - M);
-      den += w * ml[1];
-      num += w * a.part_o[((part0 + t) * a.rep + r) * 128u + d];
+  float M = -INFINITY, den = 0.f, num = 0.f;           // running maximum, and sums relative to it
+  for (uint32_t t0 = 0; t0 < a.max_tasks; t0 += kMergeBatch) {
+    const uint32_t nb = min((uint32_t)kMergeBatch, a.max_tasks - t0);
+    __syncthreads();
+    for (uint32_t t = d; t < nb; t += 128) {
+      const float* ml = a.part_ml + ((part0 + t0 + t) * a.rep + r) * 2;
+      ml_m[t] = ml[0];
+      ml_l[t] = ml[1];
+    }
+    __syncthreads();
+    float Mb = M;
+    for (uint32_t t = 0; t < nb; ++t) if (ml_l[t] > 0.f) Mb = fmaxf(Mb, ml_m[t]);
+    if (Mb == -INFINITY) continue;                     // nothing but empty tasks so far (uniform over the block)
+    const float rescale = __builtin_amdgcn_exp2f(M - Mb);   // 0 when M is still -inf
+    den *= rescale;
+    num *= rescale;
+    M = Mb;
+    // loads first, unconditionally (an empty task's slot holds anything: it is read but not used)
+#pragma unroll 8
+    for (uint32_t t = 0; t < nb; ++t) {
+      const float v = a.part_o[((part0 + t0 + t) * a.rep + r) * 128u + d];
+      const float lt = ml_l[t];
+      const float w = __builtin_amdgcn_exp2f(ml_m[t] - M);
+      den += (lt > 0.f) ? w * lt : 0.f;
+      num += (lt > 0.f) ? w * v : 0.f;
     }
   }
   a.out[(uint64_t)lq * 128u + d] = num / den;
   if (d == 0 && a.lse) a.lse[lq] = (M + __builtin_log2f(den)) * 0.69314718055994530942f;
 }
 
-__global__ void attend_status_kernel(AttendArgs a) {
+// Header verdict for the merge kernel (and the caller's status word); runs first on the stream.
+__global__ void attend_prepare_kernel(AttendArgs a) {
   CardGeom g;
   const bool ok = card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size,
                                             a.tokens, g);
-  if (threadIdx.x == 0 && blockIdx.x == 0) *a.status = ok ? 0u : QKV_STATUS_BAD_HEADER;
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    *a.valid = ok ? 1u : 0u;
+    if (a.status) *a.status = ok ? 0u : QKV_STATUS_BAD_HEADER;
+  }
 }
 
 }  // namespace
@@ -484,11 +505,12 @@ hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeo
   const uint64_t pairs = (uint64_t)expect.layers * expect.kv_heads;
   a.part_o = workspace;
   a.part_ml = workspace + pairs * a.max_tasks * a.rep * 128u;
+  a.valid = reinterpret_cast<uint32_t*>(workspace + pairs * a.max_tasks * a.rep * 130u);
   a.out = out;
   a.lse = lse;
   a.status = status;
-  if (status) {
-    hipLaunchKernelGGL(attend_status_kernel, dim3(1), dim3(kWaveSize), 0, stream, a);
+  {
+    hipLaunchKernelGGL(attend_prepare_kernel, dim3(1), dim3(kWaveSize), 0, stream, a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
