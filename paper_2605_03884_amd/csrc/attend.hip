@@ -32,6 +32,10 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRoundTokens = 16;
+#ifndef QKV_ATTEND_WAVES_PER_BLOCK
+#define QKV_ATTEND_WAVES_PER_BLOCK 1
+#endif
+constexpr int kAttendWaves = QKV_ATTEND_WAVES_PER_BLOCK;   // waves per workgroup; they do not interact
 // Rounds whose loads are in flight ahead of the arithmetic: as many as the registers allow
 // (a fetched span is 3 / 5 / 9 / 16 registers at 2 / 4 / 8 / 16 bits).
 template <int W> struct Prefetch { static constexpr int kRounds = (W == 2) ? 4 : (W == 4) ? 3 : (W == 8) ? 2 : 1; };
@@ -76,10 +80,31 @@ struct SpanData {
   uint32_t pair;
 };
 
-// Issues the loads of one span; nothing is decoded yet.
+// Where lane (n, kq) finds its span in round 0 of a task; every round is 16 rows further.
+struct LanePtrs {
+  const uint8_t* codes;    // packed codes (or the raw fp16 span)
+  const uint8_t* pair;     // the group's (scale, zero)
+};
+
 template <int W, int G>
-__device__ inline SpanData<W, G> fetch_span(const uint8_t* card, const CardGeom& g, int c, uint64_t row, uint32_t kq,
-                                            bool valid) {
+__device__ inline LanePtrs lane_pointers(const uint8_t* card, const CardGeom& g, int c, uint64_t row0, uint32_t n,
+                                         uint32_t kq) {
+  constexpr int GS = G / 32;
+  const uint64_t gsp = (row0 + n) * 4 + kq;
+  LanePtrs p;
+  if (W == 16) {
+    p.codes = card + g.off_fp16 + gsp * 64u;
+    p.pair = nullptr;
+  } else {
+    p.codes = card + g.off_codes[c] + gsp * (4u * W);
+    p.pair = card + g.off_meta[c] + (gsp / GS) * 4u;
+  }
+  return p;
+}
+
+// Issues the loads of the lane's span in round rd; nothing is decoded yet.  Zeros when !valid.
+template <int W, int G>
+__device__ inline SpanData<W, G> fetch_span(const LanePtrs& p, uint32_t rd, bool valid) {
   constexpr int GS = G / 32;
   constexpr int NW = (W == 16) ? 16 : W;
   SpanData<W, G> d;
@@ -87,28 +112,18 @@ __device__ inline SpanData<W, G> fetch_span(const uint8_t* card, const CardGeom&
   for (int i = 0; i < NW; ++i) d.cw[i] = 0;
   d.pair = 0;
   if (valid) {
-    const uint64_t gsp = row * 4 + kq;
-    if (W == 16) {
-      const u32x4* src = reinterpret_cast<const u32x4*>(card + g.off_fp16 + gsp * 64u);
+    const uint8_t* src = p.codes + (uint64_t)rd * (kRoundTokens * 16u * W);       // 16 rows of 16 W bytes
+    if (W == 2) {
+      const u32x2 t = *reinterpret_cast<const u32x2*>(src);
+      d.cw[0] = t.x; d.cw[1] = t.y;
+    } else {
 #pragma unroll
-      for (int h = 0; h < 4; ++h) {
-        const u32x4 t = src[h];
+      for (int h = 0; h < NW / 4; ++h) {
+        const u32x4 t = *reinterpret_cast<const u32x4*>(src + 16 * h);
         d.cw[4 * h] = t.x; d.cw[4 * h + 1] = t.y; d.cw[4 * h + 2] = t.z; d.cw[4 * h + 3] = t.w;
       }
-    } else {
-      const uint8_t* src = card + g.off_codes[c] + gsp * (4u * W);
-      if (W == 2) {
-        const u32x2 t = *reinterpret_cast<const u32x2*>(src);
-        d.cw[0] = t.x; d.cw[1] = t.y;
-      } else {
-#pragma unroll
-        for (int h = 0; h < NW / 4; ++h) {
-          const u32x4 t = *reinterpret_cast<const u32x4*>(src + 16 * h);
-          d.cw[4 * h] = t.x; d.cw[4 * h + 1] = t.y; d.cw[4 * h + 2] = t.z; d.cw[4 * h + 3] = t.w;
-        }
-      }
-      d.pair = reinterpret_cast<const uint32_t*>(card + g.off_meta[c])[gsp / GS];
     }
+    if (W != 16) d.pair = *reinterpret_cast<const uint32_t*>(p.pair + (uint64_t)rd * (kRoundTokens * 16u / GS));
   }
   return d;
 }
@@ -191,6 +206,8 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   const uint32_t cnt = j1 - j0;
   const uint32_t rounds = (cnt + kRoundTokens - 1) / kRoundTokens;
   constexpr int kPrefetch = Prefetch<W>::kRounds;
+  const LanePtrs kp = lane_pointers<W, G>(a.card, g, c, k_row0 + j0, n, kq);
+  const LanePtrs vp = lane_pointers<W, G>(a.card, g, c, v_row0 + j0, n, kq);
 
   // ---- q as MFMA A operands: row m = lane % 16 is query head m of this kv head, the lane holds
   // q[m][32 kq .. 32 kq + 31]; operand j is q[m][32 kq + 4 j .. + 3]
@@ -219,7 +236,7 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
 #pragma unroll
     for (int u = 0; u < kPrefetch; ++u) {
       const uint32_t t = u * kRoundTokens + n;
-      buf[u] = fetch_span<W, G>(a.card, g, c, k_row0 + j0 + t, kq, t < cnt);
+      buf[u] = fetch_span<W, G>(kp, u, t < cnt);
     }
     for (uint32_t rd0 = 0; rd0 < rounds; rd0 += kPrefetch) {
 #pragma unroll
@@ -229,7 +246,7 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
           uint32_t kb[16];
           decode_fetched<W, G>(buf[u], kb);
           const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
-          buf[u] = fetch_span<W, G>(a.card, g, c, k_row0 + j0 + tn, kq, tn < cnt);
+          buf[u] = fetch_span<W, G>(kp, rd + kPrefetch, tn < cnt);
           f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int j = 0; j < 8; ++j)
@@ -260,8 +277,14 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
     float l = 0.f;
     for (uint32_t t = lane; t < slots; t += kWaveSize) {
       const float p = __builtin_amdgcn_exp2f(row[t] - m);
-      row[t] = p;
       l += p;
+      // what the value pass feeds the MFMA: p * 2^14 as an fp16 high part plus an fp16 low part
+      // scaled by 2^11 (both normal numbers for any p that matters), packed into the score's slot
+      const float ps = p * 16384.0f;
+      const _Float16 hi = (_Float16)ps;
+      const _Float16 lo = (_Float16)((ps - (float)hi) * 2048.0f);
+      row[t] = __builtin_bit_cast(float, (uint32_t)__builtin_bit_cast(uint16_t, hi) |
+                                             ((uint32_t)__builtin_bit_cast(uint16_t, lo) << 16));
     }
     l = wave_sum(l);
     if (lane == 0 && r < R) {
@@ -271,7 +294,9 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   }
 
   // ---- values
-  constexpr uint32_t kRowBytes = 16u * W;                 // one token's packed row
+  // one token's packed row in the LDS tile; rows of 32 / 64 bytes get a pitch of 40 / 80 so that
+  // the four rows a read instruction touches (4 apart) fall on different banks
+  constexpr uint32_t kRowBytes = (W == 2) ? 40u : (W == 4) ? 80u : 16u * W;
   uint32_t* pairs_lds = reinterpret_cast<uint32_t*>(tile + 16u * 256u);
   f32x4 acc_hi[8], acc_lo[8];
 #pragma unroll
@@ -281,7 +306,7 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
 #pragma unroll
     for (int u = 0; u < kPrefetch; ++u) {
       const uint32_t t = u * kRoundTokens + n;
-      buf[u] = fetch_span<W, G>(a.card, g, c, v_row0 + j0 + t, kq, t < cnt);
+      buf[u] = fetch_span<W, G>(vp, u, t < cnt);
     }
     for (uint32_t rd0 = 0; rd0 < rounds; rd0 += kPrefetch) {
 #pragma unroll
@@ -301,7 +326,7 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
             if constexpr (W != 16) pairs_lds[n * 4u + kq] = buf[u].pair;
           }
           const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
-          buf[u] = fetch_span<W, G>(a.card, g, c, v_row0 + j0 + tn, kq, tn < cnt);
+          buf[u] = fetch_span<W, G>(vp, rd + kPrefetch, tn < cnt);
 
           // pieces of lane (a, kt) = (n, kq): tokens 4 kt + i, dimensions 8 a .. 8 a + 7
           Piece<W> pc[4];
@@ -338,19 +363,13 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
               b[e].y = decode_two_tokens(c2[e], s2, z2, c3[e], s3, z3);
             }
           }
-          // A operands: the weights of head m = n for tokens 4 kt .. 4 kt + 3, scaled by 2^14 so that
-          // fp16 holds them as normal numbers, split into a high part and a low part scaled by 2^11
-          f32x4 pw = {0.f, 0.f, 0.f, 0.f};
-          if (n < R4) pw = *reinterpret_cast<const f32x4*>(lds + n * chunk + rd * kRoundTokens + 4u * kq);
-          pw *= 16384.0f;
-          const f16x2 h01 = __builtin_convertvector((f32x2){pw.x, pw.y}, f16x2);
-          const f16x2 h23 = __builtin_convertvector((f32x2){pw.z, pw.w}, f16x2);
-          const f32x2 r01 = (f32x2){pw.x, pw.y} - __builtin_convertvector(h01, f32x2);
-          const f32x2 r23 = (f32x2){pw.z, pw.w} - __builtin_convertvector(h23, f32x2);
-          const f16x2 l01 = __builtin_convertvector(r01 * 2048.0f, f16x2);
-          const f16x2 l23 = __builtin_convertvector(r23 * 2048.0f, f16x2);
-          const f16x4 a_hi = {h01.x, h01.y, h23.x, h23.y};
-          const f16x4 a_lo = {l01.x, l01.y, l23.x, l23.y};
+          // A operands: the weights of head m = n for tokens 4 kt .. 4 kt + 3, high parts and low parts
+          u32x4 pw = (u32x4)(0u);
+          if (n < R4) pw = *reinterpret_cast<const u32x4*>(lds + n * chunk + rd * kRoundTokens + 4u * kq);
+          const f16x4 a_hi = __builtin_bit_cast(f16x4, (u32x2){__builtin_amdgcn_perm(pw.y, pw.x, 0x05040100u),
+                                                               __builtin_amdgcn_perm(pw.w, pw.z, 0x05040100u)});
+          const f16x4 a_lo = __builtin_bit_cast(f16x4, (u32x2){__builtin_amdgcn_perm(pw.y, pw.x, 0x07060302u),
+                                                               __builtin_amdgcn_perm(pw.w, pw.z, 0x07060302u)});
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
             const f16x4 be = __builtin_bit_cast(f16x4, b[e]);
@@ -377,16 +396,16 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
 }
 
 template <int G>
-__global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(2)))
+__global__ __launch_bounds__(kAttendWaves * kWaveSize) __attribute__((amdgpu_waves_per_eu(2)))
 void attend_kernel(AttendArgs a) {
-  __shared__ __attribute__((aligned(16))) float lds[kWavesPerBlock][kLdsFloatsPerWave];
-  __shared__ __attribute__((aligned(16))) uint8_t tiles[kWavesPerBlock][16 * 256 + 16 * 16];
+  __shared__ __attribute__((aligned(16))) float lds[kAttendWaves][kLdsFloatsPerWave];
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[kAttendWaves][16 * 256 + 16 * 16];
   CardGeom g;
   if (!card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, g))
     return;                                   // uniform over the grid
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t wave = threadIdx.x >> 6;
-  const uint32_t gw = blockIdx.x * kWavesPerBlock + wave;
+  const uint32_t gw = blockIdx.x * kAttendWaves + wave;
   const uint32_t pairs = g.planes >> 1;
   const uint32_t pair = gw / a.max_tasks;
   if (pair >= pairs) return;
@@ -515,7 +534,7 @@ hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeo
     if (e != hipSuccess) return e;
   }
   const uint64_t waves = pairs * a.max_tasks;
-  const dim3 grid((uint32_t)((waves + kWavesPerBlock - 1) / kWavesPerBlock)), block(kBlockThreads);
+  const dim3 grid((uint32_t)((waves + kAttendWaves - 1) / kAttendWaves)), block(kAttendWaves * kWaveSize);
   switch (expect.group_size) {
     case 32: hipLaunchKernelGGL(attend_kernel<32>, grid, block, 0, stream, a); break;
     case 64: hipLaunchKernelGGL(attend_kernel<64>, grid, block, 0, stream, a); break;
