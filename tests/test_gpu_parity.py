@@ -115,6 +115,21 @@ def test_shapes_mixed_widths(L, H, T, D, G):
     check_round_trip(desc, K, V, bits, "mixed L%d H%d T%d D%d G%d" % (L, H, T, D, G))
 
 
+def test_seeded_random_shapes_and_mixes():
+    # forty small problems drawn from one seed: shapes, group sizes, class mixes, value recipes
+    rng = np.random.default_rng(20240611)
+    for case in range(40):
+        D = int(rng.choice([64, 128, 256]))
+        G = int(rng.choice([g for g in (32, 64, 128) if g <= D]))
+        L, H = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        T = int(rng.integers(1, 700))
+        probs = rng.dirichlet(np.ones(4) * 0.6)
+        bits = rng.choice(np.array([2, 4, 8, 16], dtype=np.uint8), size=T, p=probs)
+        kind = "llama" if case % 2 else "tiny"
+        desc, K, V = make_problem(L, H, T, D, G, seed=7000 + case, kind=kind)
+        check_round_trip(desc, K, V, bits, "random case %d: L%d H%d T%d D%d G%d %s" % (case, L, H, T, D, G, kind))
+
+
 @pytest.mark.parametrize("T", [8191, 8192, 8193, 20000, 40003])
 def test_long_sequences_cross_compaction_chunks(T):
     # the compaction kernel walks the tokens in chunks of 8192
@@ -320,6 +335,54 @@ def test_card_survives_a_trip_through_host_memory():
     again = torch.from_numpy(np.frombuffer(blob, dtype=np.uint8).copy()).to(DEV)
     k2, v2, st = gpu_unpack(again, desc)
     assert st == 0 and np.array_equal(k2, k) and np.array_equal(v2, v)
+
+
+def test_handoff_replays_from_a_captured_graph():
+    # every call of the handoff is asynchronous and allocates nothing, so the three calls can be
+    # captured into one graph; each replay must reproduce the eager result, also after the inputs changed
+    L, H, T, D, G = 2, 4, 1024, 128, 32
+    desc, K0, V0 = make_problem(L, H, T, D, G, seed=111)
+    _, K1, V1 = make_problem(L, H, T, D, G, seed=112)
+    K = torch.from_numpy(K0).to(DEV)
+    V = torch.from_numpy(V0).to(DEV)
+    scores = qkv_synth.make_scores(T, 113, DEV)
+    bits = torch.empty(T, dtype=torch.uint8, device=DEV)
+    counts = qkv.budget_counts(T, 4.0)
+    card = torch.zeros(qkv.card_bytes(desc, counts), dtype=torch.uint8, device=DEV)
+    K_out = torch.zeros_like(K)
+    V_out = torch.zeros_like(V)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+
+    def handoff():
+        qkv.assign_bits(scores, 4.0, bits=bits)
+        qkv.quantize_pack(desc, K, V, bits, counts, card)
+        qkv.unpack_dequant(card, desc, K_out, V_out, status=status)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        handoff()                                    # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        handoff()
+    for rep, (Kn, Vn, seed) in enumerate([(K0, V0, 113), (K1, V1, 114), (K0, V0, 115), (K1, V1, 113)]):
+        say("graph replay %d" % rep)
+        K.copy_(torch.from_numpy(Kn))                # eager work between replays
+        V.copy_(torch.from_numpy(Vn))
+        scores.copy_(qkv_synth.make_scores(T, seed, DEV))
+        card.zero_(); K_out.zero_(); V_out.zero_(); status.fill_(9)
+        graph.replay()
+        torch.cuda.synchronize()
+        want_bits, want_counts = ref.assign_bits(scores.cpu().numpy(), 4.0)
+        assert want_counts.tolist() == counts
+        want = ref.quantize_pack(ref_desc(desc), Kn, Vn, want_bits, want_counts)
+        assert first_diff(card.cpu().numpy(), want) is None
+        wk, wv = ref.unpack_dequant(want, ref_desc(desc))
+        assert int(status.item()) == 0
+        assert np.array_equal(K_out.cpu().numpy().view(np.uint16), wk)
+        assert np.array_equal(V_out.cpu().numpy().view(np.uint16), wv)
 
 
 def test_pack_is_deterministic():
