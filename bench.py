@@ -77,6 +77,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="llama8b_8k_b3", choices=sorted(qkv_synth.CONFIGS))
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a captured graph (reported beside the eager figure)")
     ap.add_argument("--cpu-layers", type=int, default=0,
                     help="layers of the workload the CPU oracle is timed on (0: about 8192*32 token-layers)")
     args = ap.parse_args()
@@ -131,6 +133,26 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
+
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
 
     # the same K steps again with HIP events around every call (the events cost a few
     # microseconds per step themselves, which is why the figure above is taken without them)
@@ -216,6 +238,7 @@ def main():
                       "unpack_dequant": round(unpack_ms, 4)},
         "pct_hbm_peak": {"quantize_pack": round(100 * legs[0]["frac"], 2), "unpack_dequant": round(100 * legs[1]["frac"], 2)},
         "ms_per_step_with_events": round(ms_per_step_events, 4),
+        "ms_per_step_graph_replay": None if graph_ms is None else round(graph_ms, 4),
         "copy_ceiling_gbs": round(copy_gbs, 1),
         "card_attend": attend,
     }
