@@ -191,6 +191,21 @@ int qkv_quantize_pack(const qkv_desc_t* desc, const void* k_dev, const void* v_d
                       void* card_dev, uint64_t card_capacity, void* stream);
 
 /*
+ * The two halves of qkv_quantize_pack, for a sender that knows the widths before its K/V
+ * are final (paper Sec. 4.2.1: the card's metadata - bit-width vector, sequence length,
+ * identifiers, average-bit statistic - does not depend on the cache contents):
+ *   qkv_card_plan  writes the header, the bits / slot / order tables and the section pads;
+ *   qkv_card_fill  quantizes, packs and copies the K/V rows into a card planned with the
+ *                  same desc and counts (it reads the card's order table, not bits_dev).
+ * Arguments, alignment rules, error codes and status bits are those of qkv_quantize_pack;
+ * plan followed by fill on one stream produces the same bytes.  Both are asynchronous.
+ */
+int qkv_card_plan(const qkv_desc_t* desc, const uint8_t* bits_dev, const int64_t counts[4],
+                  void* card_dev, uint64_t card_capacity, void* stream);
+int qkv_card_fill(const qkv_desc_t* desc, const void* k_dev, const void* v_dev, const int64_t counts[4],
+                  void* card_dev, uint64_t card_capacity, void* stream);
+
+/*
  * Receiver-side injection (paper Sec. 4.2.2): unpack and dequantize a card into a
  * dense fp16 K/V cache.
  *   card_dev:   device, 256-byte aligned, card_bytes readable bytes.

@@ -6,6 +6,6 @@ HIP kernels.  There is no CPU path: a missing library raises at first use.
 """
 from .binding import (  # noqa: F401
     QkvError, Desc, lib, lib_path, version, error_string, card_bytes, budget_counts, assign_bits, count_bits,
-    quantize_pack, unpack_dequant, card_peek, card_attend, card_attend_workspace, STATUS_BAD_BITS, STATUS_BAD_COUNTS, STATUS_BAD_HEADER,
+    quantize_pack, card_plan, card_fill, unpack_dequant, card_peek, card_attend, card_attend_workspace, STATUS_BAD_BITS, STATUS_BAD_COUNTS, STATUS_BAD_HEADER,
     STATUS_BAD_ORDER,
 )

@@ -70,6 +70,10 @@ def lib():
     L.qkv_count_bits.argtypes = [vp, ctypes.c_int64, i64p, vp]
     L.qkv_quantize_pack.restype = ctypes.c_int
     L.qkv_quantize_pack.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, i64p, vp, ctypes.c_uint64, vp]
+    L.qkv_card_plan.restype = ctypes.c_int
+    L.qkv_card_plan.argtypes = [ctypes.POINTER(Desc), vp, i64p, vp, ctypes.c_uint64, vp]
+    L.qkv_card_fill.restype = ctypes.c_int
+    L.qkv_card_fill.argtypes = [ctypes.POINTER(Desc), vp, vp, i64p, vp, ctypes.c_uint64, vp]
     L.qkv_unpack_dequant.restype = ctypes.c_int
     L.qkv_unpack_dequant.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, vp, vp, vp]
     L.qkv_card_attend_workspace.restype = ctypes.c_int
@@ -154,6 +158,21 @@ def quantize_pack(desc, k, v, bits, counts, card, stream=None):
                                    _dev_ptr(bits, torch.uint8, "bits"), _counts(counts),
                                    _dev_ptr(card, torch.uint8, "card"), card.numel(), _stream(stream)),
            "qkv_quantize_pack")
+    return card
+
+
+def card_plan(desc, bits, counts, card, stream=None):
+    """First half of quantize_pack: header, tables and pads."""
+    _check(lib().qkv_card_plan(ctypes.byref(desc), _dev_ptr(bits, torch.uint8, "bits"), _counts(counts),
+                               _dev_ptr(card, torch.uint8, "card"), card.numel(), _stream(stream)), "qkv_card_plan")
+    return card
+
+
+def card_fill(desc, k, v, counts, card, stream=None):
+    """Second half of quantize_pack: the K/V rows into a planned card."""
+    _check(lib().qkv_card_fill(ctypes.byref(desc), _dev_ptr(k, torch.float16, "k"), _dev_ptr(v, torch.float16, "v"),
+                               _counts(counts), _dev_ptr(card, torch.uint8, "card"), card.numel(), _stream(stream)),
+           "qkv_card_fill")
     return card
 
 

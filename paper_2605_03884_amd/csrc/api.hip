@@ -188,22 +188,24 @@ int qkv_count_bits(const uint8_t* bits_dev, int64_t tokens, int64_t counts_out[4
   return QKV_OK;
 }
 
-int qkv_quantize_pack(const qkv_desc_t* desc, const void* k_dev, const void* v_dev, const uint8_t* bits_dev,
-                      const int64_t counts[4], void* card_dev, uint64_t card_capacity, void* stream) {
-  if (!desc || !k_dev || !v_dev || !bits_dev || !counts || !card_dev) return QKV_ERR_NULL;
+namespace {
+
+// Checks shared by the card-building calls; fills the geometry.
+int prepare_card(const qkv_desc_t* desc, const int64_t counts[4], const void* card_dev, uint64_t card_capacity,
+                 CardGeom& g, uint64_t n[4]) {
   int rc = check_desc(desc);
   if (rc) return rc;
   rc = check_counts(desc->tokens, counts);
   if (rc) return rc;
-  if (reinterpret_cast<uintptr_t>(k_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(v_dev) % 16 != 0 ||
-      reinterpret_cast<uintptr_t>(card_dev) % QKV_CARD_ALIGN != 0)
-    return QKV_ERR_ALIGN;
-  uint64_t n[4];
+  if (reinterpret_cast<uintptr_t>(card_dev) % QKV_CARD_ALIGN != 0) return QKV_ERR_ALIGN;
   to_u64(counts, n);
-  CardGeom g;
   build_geom(g, desc->layers, desc->kv_heads, desc->head_dim, desc->group_size, desc->tokens, n);
   if (card_capacity < g.total) return QKV_ERR_CAPACITY;
+  return QKV_OK;
+}
 
+int plan_card(const qkv_desc_t* desc, const uint8_t* bits_dev, const CardGeom& g, const uint64_t n[4], uint8_t* card,
+              hipStream_t s) {
   qkv_card_header_t h;
   std::memset(&h, 0, sizeof(h));
   static const uint8_t magic[8] = {'Q', 'K', 'V', 'C', 'A', 'R', 'D', 0};
@@ -227,10 +229,45 @@ int qkv_quantize_pack(const qkv_desc_t* desc, const void* k_dev, const void* v_d
   h.avg_bits = (float)((double)code_bits / (double)h.tokens);   // achieved average bit width (Sec. 4.2.1)
   h.flags = 0;
   h.status = 0;
+  return launch_classify(bits_dev, g, h, card, s) == hipSuccess ? QKV_OK : QKV_ERR_HIP;
+}
 
+}  // namespace
+
+int qkv_card_plan(const qkv_desc_t* desc, const uint8_t* bits_dev, const int64_t counts[4], void* card_dev,
+                  uint64_t card_capacity, void* stream) {
+  if (!desc || !bits_dev || !counts || !card_dev) return QKV_ERR_NULL;
+  CardGeom g;
+  uint64_t n[4];
+  const int rc = prepare_card(desc, counts, card_dev, card_capacity, g, n);
+  if (rc) return rc;
+  return plan_card(desc, bits_dev, g, n, static_cast<uint8_t*>(card_dev), static_cast<hipStream_t>(stream));
+}
+
+int qkv_card_fill(const qkv_desc_t* desc, const void* k_dev, const void* v_dev, const int64_t counts[4],
+                  void* card_dev, uint64_t card_capacity, void* stream) {
+  if (!desc || !k_dev || !v_dev || !counts || !card_dev) return QKV_ERR_NULL;
+  CardGeom g;
+  uint64_t n[4];
+  const int rc = prepare_card(desc, counts, card_dev, card_capacity, g, n);
+  if (rc) return rc;
+  if (reinterpret_cast<uintptr_t>(k_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(v_dev) % 16 != 0) return QKV_ERR_ALIGN;
+  return launch_pack(g, k_dev, v_dev, static_cast<uint8_t*>(card_dev), static_cast<hipStream_t>(stream)) == hipSuccess
+             ? QKV_OK : QKV_ERR_HIP;
+}
+
+int qkv_quantize_pack(const qkv_desc_t* desc, const void* k_dev, const void* v_dev, const uint8_t* bits_dev,
+                      const int64_t counts[4], void* card_dev, uint64_t card_capacity, void* stream) {
+  if (!desc || !k_dev || !v_dev || !bits_dev || !counts || !card_dev) return QKV_ERR_NULL;
+  CardGeom g;
+  uint64_t n[4];
+  int rc = prepare_card(desc, counts, card_dev, card_capacity, g, n);
+  if (rc) return rc;
+  if (reinterpret_cast<uintptr_t>(k_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(v_dev) % 16 != 0) return QKV_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
   uint8_t* card = static_cast<uint8_t*>(card_dev);
-  if (launch_classify(bits_dev, g, h, card, s) != hipSuccess) return QKV_ERR_HIP;
+  rc = plan_card(desc, bits_dev, g, n, card, s);
+  if (rc) return rc;
   if (launch_pack(g, k_dev, v_dev, card, s) != hipSuccess) return QKV_ERR_HIP;
   return QKV_OK;
 }

@@ -385,6 +385,28 @@ def test_handoff_replays_from_a_captured_graph():
         assert np.array_equal(V_out.cpu().numpy().view(np.uint16), wv)
 
 
+def test_plan_then_fill_equals_quantize_pack():
+    L, H, T, D, G = 2, 3, 777, 128, 32
+    desc, K, V = make_problem(L, H, T, D, G, seed=121)
+    bits = qkv_synth.make_bits_uniform_choice(T, 122).numpy()
+    counts = [int((bits == w).sum()) for w in (2, 4, 8, 16)]
+    Kd, Vd, bd = torch.from_numpy(K).to(DEV), torch.from_numpy(V).to(DEV), torch.from_numpy(bits).to(DEV)
+    whole, _, _ = gpu_card(desc, Kd, Vd, bd, counts)
+    n = qkv.card_bytes(desc, counts)
+    card = torch.full((n,), 0xA5, dtype=torch.uint8, device=DEV)
+    qkv.card_plan(desc, bd, counts, card)
+    torch.cuda.synchronize()
+    planned = card.cpu().numpy()
+    off = ref.card_offsets(ref_desc(desc), counts)
+    assert np.array_equal(planned[:off["codes2"]], whole[:off["codes2"]])        # header and tables are final
+    qkv.card_fill(desc, Kd, Vd, counts, card)
+    torch.cuda.synchronize()
+    assert np.array_equal(card.cpu().numpy(), whole)
+    with pytest.raises(qkv.QkvError) as e:
+        qkv.card_fill(desc, Kd, Vd, counts, card[:n - 256])
+    assert e.value.code == -5
+
+
 def test_pack_is_deterministic():
     L, H, T, D, G = 2, 2, 900, 128, 32
     desc, K, V = make_problem(L, H, T, D, G, seed=41)
