@@ -3,16 +3,16 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "qkv_ref.cpp")
+SRCS = [os.path.join(HERE, "qkv_ref.cpp"), os.path.join(HERE, "controller_ref.cpp")]
 LIB = os.path.join(HERE, "libqkvref.so")
 
 
 def build(force=True):
     """Build the shared library; returns its path.  With force=False an up-to-date one is kept."""
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(os.path.getmtime(s) for s in SRCS):
         return LIB
     cmd = ["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math",
-           "-Wall", "-Wextra", "-o", LIB, SRC]
+           "-Wall", "-Wextra", "-o", LIB] + SRCS
     subprocess.run(cmd, check=True)
     return LIB
 

@@ -116,6 +116,31 @@ def assign_bits(scores, budget):
     return bits, counts
 
 
+def controller_scores(features, w1, b1, w2):
+    """Scores of the 6 -> 64 -> 1 controller network; features [T, 6], w1 [64, 6], b1 [64], w2 [64], all float32."""
+    features = np.ascontiguousarray(features, dtype=np.float32)
+    w1 = np.ascontiguousarray(w1, dtype=np.float32)
+    b1 = np.ascontiguousarray(b1, dtype=np.float32)
+    w2 = np.ascontiguousarray(w2, dtype=np.float32)
+    assert features.ndim == 2 and features.shape[1] == 6 and w1.shape == (64, 6) and b1.shape == (64,) and w2.shape == (64,)
+    T = features.shape[0]
+    scores = np.zeros(T, dtype=np.float32)
+    _check(lib().qkv_ref_controller_scores(_ptr(features), ctypes.c_int64(T), _ptr(w1), _ptr(b1), _ptr(w2), _ptr(scores)),
+           "controller_scores")
+    return scores
+
+
+def assign_bits_greedy(scores, budget):
+    """Objective-greedy allocator: widths and class counts."""
+    scores = np.ascontiguousarray(scores, dtype=np.float32)
+    T = scores.shape[0]
+    bits = np.zeros(T, dtype=np.uint8)
+    counts = np.zeros(4, dtype=np.int64)
+    _check(lib().qkv_ref_assign_bits_greedy(_ptr(scores), ctypes.c_int64(T), ctypes.c_double(budget), _ptr(bits),
+                                            _ptr(counts)), "assign_bits_greedy")
+    return bits, counts
+
+
 def count_bits(bits):
     bits = np.ascontiguousarray(bits, dtype=np.uint8)
     counts = np.zeros(4, dtype=np.int64)

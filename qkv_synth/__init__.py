@@ -109,6 +109,27 @@ def make_scores(tokens, seed, device="cpu"):
     return uniform01(seed, 7, 0, tokens, device)
 
 
+def make_features(tokens, seed, device="cpu"):
+    """Controller features [tokens, 6], float32: frequency, quality, attention variance and entropy
+    ~ Uniform(0, 1); downstream demand ~ Uniform(0, 1) lifted by 0.5 inside shared segments; segment
+    type 0 (private), 0.5 (shared context) or 1 (shared state), constant over segments of 64 tokens."""
+    f = torch.stack([uniform01(seed, 20 + i, 0, tokens, device) for i in range(5)], dim=1)
+    n_seg = (tokens + 63) // 64
+    seg = _lsr(raw_u64(seed, 26, 0, n_seg, device), 62).clamp(max=2)        # 0, 1, 2 (2 twice as likely)
+    seg = seg.repeat_interleave(64)[:tokens].to(torch.float32) * 0.5
+    f[:, 4] = f[:, 4] + 0.5 * (seg > 0).to(torch.float32)
+    return torch.cat([f, seg.view(tokens, 1)], dim=1).contiguous()
+
+
+def make_controller(seed, device="cpu"):
+    """Random-initialised controller weights (trained ones are not available): w1 [64, 6] ~ N(0, 1/6),
+    b1 [64] ~ N(0, 0.01), w2 [64] = |N(0, 1/64)| (non-negative, so that scores are non-negative)."""
+    w1 = (normal(seed, 30, 0, 64 * 6, device) * (1.0 / math.sqrt(6.0))).view(64, 6).contiguous()
+    b1 = normal(seed, 31, 0, 64, device) * 0.1
+    w2 = (normal(seed, 32, 0, 64, device) * 0.125).abs()
+    return w1, b1, w2
+
+
 def make_bits_uniform_choice(tokens, seed, device="cpu"):
     """Each token's width drawn uniformly from {2, 4, 8, 16}: a caller-made vector."""
     r = _lsr(raw_u64(seed, 8, 0, tokens, device), 62)
