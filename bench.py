@@ -213,6 +213,28 @@ def main():
                   "frac_hbm_peak": round(att_bytes / (att_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                   "dense_cache_gbs_equivalent": round(kv_bytes / (att_ms * 1e-3) / 1e9, 1)}
 
+    # the controller in front of the handoff: features -> scores -> widths (objective-greedy), timed on its own
+    feats = qkv_synth.make_features(T, cfg["data_seed"] + 23, dev)
+    params = qkv.Controller.make(*[a.cpu() for a in qkv_synth.make_controller(cfg["data_seed"] + 24)])
+    c_scores = torch.empty(T, dtype=torch.float32, device=dev)
+    c_bits = torch.empty(T, dtype=torch.uint8, device=dev)
+    c_counts = torch.empty(4, dtype=torch.int64, device=dev)
+    n_ctl = max(10, args.steps // 4)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ctl_ms = [0.0, 0.0]
+    for it in range(3 + n_ctl):
+        ev[0].record()
+        qkv.controller_scores(feats, params, c_scores)
+        ev[1].record()
+        qkv.assign_bits_greedy(c_scores, budget if budget is not None else 4.0, c_bits, c_counts)
+        ev[2].record()
+        torch.cuda.synchronize()
+        if it >= 3:
+            ctl_ms[0] += ev[0].elapsed_time(ev[1]) / n_ctl
+            ctl_ms[1] += ev[1].elapsed_time(ev[2]) / n_ctl
+    controller = {"controller_scores_ms": round(ctl_ms[0], 4), "assign_bits_greedy_ms": round(ctl_ms[1], 4),
+                  "calls": n_ctl, "greedy_counts_2_4_8_16": c_counts.cpu().tolist()}
+
     # plain device copy of the same fp16 bytes: what this machine's HBM gives a kernel with no arithmetic
     for _ in range(3):
         K_out.copy_(K)
@@ -258,6 +280,7 @@ def main():
         "ms_per_step_graph_replay": None if graph_ms is None else round(graph_ms, 4),
         "copy_ceiling_gbs": round(copy_gbs, 1),
         "card_attend": attend,
+        "controller": controller,
     }
     if not args.no_cpu:
         layers = args.cpu_layers if args.cpu_layers > 0 else (L * 8192) // max(T, 8192)

@@ -171,6 +171,49 @@ int qkv_assign_bits(const float* scores_dev, int64_t tokens, double avg_bits_bud
 int qkv_count_bits(const uint8_t* bits_dev, int64_t tokens, int64_t counts_out[4], void* stream);
 
 /*
+ * Parameters of the extended controller's network (paper Sec. 4.1.2): a 2-layer MLP with 512
+ * parameters over the 6 per-token features [frequency, quality, attention variance, entropy,
+ * downstream demand, segment type].  The paper fixes neither hidden width, activation nor
+ * output; here: 64 hidden units with ReLU and one linear output without bias
+ * (6*64 + 64 + 64 = 512), the output being the combined score S(t) of Sec. 3.3.
+ */
+typedef struct qkv_controller {
+  float w1[64][6];   /* hidden unit j, feature i */
+  float b1[64];
+  float w2[64];
+} qkv_controller_t;
+
+/*
+ * Scores of the controller network for every token (paper Sec. 4.1.2).
+ *   features_dev: device, float[T][6], row-major, 8-byte aligned.  Caller-owned, read only.
+ *   params:       host; copied into the launch, may be freed on return.
+ *   scores_dev:   device, float[T], written.
+ * fp32 in a fixed order: hidden unit j = relu(fma chain over the features in order, starting
+ * from b1[j]); score = fma chain over the hidden units in order, starting from +0.  A hidden
+ * pre-activation that is NaN counts as 0.  Asynchronous on `stream`.
+ * Errors: QKV_ERR_NULL, QKV_ERR_SHAPE (T < 1 or T >= 2^31), QKV_ERR_ALIGN, QKV_ERR_HIP.
+ */
+int qkv_controller_scores(const float* features_dev, int64_t tokens, const qkv_controller_t* params,
+                          float* scores_dev, void* stream);
+
+/*
+ * Bit widths that follow the budgeted objective of paper Sec. 3.3 literally: minimise
+ * sum_t eps(b(t)) * S(t) under sum_t b(t) <= avg_bits_budget * T, with the error model
+ * eps(b) = 1 / (2^b - 1).  Every token starts at 2 bits; the upgrades 2->4, 4->8, 8->16 cost
+ * 2, 4, 8 bits and gain max(S, 0) * {2/15, 4/255, 32/65535} per bit (one fp32 product with the
+ * constant rounded to fp32; NaN scores count as 0).  All upgrades are ranked by (gain per bit
+ * descending, level ascending, token index ascending) and the longest prefix whose cost fits
+ * floor(budget * T) - 2T bits is taken; the budget is read as in qkv_assign_bits (rounded to
+ * 1/1000 bit).  The class counts depend on the scores, so they are produced on the device:
+ *   scores_dev: device, float[T], 4-byte aligned.   bits_dev: device, uint8_t[T], written.
+ *   counts_dev: device, uint64_t[4] for widths 2,4,8,16, 8-byte aligned, written; may be NULL.
+ * Asynchronous on `stream`; allocates nothing.
+ * Errors: QKV_ERR_NULL, QKV_ERR_SHAPE (T < 1 or T >= 2^28), QKV_ERR_BUDGET, QKV_ERR_ALIGN, QKV_ERR_HIP.
+ */
+int qkv_assign_bits_greedy(const float* scores_dev, int64_t tokens, double avg_bits_budget,
+                           uint8_t* bits_dev, uint64_t* counts_dev, void* stream);
+
+/*
  * CacheCard creation (paper Sec. 4.2.1): classify tokens by width and compact them
  * stably into per-width segments (slot, order), quantize and bit-pack K and V rows
  * at their token's width, copy 16-bit rows unchanged, write header and metadata.

@@ -37,6 +37,23 @@ class Desc(ctypes.Structure):
         return cls(layers, kv_heads, head_dim, group_size, tokens, model_id, sender_id, position_offset)
 
 
+class Controller(ctypes.Structure):
+    """qkv_controller_t: the 512 parameters of the 6 -> 64 -> 1 network."""
+    _fields_ = [("w1", ctypes.c_float * 6 * 64), ("b1", ctypes.c_float * 64), ("w2", ctypes.c_float * 64)]
+
+    @classmethod
+    def make(cls, w1, b1, w2):
+        """w1 [64, 6], b1 [64], w2 [64]: host float32 tensors or arrays."""
+        c = cls()
+        flat = [float(x) for x in torch.as_tensor(w1, dtype=torch.float32).reshape(-1).tolist()]
+        if len(flat) != 384 or len(b1) != 64 or len(w2) != 64:
+            raise ValueError("controller parameters must be w1 [64, 6], b1 [64], w2 [64]")
+        ctypes.memmove(c.w1, (ctypes.c_float * 384)(*flat), 384 * 4)
+        ctypes.memmove(c.b1, (ctypes.c_float * 64)(*[float(x) for x in torch.as_tensor(b1, dtype=torch.float32).tolist()]), 256)
+        ctypes.memmove(c.w2, (ctypes.c_float * 64)(*[float(x) for x in torch.as_tensor(w2, dtype=torch.float32).tolist()]), 256)
+        return c
+
+
 _lib = None
 
 
@@ -66,6 +83,10 @@ def lib():
     L.qkv_budget_counts.argtypes = [ctypes.c_int64, ctypes.c_double, i64p]
     L.qkv_assign_bits.restype = ctypes.c_int
     L.qkv_assign_bits.argtypes = [vp, ctypes.c_int64, ctypes.c_double, vp, i64p, vp]
+    L.qkv_controller_scores.restype = ctypes.c_int
+    L.qkv_controller_scores.argtypes = [vp, ctypes.c_int64, ctypes.POINTER(Controller), vp, vp]
+    L.qkv_assign_bits_greedy.restype = ctypes.c_int
+    L.qkv_assign_bits_greedy.argtypes = [vp, ctypes.c_int64, ctypes.c_double, vp, vp, vp]
     L.qkv_count_bits.restype = ctypes.c_int
     L.qkv_count_bits.argtypes = [vp, ctypes.c_int64, i64p, vp]
     L.qkv_quantize_pack.restype = ctypes.c_int
@@ -143,6 +164,32 @@ def assign_bits(scores, avg_bits_budget, bits=None, stream=None):
     _check(lib().qkv_assign_bits(_dev_ptr(scores, torch.float32, "scores"), T, float(avg_bits_budget),
                                  _dev_ptr(bits, torch.uint8, "bits"), out, _stream(stream)), "qkv_assign_bits")
     return bits, list(out)
+
+
+def controller_scores(features, params, scores=None, stream=None):
+    """features: device float32[T, 6]; params: Controller.  Returns scores, device float32[T]."""
+    T = features.shape[0]
+    if features.dim() != 2 or features.shape[1] != 6:
+        raise ValueError("features must be [T, 6]")
+    if scores is None:
+        scores = torch.empty(T, dtype=torch.float32, device=features.device)
+    _check(lib().qkv_controller_scores(_dev_ptr(features, torch.float32, "features"), T, ctypes.byref(params),
+                                       _dev_ptr(scores, torch.float32, "scores"), _stream(stream)),
+           "qkv_controller_scores")
+    return scores
+
+
+def assign_bits_greedy(scores, avg_bits_budget, bits=None, counts=None, stream=None):
+    """scores: device float32[T].  Returns (bits device uint8[T], counts device int64[4]); nothing synchronises."""
+    T = scores.numel()
+    if bits is None:
+        bits = torch.empty(T, dtype=torch.uint8, device=scores.device)
+    if counts is None:
+        counts = torch.empty(4, dtype=torch.int64, device=scores.device)
+    _check(lib().qkv_assign_bits_greedy(_dev_ptr(scores, torch.float32, "scores"), T, float(avg_bits_budget),
+                                        _dev_ptr(bits, torch.uint8, "bits"), _dev_ptr(counts, torch.int64, "counts"),
+                                        _stream(stream)), "qkv_assign_bits_greedy")
+    return bits, counts
 
 
 def count_bits(bits, stream=None):

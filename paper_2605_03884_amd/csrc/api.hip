@@ -172,6 +172,32 @@ int qkv_assign_bits(const float* scores_dev, int64_t tokens, double avg_bits_bud
   return QKV_OK;
 }
 
+int qkv_controller_scores(const float* features_dev, int64_t tokens, const qkv_controller_t* params,
+                          float* scores_dev, void* stream) {
+  if (!features_dev || !params || !scores_dev) return QKV_ERR_NULL;
+  if (tokens < 1 || tokens >= (1ll << 31)) return QKV_ERR_SHAPE;
+  if (reinterpret_cast<uintptr_t>(features_dev) % 8 != 0 || reinterpret_cast<uintptr_t>(scores_dev) % 4 != 0)
+    return QKV_ERR_ALIGN;
+  return launch_controller(features_dev, (uint32_t)tokens, *params, scores_dev, static_cast<hipStream_t>(stream)) ==
+                 hipSuccess ? QKV_OK : QKV_ERR_HIP;
+}
+
+int qkv_assign_bits_greedy(const float* scores_dev, int64_t tokens, double avg_bits_budget, uint8_t* bits_dev,
+                           uint64_t* counts_dev, void* stream) {
+  if (!scores_dev || !bits_dev) return QKV_ERR_NULL;
+  if (tokens < 1 || tokens >= (1ll << 28)) return QKV_ERR_SHAPE;
+  if (!(avg_bits_budget >= 2.0 && avg_bits_budget <= 16.0)) return QKV_ERR_BUDGET;
+  const long long bm = std::llrint(avg_bits_budget * 1000.0);
+  if (bm < 2000 || bm > 16000) return QKV_ERR_BUDGET;
+  if (reinterpret_cast<uintptr_t>(scores_dev) % 4 != 0 || reinterpret_cast<uintptr_t>(counts_dev) % 8 != 0)
+    return QKV_ERR_ALIGN;
+  const int64_t budget_bits = (int64_t)(((__int128)bm * tokens) / 1000);
+  const uint32_t spare_units = (uint32_t)((budget_bits - 2 * tokens) / 2);      // upgrades cost 1, 2, 4 units of 2 bits
+  return launch_greedy(scores_dev, (uint32_t)tokens, spare_units, bits_dev,
+                       reinterpret_cast<unsigned long long*>(counts_dev), static_cast<hipStream_t>(stream)) == hipSuccess
+             ? QKV_OK : QKV_ERR_HIP;
+}
+
 int qkv_count_bits(const uint8_t* bits_dev, int64_t tokens, int64_t counts_out[4], void* stream) {
   if (!bits_dev || !counts_out) return QKV_ERR_NULL;
   if (tokens < 1) return QKV_ERR_SHAPE;

@@ -28,23 +28,6 @@ __device__ inline uint32_t rank_key(float score) {
   return ~up;
 }
 
-// One wave finds the bucket that holds rank `left` in a 256-bucket histogram: the first d
-// whose cumulative count exceeds `left`.  Returns d and lowers `left` by the count before it.
-// The histogram's total must exceed `left`.
-__device__ inline uint32_t find_bucket(const uint32_t* hist, uint32_t lane, uint32_t& left) {
-  const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
-  const uint32_t inc = wave_inclusive_scan(h0 + h1 + h2 + h3);
-  const uint64_t over = __builtin_amdgcn_ballot_w64(inc > left);
-  const uint32_t owner = (uint32_t)__builtin_ctzll(over | (1ull << 63));
-  const uint32_t before = __shfl(inc - (h0 + h1 + h2 + h3), owner, kWaveSize);
-  const uint32_t a0 = __shfl(h0, owner, kWaveSize), a1 = __shfl(h1, owner, kWaveSize), a2 = __shfl(h2, owner, kWaveSize);
-  uint32_t rest = left - before;
-  uint32_t d = 4 * owner;
-  if (rest >= a0) { rest -= a0; ++d; if (rest >= a1) { rest -= a1; ++d; if (rest >= a2) { rest -= a2; ++d; } } }
-  left = rest;
-  return d;
-}
-
 // KPT > 0: each thread keeps the keys of its KPT consecutive tokens in registers (needs
 // T <= KPT * kThreads); KPT == 0: any T, keys re-read from the scores on every sweep.
 template <int KPT>

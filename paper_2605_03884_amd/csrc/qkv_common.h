@@ -109,6 +109,23 @@ __device__ inline uint32_t wave_inclusive_scan(uint32_t v) {
   return v;
 }
 
+// One wave finds the bucket that holds rank `left` in a 256-bucket histogram: the first d
+// whose cumulative count exceeds `left`.  Returns d and lowers `left` by the count before it.
+// The histogram's total must exceed `left`.
+__device__ inline uint32_t find_bucket(const uint32_t* hist, uint32_t lane, uint32_t& left) {
+  const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+  const uint32_t inc = wave_inclusive_scan(h0 + h1 + h2 + h3);
+  const uint64_t over = __builtin_amdgcn_ballot_w64(inc > left);
+  const uint32_t owner = (uint32_t)__builtin_ctzll(over | (1ull << 63));
+  const uint32_t before = __shfl(inc - (h0 + h1 + h2 + h3), owner, 64);
+  const uint32_t a0 = __shfl(h0, owner, 64), a1 = __shfl(h1, owner, 64), a2 = __shfl(h2, owner, 64);
+  uint32_t rest = left - before;
+  uint32_t d = 4 * owner;
+  if (rest >= a0) { rest -= a0; ++d; if (rest >= a1) { rest -= a1; ++d; if (rest >= a2) { rest -= a2; ++d; } } }
+  left = rest;
+  return d;
+}
+
 // Number of workgroups for a streaming kernel with `tiles` wave-tiles of work.
 int grid_blocks(uint64_t tiles);
 
@@ -125,5 +142,9 @@ hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeo
                          uint32_t q_heads, float softmax_scale, float* out, float* lse, float* workspace,
                          uint32_t* status, hipStream_t stream);
 hipError_t launch_count(const uint8_t* bits, uint64_t tokens, unsigned long long* counts4, hipStream_t stream);
+hipError_t launch_controller(const float* features, uint32_t tokens, const qkv_controller_t& params, float* scores,
+                             hipStream_t stream);
+hipError_t launch_greedy(const float* scores, uint32_t tokens, uint32_t spare_units, uint8_t* bits,
+                         unsigned long long* counts4, hipStream_t stream);
 
 }  // namespace qkv
