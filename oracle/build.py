@@ -3,7 +3,8 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRCS = [os.path.join(HERE, "qkv_ref.cpp"), os.path.join(HERE, "controller_ref.cpp")]
+SRCS = [os.path.join(HERE, "qkv_ref.cpp"), os.path.join(HERE, "controller_ref.cpp"),
+        os.path.join(HERE, "inject_ref.cpp")]
 LIB = os.path.join(HERE, "libqkvref.so")
 
 
