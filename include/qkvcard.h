@@ -267,6 +267,52 @@ int qkv_unpack_dequant(const void* card_dev, uint64_t card_bytes, const qkv_desc
                        void* k_out_dev, void* v_out_dev, uint32_t* status_dev, void* stream);
 
 /*
+ * Receiver-side injection into per-layer caches (paper Sec. 4.2.2: the receiver rebuilds fp16
+ * past_key_values, which frameworks keep as one key tensor and one value tensor per layer), for a
+ * range of layers, so that injection can run layer by layer ahead of the receiver's forward
+ * pass; optionally with the keys realigned to a shifted position (Sec. 3.2, challenge 2; the
+ * card's position-offset field of Sec. 4.2.1 exists for this).
+ *
+ * Layer layer_begin + i of the card goes to k_layers[i] / v_layers[i]: device pointers to where
+ * token 0 of head 0 lands; token t of head h lands h * head_stride + t * token_stride elements
+ * further, as one contiguous row of head_dim fp16 values.  A cache of shape
+ * [kv_heads][capacity][head_dim] that already holds a prefix of P tokens takes
+ * head_stride = capacity * head_dim, token_stride = head_dim and pointers advanced by P rows.
+ * Pointers 16-byte aligned, strides multiples of 8 elements, token_stride >= head_dim.  Any
+ * other layout in which rows do not overlap works too (the library checks alignment and
+ * token_stride only; it cannot see the tensors' extents).  The pointer arrays are host memory,
+ * read before the call returns.
+ *
+ * Realignment (rope_base > 0): cached keys are assumed to carry rotary position embedding in the
+ * half-split pairing (element i with i + head_dim/2, angle position * rope_base^(-2i/head_dim)).
+ * Moving a key by rope_delta positions is one more rotation:
+ *   theta_i = pow(rope_base, -2 i / head_dim)                      (double)
+ *   c_i = (float)cos(rope_delta * theta_i), s_i = (float)sin(...)   (double, rounded to fp32)
+ *   x'[i]     = fp16( fma(x[i],     c_i, -fl32(x[i+D/2] * s_i)) )
+ *   x'[i+D/2] = fp16( fma(x[i+D/2], c_i, +fl32(x[i]     * s_i)) )
+ * applied to the dequantized fp16 key values (and to 16-bit key rows, which must then be finite);
+ * values are never rotated.  rope_base == 0 copies the keys as qkv_unpack_dequant does.
+ *
+ * Validation, status_dev and asynchrony as for qkv_unpack_dequant.  Allocates nothing.
+ * Errors: QKV_ERR_NULL, QKV_ERR_SHAPE (layer range outside the card, layer_count < 1 or
+ * > QKV_INJECT_MAX_LAYERS, bad strides, rope_base < 0 or not finite, |rope_delta| >= 2^31),
+ * QKV_ERR_GROUP, QKV_ERR_CAPACITY, QKV_ERR_ALIGN, QKV_ERR_HIP.
+ */
+#define QKV_INJECT_MAX_LAYERS 64
+
+typedef struct qkv_inject {
+  int32_t layer_begin, layer_count;
+  void* const* k_layers;            /* host array [layer_count] of device pointers */
+  void* const* v_layers;
+  int64_t head_stride, token_stride;  /* in fp16 elements */
+  double rope_base;                 /* 0: no realignment */
+  int64_t rope_delta;               /* positions to move the keys by */
+} qkv_inject_t;
+
+int qkv_inject_layers(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect,
+                      const qkv_inject_t* where, uint32_t* status_dev, void* stream);
+
+/*
  * Decode-step attention of one new query token directly over a card, without rebuilding
  * the dense cache (paper Sec. 4.3: consuming a foreign quantized cache inside attention,
  * which the paper names as its long-term goal).  For every layer l and query head hq, with

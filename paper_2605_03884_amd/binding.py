@@ -54,6 +54,20 @@ class Controller(ctypes.Structure):
         return c
 
 
+class Inject(ctypes.Structure):
+    """qkv_inject_t."""
+    _fields_ = [
+        ("layer_begin", ctypes.c_int32),
+        ("layer_count", ctypes.c_int32),
+        ("k_layers", ctypes.POINTER(ctypes.c_void_p)),
+        ("v_layers", ctypes.POINTER(ctypes.c_void_p)),
+        ("head_stride", ctypes.c_int64),
+        ("token_stride", ctypes.c_int64),
+        ("rope_base", ctypes.c_double),
+        ("rope_delta", ctypes.c_int64),
+    ]
+
+
 _lib = None
 
 
@@ -95,6 +109,8 @@ def lib():
     L.qkv_card_plan.argtypes = [ctypes.POINTER(Desc), vp, i64p, vp, ctypes.c_uint64, vp]
     L.qkv_card_fill.restype = ctypes.c_int
     L.qkv_card_fill.argtypes = [ctypes.POINTER(Desc), vp, vp, i64p, vp, ctypes.c_uint64, vp]
+    L.qkv_inject_layers.restype = ctypes.c_int
+    L.qkv_inject_layers.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), ctypes.POINTER(Inject), vp, vp]
     L.qkv_unpack_dequant.restype = ctypes.c_int
     L.qkv_unpack_dequant.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, vp, vp, vp]
     L.qkv_card_attend_workspace.restype = ctypes.c_int
@@ -231,6 +247,33 @@ def unpack_dequant(card, expect, k_out, v_out, status=None, card_nbytes=None, st
                                     _dev_ptr(k_out, torch.float16, "k_out"), _dev_ptr(v_out, torch.float16, "v_out"),
                                     sp, _stream(stream)), "qkv_unpack_dequant")
     return k_out, v_out
+
+
+def inject_layers(card, expect, k_layers, v_layers, layer_begin=0, rope_base=0.0, rope_delta=0, status=None,
+                  card_nbytes=None, stream=None):
+    """Layers layer_begin .. layer_begin + len(k_layers) - 1 of the card into per-layer tensors.
+
+    k_layers, v_layers: lists of device float16 tensors (views are fine) of shape [kv_heads, >= tokens, head_dim]
+    whose element [h, t, :] is where token t of head h lands: rows contiguous, all layers with the same strides.
+    A cache [kv_heads, capacity, head_dim] holding a prefix of P tokens is passed as cache[:, P:P + tokens]."""
+    n = card.numel() if card_nbytes is None else int(card_nbytes)
+    count = len(k_layers)
+    if count != len(v_layers) or count < 1:
+        raise ValueError("k_layers and v_layers must be lists of the same, non-zero length")
+    ref_strides = k_layers[0].stride()
+    for t in list(k_layers) + list(v_layers):
+        if not t.is_cuda or t.dtype != torch.float16 or t.dim() != 3:
+            raise ValueError("layer tensors must be device float16 [kv_heads, tokens, head_dim]")
+        if t.shape[0] != expect.kv_heads or t.shape[1] < expect.tokens or t.shape[2] != expect.head_dim:
+            raise ValueError("layer tensor shape %s does not hold the card's tokens" % (tuple(t.shape),))
+        if t.stride() != ref_strides or t.stride(2) != 1:
+            raise ValueError("layer tensors must share their strides and have contiguous rows")
+    kp = (ctypes.c_void_p * count)(*[t.data_ptr() for t in k_layers])
+    vp_ = (ctypes.c_void_p * count)(*[t.data_ptr() for t in v_layers])
+    where = Inject(int(layer_begin), count, kp, vp_, ref_strides[0], ref_strides[1], float(rope_base), int(rope_delta))
+    sp = ctypes.c_void_p(0) if status is None else _dev_ptr(status, None, "status")
+    _check(lib().qkv_inject_layers(_dev_ptr(card, torch.uint8, "card"), n, ctypes.byref(expect), ctypes.byref(where),
+                                   sp, _stream(stream)), "qkv_inject_layers")
 
 
 def card_attend_workspace(expect, q_heads):

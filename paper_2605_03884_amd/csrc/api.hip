@@ -316,6 +316,51 @@ int qkv_unpack_dequant(const void* card_dev, uint64_t card_bytes, const qkv_desc
   return QKV_OK;
 }
 
+int qkv_inject_layers(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, const qkv_inject_t* where,
+                      uint32_t* status_dev, void* stream) {
+  if (!card_dev || !expect || !where || !where->k_layers || !where->v_layers) return QKV_ERR_NULL;
+  const int rc = check_desc(expect);
+  if (rc) return rc;
+  if (where->layer_count < 1 || where->layer_count > QKV_INJECT_MAX_LAYERS || where->layer_begin < 0 ||
+      where->layer_begin > expect->layers - where->layer_count)
+    return QKV_ERR_SHAPE;
+  if (where->token_stride < expect->head_dim || where->token_stride % 8 != 0 || where->head_stride < 0 ||
+      where->head_stride % 8 != 0 || where->token_stride >= (1ll << 40) || where->head_stride >= (1ll << 40))
+    return QKV_ERR_SHAPE;
+  if (!(where->rope_base >= 0.0) || !std::isfinite(where->rope_base) || where->rope_delta <= -(1ll << 31) ||
+      where->rope_delta >= (1ll << 31))
+    return QKV_ERR_SHAPE;
+  if (card_bytes < QKV_CARD_HEADER_BYTES) return QKV_ERR_CAPACITY;
+  if (reinterpret_cast<uintptr_t>(card_dev) % QKV_CARD_ALIGN != 0 || reinterpret_cast<uintptr_t>(status_dev) % 4 != 0)
+    return QKV_ERR_ALIGN;
+  for (int i = 0; i < where->layer_count; ++i) {
+    if (!where->k_layers[i] || !where->v_layers[i]) return QKV_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(where->k_layers[i]) % 16 != 0 || reinterpret_cast<uintptr_t>(where->v_layers[i]) % 16 != 0)
+      return QKV_ERR_ALIGN;
+  }
+  // the rotation of the shift, one (cos, sin) per element pair (Sec. 3.2, challenge 2)
+  float cos_sin[128][2];
+  const bool rope = where->rope_base > 0.0;
+  if (rope) {
+    const int D = expect->head_dim;
+    for (int i = 0; i < D / 2; ++i) {
+      const double theta = std::pow(where->rope_base, -2.0 * i / D);
+      const double angle = (double)where->rope_delta * theta;
+      cos_sin[i][0] = (float)std::cos(angle);
+      cos_sin[i][1] = (float)std::sin(angle);
+    }
+  }
+  const uint64_t zero[4] = {0, 0, 0, (uint64_t)expect->tokens};
+  CardGeom g;
+  build_geom(g, expect->layers, expect->kv_heads, expect->head_dim, expect->group_size, expect->tokens, zero);
+  if (launch_inject(static_cast<const uint8_t*>(card_dev), card_bytes, g, (uint32_t)where->layer_begin,
+                    (uint32_t)where->layer_count, where->k_layers, where->v_layers, (uint64_t)where->head_stride * 2u,
+                    (uint64_t)where->token_stride * 2u, rope ? cos_sin : nullptr, status_dev,
+                    static_cast<hipStream_t>(stream)) != hipSuccess)
+    return QKV_ERR_HIP;
+  return QKV_OK;
+}
+
 namespace {
 // Shape rules of the fused attention path and the floats of workspace it needs.
 int attend_workspace_floats(const qkv_desc_t* expect, int32_t q_heads, uint64_t* floats) {

@@ -29,6 +29,31 @@ struct UnpackArgs {
   uint32_t* status;                                  // may be null
 };
 
+// Injection into per-layer caches: the same tiles, but only the planes of a layer range,
+// rows addressed through per-layer base pointers and strides, and - optionally - every key
+// row rotated to a shifted position on its way out (rotary embedding, half-split pairing).
+struct InjectArgs {
+  const uint8_t* card;
+  uint64_t card_bytes;
+  uint32_t layers, kv_heads, head_dim, group_size;
+  uint64_t tokens;
+  uint32_t layer_begin, layer_count;
+  uint64_t head_stride, token_stride;                // bytes
+  uint32_t rope;                                     // 1: rotate the keys with cs[]
+  uint32_t* status;                                  // may be null
+  uint64_t k_layer[QKV_INJECT_MAX_LAYERS];           // where token 0 of head 0 of layer layer_begin + i goes
+  uint64_t v_layer[QKV_INJECT_MAX_LAYERS];
+  float cs[128][2];                                  // (cos, sin) of the shift for pair index i < head_dim / 2
+};
+
+// What a lane needs to rotate its 16-byte chunk of a key row: the (cos, sin) of its 8 elements,
+// the sign of the partner term and where the partner chunk sits.
+struct RopeLane {
+  float c[8], s[8];
+  uint32_t flip;          // 0x80000000 for the first half of a row (x c - y s), 0 for the second (x c + y s)
+  uint32_t partner;       // lane distance (XOR) to the chunk holding the partner elements
+};
+
 typedef __attribute__((address_space(1))) u32x4 global_u32x4;
 
 // LDS position (in 16-byte units) of output chunk q of a tile.
@@ -57,6 +82,29 @@ __device__ inline uint64_t tile_row_address(const UnpackArgs& a, const CardGeom&
   return addr;
 }
 
+// Two elements x of a key row and their partners y: fp16( fma(x, cos, -+ fl32(y * sin)) ).  The fp32 result
+// and the conversion are kept apart (see decode_pair).
+__device__ inline uint32_t rotate_pair(uint32_t xd, uint32_t yd, float c0, float s0, float c1, float s1, uint32_t flip) {
+  const f16x2 xh = __builtin_bit_cast(f16x2, xd), yh = __builtin_bit_cast(f16x2, yd);
+  const float t0 = __uint_as_float(__float_as_uint((float)yh.x * s0) ^ flip);
+  const float t1 = __uint_as_float(__float_as_uint((float)yh.y * s1) ^ flip);
+  float r0 = __builtin_fmaf((float)xh.x, c0, t0);
+  float r1 = __builtin_fmaf((float)xh.y, c1, t1);
+  asm("" : "+v"(r0));
+  asm("" : "+v"(r1));
+  const f32x2 v = {r0, r1};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
+
+__device__ inline u32x4 rotate_chunk(u32x4 x, u32x4 y, const RopeLane& r) {
+  u32x4 o;
+  o.x = rotate_pair(x.x, y.x, r.c[0], r.s[0], r.c[1], r.s[1], r.flip);
+  o.y = rotate_pair(x.y, y.y, r.c[2], r.s[2], r.c[3], r.s[3], r.flip);
+  o.z = rotate_pair(x.z, y.z, r.c[4], r.s[4], r.c[5], r.s[5], r.flip);
+  o.w = rotate_pair(x.w, y.w, r.c[6], r.s[6], r.c[7], r.s[7], r.flip);
+  return o;
+}
+
 // Stores the tile: chunk 64 k + lane goes to its row, rows without an address are skipped.
 __device__ inline void store_tile(uint64_t my_row_addr, uint32_t lane, uint32_t lpr_shift, const u32x4 (&data)[kTileIters]) {
   const uint32_t in_row = (lane & ((1u << lpr_shift) - 1u)) * 16u;
@@ -70,17 +118,17 @@ __device__ inline void store_tile(uint64_t my_row_addr, uint32_t lane, uint32_t 
   }
 }
 
-template <int W, int G, bool KEEP>
-__device__ inline void unpack_tile(const UnpackArgs& a, const CardGeom& g, int c, uint32_t r0, uint32_t n_rows,
-                                   uint32_t lane, u32x4* lds, uint32_t& bad) {
+// Decodes the tile of class c that starts at segment row r0 (rows at or past n_rows are skipped) and stores
+// it to the row addresses in my_row (lane i: row r0 + i).  ROPE: rotate every row with `rope`.
+template <int W, int G, bool KEEP, bool ROPE>
+__device__ inline void unpack_tile(const uint8_t* card, const CardGeom& g, int c, uint32_t r0, uint32_t n_rows,
+                                   uint64_t my_row, uint32_t lane, u32x4* lds, const RopeLane& rope) {
   constexpr int GS = G / 32;                     // spans (lanes) per group
   const uint32_t lpr_shift = g.lpr_shift;
-  const uint32_t tile_rows = kTileChunks >> lpr_shift;
   const uint32_t spr_shift = lpr_shift - 2;      // log2(spans per row)
-  const uint64_t my_row = tile_row_address(a, g, c, r0, n_rows, lane, tile_rows, bad);
 
-  const uint8_t* codes_seg = a.card + g.off_codes[c];
-  const uint32_t* meta_seg = reinterpret_cast<const uint32_t*>(a.card + g.off_meta[c]);
+  const uint8_t* codes_seg = card + g.off_codes[c];
+  const uint32_t* meta_seg = reinterpret_cast<const uint32_t*>(card + g.off_meta[c]);
   const uint64_t span0 = (uint64_t)r0 << spr_shift;
   const uint64_t seg_spans = (uint64_t)n_rows << spr_shift;
 
@@ -125,17 +173,20 @@ __device__ inline void unpack_tile(const UnpackArgs& a, const CardGeom& g, int c
   const uint32_t rslot = swizzle(lane);
 #pragma unroll
   for (int k = 0; k < kTileIters; ++k) data[k] = lds[k * kWaveSize + rslot];
+  if (ROPE) {                                    // the partner chunk of the same row, straight from LDS
+    const uint32_t pslot = swizzle(lane ^ rope.partner);
+#pragma unroll
+    for (int k = 0; k < kTileIters; ++k) data[k] = rotate_chunk(data[k], lds[k * kWaveSize + pslot], rope);
+  }
   store_tile(my_row, lane, lpr_shift, data);
 }
 
-template <bool KEEP>
-__device__ inline void copy_tile(const UnpackArgs& a, const CardGeom& g, uint32_t r0, uint32_t n_rows, uint32_t lane,
-                                 uint32_t& bad) {
+template <bool KEEP, bool ROPE>
+__device__ inline void copy_tile(const uint8_t* card, const CardGeom& g, uint32_t r0, uint32_t n_rows, uint64_t my_row,
+                                 uint32_t lane, const RopeLane& rope) {
   const uint32_t lpr_shift = g.lpr_shift;
-  const uint32_t tile_rows = kTileChunks >> lpr_shift;
   const uint32_t row_bytes = g.head_dim * 2u;
-  const uint64_t my_row = tile_row_address(a, g, 3, r0, n_rows, lane, tile_rows, bad);
-  const uint8_t* src = a.card + g.off_fp16 + (uint64_t)r0 * row_bytes;
+  const uint8_t* src = card + g.off_fp16 + (uint64_t)r0 * row_bytes;
   const uint64_t seg_left = ((uint64_t)n_rows - r0) * row_bytes;   // bytes from the tile start to the segment end
   u32x4 data[kTileIters];
 #pragma unroll
@@ -143,6 +194,15 @@ __device__ inline void copy_tile(const UnpackArgs& a, const CardGeom& g, uint32_
     const uint64_t off = (uint64_t)(k * kWaveSize + lane) * 16u;
     data[k] = (u32x4)(0u);
     if (off < seg_left) data[k] = card_load<KEEP>(reinterpret_cast<const u32x4*>(src + off));
+  }
+  if (ROPE) {
+#pragma unroll
+    for (int k = 0; k < kTileIters; ++k) {
+      u32x4 y;
+      y.x = __shfl_xor(data[k].x, rope.partner, kWaveSize); y.y = __shfl_xor(data[k].y, rope.partner, kWaveSize);
+      y.z = __shfl_xor(data[k].z, rope.partner, kWaveSize); y.w = __shfl_xor(data[k].w, rope.partner, kWaveSize);
+      data[k] = rotate_chunk(data[k], y, rope);
+    }
   }
   store_tile(my_row, lane, lpr_shift, data);
 }
@@ -171,6 +231,7 @@ __global__ __launch_bounds__(kBlockThreads) void unpack_kernel(UnpackArgs a) {
   // front to back; cards that fit, or that are several times larger, are indifferent).
   uint32_t bad = 0;
   uint32_t cum = 0;
+  const RopeLane no_rope = {};
 #pragma unroll
   for (int c = 3; c >= 0; --c) {
     const uint32_t n_rows = g.planes * g.n[c];
@@ -179,13 +240,103 @@ __global__ __launch_bounds__(kBlockThreads) void unpack_kernel(UnpackArgs a) {
     const uint32_t first = (gw + n_waves - cum) % n_waves;
     for (uint32_t i = first; i < tiles; i += n_waves) {
       const uint32_t r0 = (tiles - 1 - i) * tile_rows;
-      if (c == 0) unpack_tile<2, G, KEEP>(a, g, 0, r0, n_rows, lane, my_lds, bad);
-      if (c == 1) unpack_tile<4, G, KEEP>(a, g, 1, r0, n_rows, lane, my_lds, bad);
-      if (c == 2) unpack_tile<8, G, KEEP>(a, g, 2, r0, n_rows, lane, my_lds, bad);
-      if (c == 3) copy_tile<KEEP>(a, g, r0, n_rows, lane, bad);
+      const uint64_t my_row = tile_row_address(a, g, c, r0, n_rows, lane, tile_rows, bad);
+      if (c == 0) unpack_tile<2, G, KEEP, false>(a.card, g, 0, r0, n_rows, my_row, lane, my_lds, no_rope);
+      if (c == 1) unpack_tile<4, G, KEEP, false>(a.card, g, 1, r0, n_rows, my_row, lane, my_lds, no_rope);
+      if (c == 2) unpack_tile<8, G, KEEP, false>(a.card, g, 2, r0, n_rows, my_row, lane, my_lds, no_rope);
+      if (c == 3) copy_tile<KEEP, false>(a.card, g, r0, n_rows, my_row, lane, no_rope);
     }
     cum = (cum + tiles) % n_waves;
   }
+  if (bad && a.status) atomicOr(a.status, QKV_STATUS_BAD_ORDER);
+}
+
+// Row address for injection: plane p of the card -> (K or V, layer, head) -> the caller's
+// per-layer tensor.  Only planes of the layer range are ever asked for.
+__device__ inline uint64_t inject_row_address(const InjectArgs& a, const CardGeom& g, int c, uint32_t kv, uint32_t r0,
+                                              uint32_t seg_hi, uint32_t lane, uint32_t tile_rows, uint32_t& bad) {
+  uint64_t addr = 0;
+  const uint32_t r = r0 + lane;
+  if (lane < tile_rows && r < seg_hi) {
+    const uint32_t n = g.n[c];
+    const uint32_t p = r / n;
+    const uint32_t j = r - p * n;
+    const uint32_t t = reinterpret_cast<const uint32_t*>(a.card + g.off_order)[g.base[c] + j];
+    const uint32_t pl = p - kv * (g.planes >> 1);
+    const uint32_t layer = pl / a.kv_heads;
+    const uint32_t head = pl - layer * a.kv_heads;
+    const uint32_t li = min(layer - a.layer_begin, a.layer_count - 1u);
+    if (t < g.tokens) {
+      addr = (kv ? a.v_layer[li] : a.k_layer[li]) + head * a.head_stride + t * a.token_stride;
+    } else {
+      bad = 1;
+    }
+  }
+  return addr;
+}
+
+// One (class, K or V) range of the card's rows for the layer range: its tiles are dealt to the
+// waves round-robin, continuing where the previous range stopped.
+template <int C, int KV, int G, bool KEEP>
+__device__ inline void inject_range(const InjectArgs& a, const CardGeom& g, const RopeLane& rope, uint32_t gw,
+                                    uint32_t n_waves, uint32_t lane, u32x4* lds, uint32_t& cum, uint32_t& bad) {
+  const uint32_t n = g.n[C];
+  if (n == 0) return;
+  const uint32_t tile_rows = kTileChunks >> g.lpr_shift;
+  const uint32_t seg_lo = ((uint32_t)KV * (g.planes >> 1) + a.layer_begin * a.kv_heads) * n;
+  const uint32_t seg_rows = a.layer_count * a.kv_heads * n;
+  const uint32_t seg_hi = seg_lo + seg_rows;
+  const uint32_t tiles = (seg_rows + tile_rows - 1) / tile_rows;
+  const bool rot = KV == 0 && a.rope != 0;
+  const uint32_t first = (gw + n_waves - cum) % n_waves;
+  for (uint32_t i = first; i < tiles; i += n_waves) {
+    const uint32_t r0 = seg_lo + (tiles - 1 - i) * tile_rows;
+    const uint64_t my_row = inject_row_address(a, g, C, (uint32_t)KV, r0, seg_hi, lane, tile_rows, bad);
+    if (C == 3) {
+      if (rot) copy_tile<KEEP, true>(a.card, g, r0, seg_hi, my_row, lane, rope);
+      else copy_tile<KEEP, false>(a.card, g, r0, seg_hi, my_row, lane, rope);
+    } else {
+      constexpr int W = C == 0 ? 2 : C == 1 ? 4 : 8;
+      if (rot) unpack_tile<W, G, KEEP, true>(a.card, g, C, r0, seg_hi, my_row, lane, lds, rope);
+      else unpack_tile<W, G, KEEP, false>(a.card, g, C, r0, seg_hi, my_row, lane, lds, rope);
+    }
+  }
+  cum = (cum + tiles) % n_waves;
+}
+
+template <int G, bool KEEP>
+__global__ __launch_bounds__(kBlockThreads) void inject_kernel(InjectArgs a) {
+  __shared__ u32x4 lds[kWavesPerBlock][kTileChunks];
+  CardGeom g;
+  if (!card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, g)) return;
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t wave = threadIdx.x >> 6;
+  const uint32_t gw = blockIdx.x * kWavesPerBlock + wave;
+  const uint32_t n_waves = gridDim.x * kWavesPerBlock;
+  u32x4* my_lds = lds[wave];
+
+  // chunk 64 k + lane of a tile is chunk (lane mod chunks-per-row) of its row, whatever k
+  RopeLane rope = {};
+  if (a.rope) {
+    const uint32_t half = (1u << g.lpr_shift) >> 1;             // chunks in half a row
+    const uint32_t qc = lane & (2u * half - 1u);
+    rope.partner = half;
+    rope.flip = qc < half ? 0x80000000u : 0u;
+    const uint32_t i0 = 8u * (qc & (half - 1u));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { rope.c[e] = a.cs[i0 + e][0]; rope.s[e] = a.cs[i0 + e][1]; }
+  }
+
+  // from the card's end to its start, as the dense kernel does
+  uint32_t bad = 0, cum = 0;
+  inject_range<3, 1, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<3, 0, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<2, 1, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<2, 0, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<1, 1, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<1, 0, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<0, 1, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<0, 0, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
   if (bad && a.status) atomicOr(a.status, QKV_STATUS_BAD_ORDER);
 }
 
@@ -219,6 +370,56 @@ hipError_t launch_unpack(const uint8_t* card, uint64_t card_bytes, const CardGeo
     case 128: hipLaunchKernelGGL((unpack_kernel<64, false>), grid, block, 0, stream, a); break;
     case 257: hipLaunchKernelGGL((unpack_kernel<128, true>), grid, block, 0, stream, a); break;
     default: hipLaunchKernelGGL((unpack_kernel<128, false>), grid, block, 0, stream, a); break;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_inject(const uint8_t* card, uint64_t card_bytes, const CardGeom& expect, uint32_t layer_begin,
+                         uint32_t layer_count, void* const* k_layers, void* const* v_layers, uint64_t head_stride_bytes,
+                         uint64_t token_stride_bytes, const float (*cos_sin)[2], uint32_t* status, hipStream_t stream) {
+  InjectArgs a;
+  a.card = card;
+  a.card_bytes = card_bytes;
+  a.layers = expect.layers; a.kv_heads = expect.kv_heads; a.head_dim = expect.head_dim; a.group_size = expect.group_size;
+  a.tokens = expect.tokens;
+  a.layer_begin = layer_begin;
+  a.layer_count = layer_count;
+  a.head_stride = head_stride_bytes;
+  a.token_stride = token_stride_bytes;
+  a.rope = cos_sin != nullptr;
+  a.status = status;
+  for (uint32_t i = 0; i < QKV_INJECT_MAX_LAYERS; ++i) {
+    a.k_layer[i] = i < layer_count ? reinterpret_cast<uint64_t>(k_layers[i]) : 0;
+    a.v_layer[i] = i < layer_count ? reinterpret_cast<uint64_t>(v_layers[i]) : 0;
+  }
+  for (uint32_t i = 0; i < 128; ++i) {
+    const bool used = cos_sin != nullptr && i < expect.head_dim / 2;
+    a.cs[i][0] = used ? cos_sin[i][0] : 1.0f;
+    a.cs[i][1] = used ? cos_sin[i][1] : 0.0f;
+  }
+  if (status) {
+    UnpackArgs u;
+    u.card = card; u.card_bytes = card_bytes;
+    u.layers = expect.layers; u.kv_heads = expect.kv_heads; u.head_dim = expect.head_dim; u.group_size = expect.group_size;
+    u.tokens = expect.tokens;
+    u.k_out = nullptr; u.v_out = nullptr; u.status = status;
+    hipLaunchKernelGGL(unpack_status_kernel, dim3(1), dim3(kWaveSize), 0, stream, u);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  // worst split of the tokens over the classes; every (class, K or V) range may end in a partial tile
+  const uint32_t tile_rows = kTileChunks >> expect.lpr_shift;
+  const uint64_t rows = 2ull * layer_count * expect.kv_heads * expect.tokens;
+  const uint64_t tiles = (rows + tile_rows - 1) / tile_rows + 8;
+  const dim3 grid(grid_blocks(tiles)), block(kBlockThreads);
+  const bool keep = card_bytes <= kCacheResidentCardBytes;
+  switch (expect.group_size * 2 + (keep ? 1 : 0)) {
+    case 65: hipLaunchKernelGGL((inject_kernel<32, true>), grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((inject_kernel<32, false>), grid, block, 0, stream, a); break;
+    case 129: hipLaunchKernelGGL((inject_kernel<64, true>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((inject_kernel<64, false>), grid, block, 0, stream, a); break;
+    case 257: hipLaunchKernelGGL((inject_kernel<128, true>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((inject_kernel<128, false>), grid, block, 0, stream, a); break;
   }
   return hipGetLastError();
 }
