@@ -81,6 +81,10 @@ def main():
                     help="card / output buffer sets rotated over the steps, so that a card is never written over "
                          "its own copy still sitting in the 256 MB memory-side cache (that would hide its HBM "
                          "write-back: 223 instead of 244 us for quantize_pack at 8K with a single set)")
+    ap.add_argument("--inject-layout", default="separate", choices=["separate", "pool", "dense"],
+                    help="where the per-layer injection writes: one allocation per layer tensor with room for a 64-token "
+                         "prefix (as frameworks keep their caches), views of one pooled allocation, or the dense output "
+                         "tensors of the handoff itself (same addresses as qkv_unpack_dequant)")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a captured graph (reported beside the eager figure)")
     ap.add_argument("--cpu-layers", type=int, default=0,
@@ -213,6 +217,52 @@ def main():
                   "frac_hbm_peak": round(att_bytes / (att_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                   "dense_cache_gbs_equivalent": round(kv_bytes / (att_ms * 1e-3) / 1e9, 1)}
 
+    # injection into per-layer caches (one key and one value tensor per layer, room for a prefix), with and
+    # without realigning the keys, in one call and layer by layer
+    inject = None
+    if L <= 64:
+        prefix, cap = 64, T + 64
+        if args.inject_layout == "dense":
+            prefix, cap = 0, T
+            per_layer = [(K_out[l], V_out[l]) for l in range(L)]
+        elif args.inject_layout == "pool":
+            pool = torch.empty((L, 2, H, cap, D), dtype=torch.float16, device=dev)
+            per_layer = [(pool[l, 0], pool[l, 1]) for l in range(L)]
+        else:
+            per_layer = [(torch.empty((H, cap, D), dtype=torch.float16, device=dev), torch.empty((H, cap, D), dtype=torch.float16, device=dev))
+                         for _ in range(L)]
+        kls = [k[:, prefix:prefix + T] for k, _ in per_layer]
+        vls = [v[:, prefix:prefix + T] for _, v in per_layer]
+        n_inj = max(10, args.steps // 4)
+
+        def timed(fn):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(n_inj):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n_inj
+
+        dense_ms = timed(lambda: qkv.unpack_dequant(card, desc, K_out, V_out))     # same loop, for comparison
+        plain_ms = timed(lambda: qkv.inject_layers(card, desc, kls, vls, 0))
+        rope_ms = timed(lambda: qkv.inject_layers(card, desc, kls, vls, 0, rope_base=500000.0, rope_delta=prefix))
+
+        def by_layer():
+            for l in range(L):
+                qkv.inject_layers(card, desc, kls[l:l + 1], vls[l:l + 1], l, rope_base=500000.0, rope_delta=prefix)
+
+        layer_ms = timed(by_layer)
+        inject = {"call": "qkv_inject_layers", "layers": L, "calls": n_inj, "layout": args.inject_layout,
+                  "unpack_dequant_same_loop_ms": round(dense_ms, 4), "one_call_ms": round(plain_ms, 4), "one_call_realigned_ms": round(rope_ms, 4),
+                  "layer_by_layer_realigned_ms": round(layer_ms, 4),
+                  "frac_hbm_peak": round(moved / (plain_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                  "frac_hbm_peak_realigned": round(moved / (rope_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del per_layer, kls, vls
+
     # the controller in front of the handoff: features -> scores -> widths (objective-greedy), timed on its own
     feats = qkv_synth.make_features(T, cfg["data_seed"] + 23, dev)
     params = qkv.Controller.make(*[a.cpu() for a in qkv_synth.make_controller(cfg["data_seed"] + 24)])
@@ -281,6 +331,7 @@ def main():
         "copy_ceiling_gbs": round(copy_gbs, 1),
         "card_attend": attend,
         "controller": controller,
+        "inject_layers": inject,
     }
     if not args.no_cpu:
         layers = args.cpu_layers if args.cpu_layers > 0 else (L * 8192) // max(T, 8192)

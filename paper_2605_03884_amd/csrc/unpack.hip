@@ -276,8 +276,9 @@ __device__ inline uint64_t inject_row_address(const InjectArgs& a, const CardGeo
 }
 
 // One (class, K or V) range of the card's rows for the layer range: its tiles are dealt to the
-// waves round-robin, continuing where the previous range stopped.
-template <int C, int KV, int G, bool KEEP>
+// waves round-robin, continuing where the previous range stopped.  (K and V as separate
+// instances of this code measure faster than one instance looping over both.)
+template <int C, int KV, int G, bool KEEP, bool ROPE>
 __device__ inline void inject_range(const InjectArgs& a, const CardGeom& g, const RopeLane& rope, uint32_t gw,
                                     uint32_t n_waves, uint32_t lane, u32x4* lds, uint32_t& cum, uint32_t& bad) {
   const uint32_t n = g.n[C];
@@ -287,24 +288,22 @@ __device__ inline void inject_range(const InjectArgs& a, const CardGeom& g, cons
   const uint32_t seg_rows = a.layer_count * a.kv_heads * n;
   const uint32_t seg_hi = seg_lo + seg_rows;
   const uint32_t tiles = (seg_rows + tile_rows - 1) / tile_rows;
-  const bool rot = KV == 0 && a.rope != 0;
+  constexpr bool rot = KV == 0 && ROPE;            // only keys depend on the position
   const uint32_t first = (gw + n_waves - cum) % n_waves;
   for (uint32_t i = first; i < tiles; i += n_waves) {
     const uint32_t r0 = seg_lo + (tiles - 1 - i) * tile_rows;
     const uint64_t my_row = inject_row_address(a, g, C, (uint32_t)KV, r0, seg_hi, lane, tile_rows, bad);
     if (C == 3) {
-      if (rot) copy_tile<KEEP, true>(a.card, g, r0, seg_hi, my_row, lane, rope);
-      else copy_tile<KEEP, false>(a.card, g, r0, seg_hi, my_row, lane, rope);
+      copy_tile<KEEP, rot>(a.card, g, r0, seg_hi, my_row, lane, rope);
     } else {
       constexpr int W = C == 0 ? 2 : C == 1 ? 4 : 8;
-      if (rot) unpack_tile<W, G, KEEP, true>(a.card, g, C, r0, seg_hi, my_row, lane, lds, rope);
-      else unpack_tile<W, G, KEEP, false>(a.card, g, C, r0, seg_hi, my_row, lane, lds, rope);
+      unpack_tile<W, G, KEEP, rot>(a.card, g, C, r0, seg_hi, my_row, lane, lds, rope);
     }
   }
   cum = (cum + tiles) % n_waves;
 }
 
-template <int G, bool KEEP>
+template <int G, bool KEEP, bool ROPE>
 __global__ __launch_bounds__(kBlockThreads) void inject_kernel(InjectArgs a) {
   __shared__ u32x4 lds[kWavesPerBlock][kTileChunks];
   CardGeom g;
@@ -317,7 +316,7 @@ __global__ __launch_bounds__(kBlockThreads) void inject_kernel(InjectArgs a) {
 
   // chunk 64 k + lane of a tile is chunk (lane mod chunks-per-row) of its row, whatever k
   RopeLane rope = {};
-  if (a.rope) {
+  if (ROPE) {
     const uint32_t half = (1u << g.lpr_shift) >> 1;             // chunks in half a row
     const uint32_t qc = lane & (2u * half - 1u);
     rope.partner = half;
@@ -329,14 +328,14 @@ __global__ __launch_bounds__(kBlockThreads) void inject_kernel(InjectArgs a) {
 
   // from the card's end to its start, as the dense kernel does
   uint32_t bad = 0, cum = 0;
-  inject_range<3, 1, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
-  inject_range<3, 0, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
-  inject_range<2, 1, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
-  inject_range<2, 0, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
-  inject_range<1, 1, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
-  inject_range<1, 0, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
-  inject_range<0, 1, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
-  inject_range<0, 0, G, KEEP>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<3, 1, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<3, 0, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<2, 1, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<2, 0, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<1, 1, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<1, 0, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<0, 1, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<0, 0, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
   if (bad && a.status) atomicOr(a.status, QKV_STATUS_BAD_ORDER);
 }
 
@@ -413,13 +412,20 @@ hipError_t launch_inject(const uint8_t* card, uint64_t card_bytes, const CardGeo
   const uint64_t tiles = (rows + tile_rows - 1) / tile_rows + 8;
   const dim3 grid(grid_blocks(tiles)), block(kBlockThreads);
   const bool keep = card_bytes <= kCacheResidentCardBytes;
-  switch (expect.group_size * 2 + (keep ? 1 : 0)) {
-    case 65: hipLaunchKernelGGL((inject_kernel<32, true>), grid, block, 0, stream, a); break;
-    case 64: hipLaunchKernelGGL((inject_kernel<32, false>), grid, block, 0, stream, a); break;
-    case 129: hipLaunchKernelGGL((inject_kernel<64, true>), grid, block, 0, stream, a); break;
-    case 128: hipLaunchKernelGGL((inject_kernel<64, false>), grid, block, 0, stream, a); break;
-    case 257: hipLaunchKernelGGL((inject_kernel<128, true>), grid, block, 0, stream, a); break;
-    default: hipLaunchKernelGGL((inject_kernel<128, false>), grid, block, 0, stream, a); break;
+  const int variant = (int)expect.group_size * 4 + (keep ? 2 : 0) + (a.rope ? 1 : 0);
+  switch (variant) {
+    case 131: hipLaunchKernelGGL((inject_kernel<32, true, true>), grid, block, 0, stream, a); break;
+    case 130: hipLaunchKernelGGL((inject_kernel<32, true, false>), grid, block, 0, stream, a); break;
+    case 129: hipLaunchKernelGGL((inject_kernel<32, false, true>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((inject_kernel<32, false, false>), grid, block, 0, stream, a); break;
+    case 259: hipLaunchKernelGGL((inject_kernel<64, true, true>), grid, block, 0, stream, a); break;
+    case 258: hipLaunchKernelGGL((inject_kernel<64, true, false>), grid, block, 0, stream, a); break;
+    case 257: hipLaunchKernelGGL((inject_kernel<64, false, true>), grid, block, 0, stream, a); break;
+    case 256: hipLaunchKernelGGL((inject_kernel<64, false, false>), grid, block, 0, stream, a); break;
+    case 515: hipLaunchKernelGGL((inject_kernel<128, true, true>), grid, block, 0, stream, a); break;
+    case 514: hipLaunchKernelGGL((inject_kernel<128, true, false>), grid, block, 0, stream, a); break;
+    case 513: hipLaunchKernelGGL((inject_kernel<128, false, true>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((inject_kernel<128, false, false>), grid, block, 0, stream, a); break;
   }
   return hipGetLastError();
 }
