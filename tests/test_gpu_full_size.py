@@ -149,3 +149,51 @@ def test_32k_four_hops_sampled_planes():
             assert torch.equal(K_out[:, :, t], K[:, :, t])
         K, K_out = K_out, K
         V, V_out = V_out, V
+
+
+def test_8k_injection_into_per_layer_caches_realigned():
+    """The 8K workload injected as the benchmark does it (all 32 layers in one call, one tensor per layer with a
+    64-token prefix, keys moved by 64 positions), sampled layers against the oracle, then the same layers once
+    more through single-layer calls."""
+    from oracle import inject_ref
+    cfg = qkv_synth.CONFIGS["llama8b_8k_b3"]
+    L, H, T, D, G = cfg["layers"], cfg["kv_heads"], cfg["tokens"], cfg["head_dim"], cfg["group_size"]
+    say("8K inject: generating")
+    K, V = qkv_synth.make_kv(L, H, T, D, cfg["data_seed"], cfg["kind"], device=DEV)
+    bits, counts = widths_for(cfg, DEV)
+    desc = qkv.Desc.make(L, H, T, D, G)
+    card = torch.empty(qkv.card_bytes(desc, counts), dtype=torch.uint8, device=DEV)
+    qkv.quantize_pack(desc, K, V, bits, counts, card)
+    prefix, cap = 64, T + 64
+    canary = 0x7E11
+    mk = lambda: torch.zeros((H, cap, D), dtype=torch.int16, device=DEV).fill_(canary).view(torch.float16)
+    kc = [mk() for _ in range(L)]
+    vc = [mk() for _ in range(L)]
+    status = torch.ones(1, dtype=torch.int32, device=DEV)
+    say("8K inject: one call")
+    qkv.inject_layers(card, desc, [k[:, prefix:] for k in kc], [v[:, prefix:] for v in vc], 0, rope_base=500000.0,
+                      rope_delta=prefix, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    say("8K inject: oracle")
+    rd = ref.make_desc(L, H, T, D, G)
+    want_card = ref.quantize_pack(rd, K.cpu().numpy(), V.cpu().numpy(), bits.cpu().numpy(), counts)
+    assert np.array_equal(card.cpu().numpy(), want_card)
+    wk, wv = ref.unpack_dequant(want_card, rd)
+    table = inject_ref.rope_table(D, 500000.0, prefix)
+    sampled = (0, 13, 31)
+    for l in sampled:
+        gk = kc[l].view(torch.int16).cpu().numpy().view(np.uint16)
+        gv = vc[l].view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.all(gk[:, :prefix] == canary) and np.all(gv[:, :prefix] == canary)
+        assert np.array_equal(gv[:, prefix:], wv[l]), l
+        assert np.array_equal(gk[:, prefix:], inject_ref.rope_rotate(wk[l], *table)), l
+    say("8K inject: layer by layer")
+    k1 = {l: mk() for l in sampled}
+    v1 = {l: mk() for l in sampled}
+    for l in sampled:
+        qkv.inject_layers(card, desc, [k1[l][:, prefix:]], [v1[l][:, prefix:]], l, rope_base=500000.0, rope_delta=prefix)
+    torch.cuda.synchronize()
+    for l in sampled:
+        assert torch.equal(k1[l].view(torch.int16), kc[l].view(torch.int16))
+        assert torch.equal(v1[l].view(torch.int16), vc[l].view(torch.int16))
