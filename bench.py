@@ -11,6 +11,7 @@ workload.
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -68,6 +69,75 @@ def cpu_baseline(cfg, K_dev, V_dev, bits_host, budget, layers):
     dt = time.perf_counter() - t0
     kv_bytes = 2 * layers * H * T * D * 2
     return kv_bytes / dt / 1e9, dt
+
+
+def cpu_baseline_threads(cfg, K_dev, V_dev, bits_host, layers, threads):
+    """The same unchanged oracle on disjoint layers in `threads` host threads (the planes of different layers
+    are independent given the widths); every thread builds and unpacks the one-layer card of its layers."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import ref
+    T, D, H, G = cfg["tokens"], cfg["head_dim"], cfg["kv_heads"], cfg["group_size"]
+    K = K_dev[:layers].cpu().numpy()
+    V = V_dev[:layers].cpu().numpy()
+    counts = ref.count_bits(bits_host)
+    d1 = ref.make_desc(1, H, T, D, G)
+    ref.lib()
+
+    def one(l):
+        card = ref.quantize_pack(d1, K[l:l + 1], V[l:l + 1], bits_host, counts)
+        ref.unpack_dequant(card, d1)
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        list(pool.map(one, range(layers)))
+    dt = time.perf_counter() - t0
+    return 2 * layers * H * T * D * 2 / dt / 1e9, dt
+
+
+def hop_report(qkv, cfg, K, V, desc, dev):
+    """The multi-hop workload: every hop quantizes what the previous hop's receiver rebuilt, at that hop's budget
+    (paper Sec. 3.2, challenge 3: error accumulates across hops).  Per hop: class counts, kernel times by HIP
+    events, and the signal-to-noise ratio of the rebuilt cache against the original one."""
+    T = cfg["tokens"]
+    seeds, budgets = cfg["bits"][1], cfg["bits"][2]
+    src_k, src_v = K, V
+    out = []
+    k_out, v_out = torch.empty_like(K), torch.empty_like(V)
+
+    def snr_db(ref_t, got_t):
+        num = den = 0.0
+        for l in range(ref_t.shape[0]):                # layer by layer: no 4 GiB temporaries
+            r = ref_t[l].float()
+            num += float((r * r).sum(dtype=torch.float64))
+            den += float(((got_t[l].float() - r) ** 2).sum(dtype=torch.float64))
+        return round(10.0 * math.log10(num / den), 2) if den > 0 else float("inf")
+
+    for hop, (seed, budget) in enumerate(zip(seeds, budgets)):
+        scores = qkv_synth.make_scores(T, seed, dev)
+        bits, counts = qkv.assign_bits(scores, budget)
+        card = torch.empty(qkv.card_bytes(desc, counts), dtype=torch.uint8, device=dev)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        for rep in range(3):                            # the last repetition is the one reported
+            ev[0].record()
+            qkv.quantize_pack(desc, src_k, src_v, bits, counts, card)
+            ev[1].record()
+            qkv.unpack_dequant(card, desc, k_out, v_out)
+            ev[2].record()
+            torch.cuda.synchronize()
+        moved = K.numel() * 4 + card.numel()
+        pack_ms, unpack_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
+        out.append({"hop": hop + 1, "budget": budget, "counts_2_4_8_16": counts, "card_bytes": card.numel(),
+                    "quantize_pack_ms": round(pack_ms, 4), "unpack_dequant_ms": round(unpack_ms, 4),
+                    "pct_hbm_peak": [round(100 * moved / (pack_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 1),
+                                     round(100 * moved / (unpack_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 1)],
+                    "snr_db_k": snr_db(K, k_out), "snr_db_v": snr_db(V, v_out)})
+        if hop == 0:
+            src_k, src_v = torch.empty_like(K), torch.empty_like(V)
+        src_k.copy_(k_out)
+        src_v.copy_(v_out)
+        del card
+    return out
 
 
 def main():
@@ -186,6 +256,13 @@ def main():
 
     assign_ms, pack_ms, unpack_ms = avg_ms(0, 1), avg_ms(1, 2), avg_ms(2, 3)
     plan_ms, fill_ms = avg_ms(1, 4), avg_ms(4, 2)
+
+    def spread(a, b):
+        v = sorted(e[a].elapsed_time(e[b]) for e in evs)
+        return {"median": round(v[len(v) // 2], 4), "min": round(v[0], 4), "max": round(v[-1], 4)}
+
+    stage_spread = {"assign_bits": spread(0, 1), "quantize_pack": spread(1, 2), "quantize_pack.fill": spread(4, 2),
+                    "unpack_dequant": spread(2, 3)}
 
     # the card just built must be readable and clean
     _, c2, avg_bits, status = qkv.card_peek(card)
@@ -326,6 +403,7 @@ def main():
         "pct_hbm_peak": {"quantize_pack": round(100 * moved / (pack_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
                          "quantize_pack.fill": round(100 * legs[0]["frac"], 2),
                          "unpack_dequant": round(100 * legs[1]["frac"], 2)},
+        "stages_ms_spread": stage_spread,
         "ms_per_step_with_events": round(ms_per_step_events, 4),
         "ms_per_step_graph_replay": None if graph_ms is None else round(graph_ms, 4),
         "copy_ceiling_gbs": round(copy_gbs, 1),
@@ -340,6 +418,13 @@ def main():
         out["cpu_baseline"] = {"value": round(v, 4), "unit": out["unit"], "cores": 1, "kind": "oracle",
                                "sample": "first %d of %d layers of the same tensors, all tokens, same widths; %.1f s"
                                          % (layers, L, secs)}
+        threads = max(1, min(16, os.cpu_count() or 1, layers))
+        v2, secs2 = cpu_baseline_threads(cfg, K, V, bits.cpu().numpy(), layers, threads)
+        out["cpu_baseline_all_cores"] = {"value": round(v2, 4), "unit": out["unit"], "cores": threads, "kind": "oracle",
+                                         "sample": "the same %d layers, one layer per task, quantize_pack + unpack_dequant "
+                                                   "only (widths given); %.1f s" % (layers, secs2)}
+    if cfg["bits"][0] == "hops":
+        out["hops"] = hop_report(qkv, cfg, K, V, desc, dev)
     print(json.dumps(out))
     return 0
 
