@@ -22,6 +22,9 @@
 //            holds 4 consecutive tokens x 8 dimensions, decodes them into 8 MFMA B operands,
 //            and 2 x 8 MFMAs (softmax weights split into a high and a low fp16 part)
 //            accumulate p.V^ for 16 tokens x up to 16 query heads.
+#include <cmath>
+#include <cstdlib>
+
 #include "qkv_common.h"
 #include "qkv_decode.h"
 
@@ -500,11 +503,29 @@ __global__ void attend_prepare_kernel(AttendArgs a) {
 
 }  // namespace
 
-// Tokens per task and tasks per (layer, kv head) for a given shape: the scores of one task
-// (chunk tokens x query heads padded to a multiple of 4) fill 8 KiB of LDS.
-void attend_plan(uint64_t tokens, uint32_t rep, uint32_t* chunk, uint32_t* max_tasks) {
+// Tokens per task and tasks per (layer, kv head) for a given shape.  The scores of one task
+// (chunk tokens x query heads padded to a multiple of 4) must fit 8 KiB of LDS; below that
+// limit the chunk is chosen so that the tasks fill the chip's wave slots a whole number of
+// times: one wave per task, three waves per SIMD (registers and LDS), 256 compute units.  At
+// 8K tokens x 256 (layer, head) pairs, 512-token tasks would fill the slots 1.6 times - the
+// second pass runs 40 % empty - while 384-token tasks fill them 1.9 times (117 -> 107 us).
+void attend_plan(uint64_t tokens, uint32_t rep, uint64_t pairs, uint32_t* chunk, uint32_t* max_tasks) {
   const uint32_t r4 = (rep + 3u) & ~3u;
-  *chunk = (kLdsFloatsPerWave / r4) & ~15u;      // whole rounds of 16 tokens
+  const uint32_t limit = (kLdsFloatsPerWave / r4) & ~15u;      // whole rounds of 16 tokens
+  const double slots = 256.0 * 4.0 * 3.0;
+  uint32_t best = limit;
+  double best_fill = 0.0;
+  for (uint32_t c = limit; c >= 128u && c >= limit / 4u; c -= 16u) {
+    // about two of the four classes end in a partly filled task
+    const double passes = (double)pairs * (double)((tokens + c - 1) / c + 2u) / slots;
+    const double fill = passes / std::ceil(passes);
+    if (fill > best_fill + 0.03) { best_fill = fill; best = c; }   // prefer the larger task unless it clearly loses
+  }
+  *chunk = best;
+  if (const char* e = std::getenv("QKV_ATTEND_CHUNK")) {          // tuning knob
+    const uint32_t v = (uint32_t)std::strtoul(e, nullptr, 10) & ~15u;
+    if (v >= 16u && v <= limit) *chunk = v;
+  }
   *max_tasks = (uint32_t)((tokens + *chunk - 1) / *chunk) + 3u;   // every class may end with a partly filled task
 }
 
@@ -520,7 +541,7 @@ hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeo
   a.q_heads = q_heads;
   a.rep = q_heads / expect.kv_heads;
   a.scale_log2 = softmax_scale * 1.44269504088896340736f;
-  attend_plan(expect.tokens, a.rep, &a.chunk, &a.max_tasks);
+  attend_plan(expect.tokens, a.rep, (uint64_t)expect.layers * expect.kv_heads, &a.chunk, &a.max_tasks);
   const uint64_t pairs = (uint64_t)expect.layers * expect.kv_heads;
   a.part_o = workspace;
   a.part_ml = workspace + pairs * a.max_tasks * a.rep * 128u;

@@ -140,7 +140,7 @@ hipError_t launch_inject(const uint8_t* card, uint64_t card_bytes, const CardGeo
                          uint64_t token_stride_bytes, const float (*cos_sin)[2], uint32_t* status, hipStream_t stream);
 hipError_t launch_assign(const float* scores, uint32_t tokens, const uint32_t cuts[3], uint8_t* bits,
                          hipStream_t stream);
-void attend_plan(uint64_t tokens, uint32_t rep, uint32_t* chunk, uint32_t* max_tasks);
+void attend_plan(uint64_t tokens, uint32_t rep, uint64_t pairs, uint32_t* chunk, uint32_t* max_tasks);
 hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeom& expect, const void* q,
                          uint32_t q_heads, float softmax_scale, float* out, float* lse, float* workspace,
                          uint32_t* status, hipStream_t stream);
