@@ -35,6 +35,10 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRoundTokens = 16;
+#ifndef QKV_ATTEND_V_SELECT
+#define QKV_ATTEND_V_SELECT 1
+#endif
+constexpr bool kSelectV = QKV_ATTEND_V_SELECT != 0;        // 2-bit value rows decoded by selection
 #ifndef QKV_ATTEND_WAVES_PER_BLOCK
 #define QKV_ATTEND_WAVES_PER_BLOCK 1
 #endif
@@ -43,7 +47,7 @@ constexpr int kAttendWaves = QKV_ATTEND_WAVES_PER_BLOCK;   // waves per workgrou
 // (a fetched span is 3 / 5 / 9 / 16 registers at 2 / 4 / 8 / 16 bits).
 template <int W> struct Prefetch { static constexpr int kRounds = (W == 2) ? 4 : (W == 4) ? 3 : (W == 8) ? 2 : 1; };
 #ifndef QKV_ATTEND_LDS_FLOATS
-#define QKV_ATTEND_LDS_FLOATS 2048
+#define QKV_ATTEND_LDS_FLOATS 1536
 #endif
 constexpr int kLdsFloatsPerWave = QKV_ATTEND_LDS_FLOATS;   // scores of one task: chunk tokens x padded query heads
 
@@ -144,6 +148,37 @@ __device__ inline void decode_fetched(const SpanData<W, G>& d, uint32_t (&out)[1
   }
 }
 
+// 2-bit spans decoded by selection instead of arithmetic: a group has only four decoded values
+// x_k = fp16(fma(k, scale, zero)), computed once per span; a table in LDS, indexed by a byte of
+// four codes, holds the two byte selectors that pick (x_c0, x_c1) and (x_c2, x_c3) out of the
+// eight bytes {x_0 .. x_3}.  About one vector instruction per value instead of three.
+__device__ inline void build_select_table(u32x2* table, uint32_t lane) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t b = lane * 4u + i;
+    const uint32_t c0 = b & 3u, c1 = (b >> 2) & 3u, c2 = (b >> 4) & 3u, c3 = b >> 6;
+    table[b] = (u32x2){0x01000100u + 2u * (c0 * 0x0101u + c1 * 0x01010000u),
+                       0x01000100u + 2u * (c2 * 0x0101u + c3 * 0x01010000u)};
+  }
+}
+
+template <int G>
+__device__ inline void decode_fetched_select(const SpanData<2, G>& d, const u32x2* table, uint32_t (&out)[16]) {
+  const float s = half_bits_to_float(d.pair & 0xFFFFu);
+  const float z = half_bits_to_float(d.pair >> 16);
+  const uint32_t x01 = decode_pair(0.0f, 1.0f, s, z);
+  const uint32_t x23 = decode_pair(2.0f, 3.0f, s, z);
+#pragma unroll
+  for (int w = 0; w < 2; ++w) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const u32x2 sel = table[(d.cw[w] >> (8 * j)) & 0xFFu];
+      out[8 * w + 2 * j] = __builtin_amdgcn_perm(x23, x01, sel.x);
+      out[8 * w + 2 * j + 1] = __builtin_amdgcn_perm(x23, x01, sel.y);
+    }
+  }
+}
+
 // ---- value pass helpers -----------------------------------------------------------------------
 //
 // For the weighted sum the MFMA contracts over tokens, so a lane must hold, for one output
@@ -198,10 +233,10 @@ __device__ inline uint32_t decode_two_tokens(float c0, float s0, float z0, float
 // tile: the round's packed rows (16 tokens x up to 256 bytes) followed by 16 x 4 pairs.
 template <int W, int G>
 __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c, uint32_t pair, uint32_t j0, uint32_t j1,
-                                   uint32_t lane, float* lds, uint8_t* tile, uint64_t part) {
+                                   uint32_t lane, float* lds, uint8_t* tile, const u32x2* table, uint64_t part) {
   const uint32_t n = lane & 15u, kq = lane >> 4;          // also (a, kt) of the value pass and (m, k group) of the MFMAs
   const uint32_t R = a.rep, R4 = (R + 3u) & ~3u;
-  const uint32_t chunk = a.chunk;
+  const uint32_t chunk = a.chunk % 192u == 0u ? a.chunk : 96u;      // LDS pitch of a head's scores: the task size, padded
   const uint32_t lh = g.planes >> 1;
   const uint32_t n_c = g.n[c];
   const uint64_t k_row0 = (uint64_t)pair * n_c;            // K plane p = pair, V plane p = L*H + pair
@@ -245,9 +280,10 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
 #pragma unroll
       for (int u = 0; u < kPrefetch; ++u) {
         const uint32_t rd = rd0 + u;
-        if (rd < rounds) {                         // uniform over the wave
+        {                                          // rounds past the task's end see zeros and store -inf
           uint32_t kb[16];
-          decode_fetched<W, G>(buf[u], kb);
+          if constexpr (W == 2) decode_fetched_select<G>(buf[u], table, kb);
+          else decode_fetched<W, G>(buf[u], kb);
           const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
           buf[u] = fetch_span<W, G>(kp, rd + kPrefetch, tn < cnt);
           f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -271,7 +307,9 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   }
 
   // ---- softmax over the task's tokens, head by head (the wave's own LDS accesses are in order)
-  const uint32_t slots = rounds * kRoundTokens;
+  // whole groups of kPrefetch rounds are processed; the task size is a multiple of such a group,
+  // so the padded rounds stay inside the task's share of LDS
+  const uint32_t slots = (rounds + kPrefetch - 1) / kPrefetch * kPrefetch * kRoundTokens;
   for (uint32_t r = 0; r < R4; ++r) {
     float* row = lds + r * chunk;
     float m = -INFINITY;
@@ -315,7 +353,7 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
 #pragma unroll
       for (int u = 0; u < kPrefetch; ++u) {
         const uint32_t rd = rd0 + u;
-        if (rd < rounds) {
+        {                                          // rounds past the task's end add zero weights times zeros
           // rows into LDS as they were loaded: token n, quarter kq
           {
             uint8_t* dst = tile + n * kRowBytes + kq * (4u * W);
@@ -326,12 +364,42 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
               for (int h = 0; h < (W == 16 ? 16 : W) / 4; ++h)
                 reinterpret_cast<u32x4*>(dst)[h] = (u32x4){buf[u].cw[4 * h], buf[u].cw[4 * h + 1], buf[u].cw[4 * h + 2], buf[u].cw[4 * h + 3]};
             }
-            if constexpr (W != 16) pairs_lds[n * 4u + kq] = buf[u].pair;
+            if constexpr (W == 2 && kSelectV) {
+              // the span's four decoded values instead of its (scale, zero): x_k = fp16(fma(k, scale, zero))
+              const float s = half_bits_to_float(buf[u].pair & 0xFFFFu);
+              const float z = half_bits_to_float(buf[u].pair >> 16);
+              reinterpret_cast<u32x2*>(pairs_lds)[n * 4u + kq] = (u32x2){decode_pair(0.0f, 1.0f, s, z), decode_pair(2.0f, 3.0f, s, z)};
+            } else if constexpr (W != 16) {
+              pairs_lds[n * 4u + kq] = buf[u].pair;
+            }
           }
           const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
           buf[u] = fetch_span<W, G>(vp, rd + kPrefetch, tn < cnt);
 
           // pieces of lane (a, kt) = (n, kq): tokens 4 kt + i, dimensions 8 a .. 8 a + 7
+          // B operands: b[e] = {V^[4kt][8a+e], V^[4kt+1][8a+e], V^[4kt+2][8a+e], V^[4kt+3][8a+e]}
+          u32x2 b[8];
+          if constexpr (W == 2 && kSelectV) {
+            // by selection: the piece's two code bytes index the selector table, the selectors pick the
+            // values out of the token's four; then pairs of dimensions are turned into pairs of tokens
+            uint32_t tv[4][4];                     // token i, dimension pair m: {V^[8a+2m], V^[8a+2m+1]}
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const uint32_t piece = *reinterpret_cast<const uint16_t*>(tile + (4u * kq + i) * kRowBytes + n * 2u);
+              const u32x2 x = reinterpret_cast<const u32x2*>(pairs_lds)[(4u * kq + i) * 4u + (n >> 2)];
+              const u32x2 s0 = table[piece & 0xFFu], s1 = table[piece >> 8];
+              tv[i][0] = __builtin_amdgcn_perm(x.y, x.x, s0.x);
+              tv[i][1] = __builtin_amdgcn_perm(x.y, x.x, s0.y);
+              tv[i][2] = __builtin_amdgcn_perm(x.y, x.x, s1.x);
+              tv[i][3] = __builtin_amdgcn_perm(x.y, x.x, s1.y);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;      // high or low halves of two words
+              b[e].x = __builtin_amdgcn_perm(tv[1][e >> 1], tv[0][e >> 1], sel);
+              b[e].y = __builtin_amdgcn_perm(tv[3][e >> 1], tv[2][e >> 1], sel);
+            }
+          } else {
           Piece<W> pc[4];
           uint32_t pr[4];
 #pragma unroll
@@ -343,8 +411,6 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
             else { const u32x4 t = *reinterpret_cast<const u32x4*>(src); pc[i].w[0] = t.x; pc[i].w[1] = t.y; pc[i].w[2] = t.z; pc[i].w[3] = t.w; }
             pr[i] = (W != 16) ? pairs_lds[(4u * kq + i) * 4u + (n >> 2)] : 0u;
           }
-          // B operands: b[e] = {V^[4kt][8a+e], V^[4kt+1][8a+e], V^[4kt+2][8a+e], V^[4kt+3][8a+e]}
-          u32x2 b[8];
           if constexpr (W == 16) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -365,6 +431,7 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
               b[e].x = decode_two_tokens(c0[e], s0, z0, c1[e], s1, z1);
               b[e].y = decode_two_tokens(c2[e], s2, z2, c3[e], s3, z3);
             }
+          }
           }
           // A operands: the weights of head m = n for tokens 4 kt .. 4 kt + 3, high parts and low parts
           u32x4 pw = (u32x4)(0u);
@@ -402,7 +469,8 @@ template <int G>
 __global__ __launch_bounds__(kAttendWaves * kWaveSize) __attribute__((amdgpu_waves_per_eu(2)))
 void attend_kernel(AttendArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[kAttendWaves][kLdsFloatsPerWave];
-  __shared__ __attribute__((aligned(16))) uint8_t tiles[kAttendWaves][16 * 256 + 16 * 16];
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[kAttendWaves][16 * 256 + 16 * 32];
+  __shared__ u32x2 select_table[kAttendWaves][256];
   CardGeom g;
   if (!card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, g))
     return;                                   // uniform over the grid
@@ -440,10 +508,14 @@ void attend_kernel(AttendArgs a) {
   }
   float* my_lds = lds[wave];
   uint8_t* my_tile = tiles[wave];
-  if (cls == 0) attend_task<2, G>(a, g, 0, pair, j0, j1, lane, my_lds, my_tile, part);
-  if (cls == 1) attend_task<4, G>(a, g, 1, pair, j0, j1, lane, my_lds, my_tile, part);
-  if (cls == 2) attend_task<8, G>(a, g, 2, pair, j0, j1, lane, my_lds, my_tile, part);
-  if (cls == 3) attend_task<16, G>(a, g, 3, pair, j0, j1, lane, my_lds, my_tile, part);
+  const u32x2* my_table = select_table[wave];
+  if (cls == 0) {
+    build_select_table(select_table[wave], lane);
+    attend_task<2, G>(a, g, 0, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+  }
+  if (cls == 1) attend_task<4, G>(a, g, 1, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+  if (cls == 2) attend_task<8, G>(a, g, 2, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+  if (cls == 3) attend_task<16, G>(a, g, 3, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
 }
 
 // Merges the partials of one (layer, query head): thread d owns output dimension d.  The
@@ -511,21 +583,21 @@ __global__ void attend_prepare_kernel(AttendArgs a) {
 // second pass runs 40 % empty - while 384-token tasks fill them 1.9 times (117 -> 107 us).
 void attend_plan(uint64_t tokens, uint32_t rep, uint64_t pairs, uint32_t* chunk, uint32_t* max_tasks) {
   const uint32_t r4 = (rep + 3u) & ~3u;
-  const uint32_t limit = (kLdsFloatsPerWave / r4) & ~15u;      // whole rounds of 16 tokens
+  const uint32_t room = kLdsFloatsPerWave / r4;                 // tokens whose scores fit, 96 at least
+  // Tasks are processed in groups of 4, 3, 2 or 1 rounds of 16 tokens, depending on the width; a task size
+  // that all of these divide keeps the padded rounds inside the task's LDS: multiples of 192, or 64 tokens
+  // when fewer than 192 fit (a 64-token task pads to 96 at most).
+  const uint32_t limit = room >= 192u ? room / 192u * 192u : 64u;
   const double slots = 256.0 * 4.0 * 3.0;
   uint32_t best = limit;
   double best_fill = 0.0;
-  for (uint32_t c = limit; c >= 128u && c >= limit / 4u; c -= 16u) {
+  for (uint32_t c = limit; c >= 192u; c -= 192u) {
     // about two of the four classes end in a partly filled task
     const double passes = (double)pairs * (double)((tokens + c - 1) / c + 2u) / slots;
     const double fill = passes / std::ceil(passes);
     if (fill > best_fill + 0.03) { best_fill = fill; best = c; }   // prefer the larger task unless it clearly loses
   }
   *chunk = best;
-  if (const char* e = std::getenv("QKV_ATTEND_CHUNK")) {          // tuning knob
-    const uint32_t v = (uint32_t)std::strtoul(e, nullptr, 10) & ~15u;
-    if (v >= 16u && v <= limit) *chunk = v;
-  }
   *max_tasks = (uint32_t)((tokens + *chunk - 1) / *chunk) + 3u;   // every class may end with a partly filled task
 }
 
