@@ -20,10 +20,13 @@
 //   softmax  one maximum per head over the task's tokens, p = exp2(s - m) back into LDS.
 //   values   the round's packed V rows are regrouped through LDS (still packed) so that a lane
 //            holds 4 consecutive tokens x 8 dimensions, decodes them into 8 MFMA B operands,
-//            and 2 x 8 MFMAs (softmax weights split into a high and a low fp16 part)
-//            accumulate p.V^ for 16 tokens x up to 16 query heads.
-#include <cmath>
-#include <cstdlib>
+//            and 2 x 8 MFMAs (softmax weights as an fp16 high part and the fp16 remainder, into
+//            the same accumulators) add p.V^ for 16 tokens x up to 16 query heads.
+// 2-bit spans, most of a card at low budgets, are not decoded by arithmetic: a group has only
+// four decoded values, which are computed once, and a selector table in LDS indexed by a byte
+// of four codes drives v_perm_b32 to pick them.  Rounds are taken in whole groups of 4 / 3 / 2 /
+// 1 (at 2 / 4 / 8 / 16 bits) without a branch in between; rounds past a task's end see zeros and
+// count as -inf.  114 registers and 10 KiB of LDS per wave: four waves per SIMD.
 
 #include "qkv_common.h"
 #include "qkv_decode.h"
@@ -319,11 +322,12 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
     for (uint32_t t = lane; t < slots; t += kWaveSize) {
       const float p = __builtin_amdgcn_exp2f(row[t] - m);
       l += p;
-      // what the value pass feeds the MFMA: p * 2^14 as an fp16 high part plus an fp16 low part
-      // scaled by 2^11 (both normal numbers for any p that matters), packed into the score's slot
+      // what the value pass feeds the MFMA: p * 2^14 as an fp16 high part plus the fp16 remainder (both go
+      // into the same accumulator; the remainder is a normal number for any p that matters), packed into
+      // the score's slot
       const float ps = p * 16384.0f;
       const _Float16 hi = (_Float16)ps;
-      const _Float16 lo = (_Float16)((ps - (float)hi) * 2048.0f);
+      const _Float16 lo = (_Float16)(ps - (float)hi);
       row[t] = __builtin_bit_cast(float, (uint32_t)__builtin_bit_cast(uint16_t, hi) |
                                              ((uint32_t)__builtin_bit_cast(uint16_t, lo) << 16));
     }
@@ -338,10 +342,11 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   // one token's packed row in the LDS tile; rows of 32 / 64 bytes get a pitch of 40 / 80 so that
   // the four rows a read instruction touches (4 apart) fall on different banks
   constexpr uint32_t kRowBytes = (W == 2) ? 40u : (W == 4) ? 80u : 16u * W;
-  uint32_t* pairs_lds = reinterpret_cast<uint32_t*>(tile + 16u * 256u);
-  f32x4 acc_hi[8], acc_lo[8];
+  // behind the rows: the 16 x 4 pairs (2-bit rows: 16 x 4 four-value tables), and for 2-bit rows the selector table
+  uint32_t* pairs_lds = reinterpret_cast<uint32_t*>(tile + ((W == 16) ? 0u : 16u * kRowBytes));
+  f32x4 acc[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { acc_hi[e] = (f32x4){0.f, 0.f, 0.f, 0.f}; acc_lo[e] = (f32x4){0.f, 0.f, 0.f, 0.f}; }
+  for (int e = 0; e < 8; ++e) acc[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
   {
     SpanData<W, G> buf[kPrefetch];
 #pragma unroll
@@ -443,8 +448,8 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
             const f16x4 be = __builtin_bit_cast(f16x4, b[e]);
-            acc_hi[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(a_hi, be, acc_hi[e], 0, 0, 0);
-            acc_lo[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(a_lo, be, acc_lo[e], 0, 0, 0);
+            acc[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(a_hi, be, acc[e], 0, 0, 0);
+            acc[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(a_lo, be, acc[e], 0, 0, 0);
           }
         }
       }
@@ -457,7 +462,7 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
     if (r < R) {
       float o[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] = (acc_hi[e][i] + acc_lo[e][i] * (1.0f / 2048.0f)) * (1.0f / 16384.0f);
+      for (int e = 0; e < 8; ++e) o[e] = acc[e][i] * (1.0f / 16384.0f);
       f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + r) * 128u + 8u * n);
       dst[0] = (f32x4){o[0], o[1], o[2], o[3]};
       dst[1] = (f32x4){o[4], o[5], o[6], o[7]};
@@ -469,8 +474,9 @@ template <int G>
 __global__ __launch_bounds__(kAttendWaves * kWaveSize) __attribute__((amdgpu_waves_per_eu(2)))
 void attend_kernel(AttendArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[kAttendWaves][kLdsFloatsPerWave];
-  __shared__ __attribute__((aligned(16))) uint8_t tiles[kAttendWaves][16 * 256 + 16 * 32];
-  __shared__ u32x2 select_table[kAttendWaves][256];
+  // the value pass's LDS, 4 KiB: 16 packed rows (640 / 1280 / 2048 / 4096 bytes at 2 / 4 / 8 / 16 bits), then the
+  // rows' pairs (256 bytes; 512 bytes of four-value tables at 2 bits), then at 2 bits the 2 KiB selector table
+  __shared__ __attribute__((aligned(16))) uint8_t tiles[kAttendWaves][16 * 256];
   CardGeom g;
   if (!card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, g))
     return;                                   // uniform over the grid
@@ -508,9 +514,9 @@ void attend_kernel(AttendArgs a) {
   }
   float* my_lds = lds[wave];
   uint8_t* my_tile = tiles[wave];
-  const u32x2* my_table = select_table[wave];
+  u32x2* my_table = reinterpret_cast<u32x2*>(my_tile + 16 * 40 + 512);
   if (cls == 0) {
-    build_select_table(select_table[wave], lane);
+    build_select_table(my_table, lane);
     attend_task<2, G>(a, g, 0, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
   }
   if (cls == 1) attend_task<4, G>(a, g, 1, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
@@ -575,29 +581,21 @@ __global__ void attend_prepare_kernel(AttendArgs a) {
 
 }  // namespace
 
-// Tokens per task and tasks per (layer, kv head) for a given shape.  The scores of one task
-// (chunk tokens x query heads padded to a multiple of 4) must fit 8 KiB of LDS; below that
-// limit the chunk is chosen so that the tasks fill the chip's wave slots a whole number of
-// times: one wave per task, three waves per SIMD (registers and LDS), 256 compute units.  At
-// 8K tokens x 256 (layer, head) pairs, 512-token tasks would fill the slots 1.6 times - the
-// second pass runs 40 % empty - while 384-token tasks fill them 1.9 times (117 -> 107 us).
+// Tokens per task and tasks per (layer, kv head) for a given shape.  The scores of one task (tokens x
+// query heads padded to a multiple of 4) must fit the wave's 6 KiB of LDS.  Tasks are processed in groups
+// of 4, 3, 2 or 1 rounds of 16 tokens, depending on the width, and a task size that all of these divide
+// keeps the padded rounds inside the task's LDS: multiples of 192 tokens, or 64 tokens when fewer than
+// 192 fit (a 64-token task pads to 96 at most).  The larger size means fewer partials and less per-task
+// work (90 us against 96 us at 8K tokens x 256 pairs); the smaller one is taken when the larger would
+// not even fill the chip's wave slots once (one wave per task, four waves per SIMD, 256 compute units).
 void attend_plan(uint64_t tokens, uint32_t rep, uint64_t pairs, uint32_t* chunk, uint32_t* max_tasks) {
   const uint32_t r4 = (rep + 3u) & ~3u;
   const uint32_t room = kLdsFloatsPerWave / r4;                 // tokens whose scores fit, 96 at least
-  // Tasks are processed in groups of 4, 3, 2 or 1 rounds of 16 tokens, depending on the width; a task size
-  // that all of these divide keeps the padded rounds inside the task's LDS: multiples of 192, or 64 tokens
-  // when fewer than 192 fit (a 64-token task pads to 96 at most).
   const uint32_t limit = room >= 192u ? room / 192u * 192u : 64u;
-  const double slots = 256.0 * 4.0 * 3.0;
-  uint32_t best = limit;
-  double best_fill = 0.0;
-  for (uint32_t c = limit; c >= 192u; c -= 192u) {
-    // about two of the four classes end in a partly filled task
-    const double passes = (double)pairs * (double)((tokens + c - 1) / c + 2u) / slots;
-    const double fill = passes / std::ceil(passes);
-    if (fill > best_fill + 0.03) { best_fill = fill; best = c; }   // prefer the larger task unless it clearly loses
-  }
-  *chunk = best;
+  const uint64_t slots = 256u * 4u * 4u;
+  uint32_t c = limit;
+  while (c > 192u && pairs * ((tokens + c - 1) / c + 2u) < slots) c -= 192u;
+  *chunk = c;
   *max_tasks = (uint32_t)((tokens + *chunk - 1) / *chunk) + 3u;   // every class may end with a partly filled task
 }
 
