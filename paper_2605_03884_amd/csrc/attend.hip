@@ -478,8 +478,14 @@ void attend_kernel(AttendArgs a) {
   // rows' pairs (256 bytes; 512 bytes of four-value tables at 2 bits), then at 2 bits the 2 KiB selector table
   __shared__ __attribute__((aligned(16))) uint8_t tiles[kAttendWaves][16 * 256];
   CardGeom g;
-  if (!card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, g))
-    return;                                   // uniform over the grid
+  const bool ok = card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size,
+                                            a.tokens, g);
+  // the header's verdict, for the merging kernel that follows on the stream and for the caller
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    *a.valid = ok ? 1u : 0u;
+    if (a.status) *a.status = ok ? 0u : QKV_STATUS_BAD_HEADER;
+  }
+  if (!ok) return;                            // uniform over the grid
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t wave = threadIdx.x >> 6;
   const uint32_t gw = blockIdx.x * kAttendWaves + wave;
@@ -568,17 +574,6 @@ __global__ __launch_bounds__(128) void attend_merge_kernel(AttendArgs a) {
   if (d == 0 && a.lse) a.lse[lq] = (M + __builtin_log2f(den)) * 0.69314718055994530942f;
 }
 
-// Header verdict for the merge kernel (and the caller's status word); runs first on the stream.
-__global__ void attend_prepare_kernel(AttendArgs a) {
-  CardGeom g;
-  const bool ok = card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size,
-                                            a.tokens, g);
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    *a.valid = ok ? 1u : 0u;
-    if (a.status) *a.status = ok ? 0u : QKV_STATUS_BAD_HEADER;
-  }
-}
-
 }  // namespace
 
 // Tokens per task and tasks per (layer, kv head) for a given shape.  The scores of one task (tokens x
@@ -619,11 +614,6 @@ hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeo
   a.out = out;
   a.lse = lse;
   a.status = status;
-  {
-    hipLaunchKernelGGL(attend_prepare_kernel, dim3(1), dim3(kWaveSize), 0, stream, a);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
   const uint64_t waves = pairs * a.max_tasks;
   const dim3 grid((uint32_t)((waves + kAttendWaves - 1) / kAttendWaves)), block(kAttendWaves * kWaveSize);
   switch (expect.group_size) {
