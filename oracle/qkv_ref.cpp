@@ -549,35 +549,15 @@ int qkv_ref_card_peek(const uint8_t* card, uint64_t card_bytes, RefDesc* desc_ou
   return kOk;
 }
 
-// Receiver-side injection (paper Sec. 4.2.2): dense fp16 K/V from a card.  Token t's row
-// is found through the card's own bits and slot tables.
-int qkv_ref_unpack_dequant(const uint8_t* card, uint64_t card_bytes, const RefDesc* expect,
-                           uint16_t* k_out, uint16_t* v_out) {
-  if (!card || !expect || !k_out || !v_out) return kErrNull;
-  RefDesc d{};
-  int64_t counts[4];
-  Layout lay;
-  int rc = parse_header(card, card_bytes, &d, counts, &lay);
-  if (rc) return rc;
-  if (d.layers != expect->layers || d.kv_heads != expect->kv_heads || d.head_dim != expect->head_dim ||
-      d.group_size != expect->group_size || d.tokens != expect->tokens) return kErrFormat;
+// The planes [p_begin, p_end) of a card with per-token groups, decoded into k_out / v_out.
+static void unpack_per_token(const uint8_t* card, const Layout& lay, const RefDesc& d, const int64_t counts[4],
+                             uint64_t p_begin, uint64_t p_end, uint16_t* k_out, uint16_t* v_out) {
   const int64_t T = d.tokens;
   const int D = d.head_dim, G = d.group_size;
   const uint64_t planes_per_tensor = (uint64_t)d.layers * (uint64_t)d.kv_heads;
   const uint8_t* bits = card + lay.off_bits;
-  // validate the tables before using them as indices
-  {
-    int64_t seen[4] = {0, 0, 0, 0};
-    for (int64_t t = 0; t < T; ++t) {
-      const int c = class_of_width(bits[t]);
-      if (c < 0) return kErrFormat;
-      if ((int64_t)get_u32(card + lay.off_slot + 4 * (uint64_t)t) != seen[c]) return kErrFormat;
-      seen[c] += 1;
-    }
-    for (int c = 0; c < 4; ++c) if (seen[c] != counts[c]) return kErrFormat;
-  }
   std::vector<uint8_t> codes((size_t)D);
-  for (uint64_t p = 0; p < lay.planes; ++p) {
+  for (uint64_t p = p_begin; p < p_end; ++p) {
     uint16_t* dst_plane = (p < planes_per_tensor) ? k_out + p * (uint64_t)T * D
                                                   : v_out + (p - planes_per_tensor) * (uint64_t)T * D;
     for (int64_t t = 0; t < T; ++t) {
@@ -597,6 +577,127 @@ int qkv_ref_unpack_dequant(const uint8_t* card, uint64_t card_bytes, const RefDe
         const uint16_t sh = (uint16_t)(src_meta[4 * g] | (src_meta[4 * g + 1] << 8));
         const uint16_t zh = (uint16_t)(src_meta[4 * g + 2] | (src_meta[4 * g + 3] << 8));
         for (int i = 0; i < G; ++i) row[g * G + i] = dequantize_one(codes[(size_t)(g * G + i)], sh, zh);
+      }
+    }
+  }
+}
+
+// Checks the bits / slot tables of a parsed card before they are used as indices.
+static int validate_tables(const uint8_t* card, const Layout& lay, const RefDesc& d, const int64_t counts[4]) {
+  const uint8_t* bits = card + lay.off_bits;
+  int64_t seen[4] = {0, 0, 0, 0};
+  for (int64_t t = 0; t < d.tokens; ++t) {
+    const int c = class_of_width(bits[t]);
+    if (c < 0) return kErrFormat;
+    if ((int64_t)get_u32(card + lay.off_slot + 4 * (uint64_t)t) != seen[c]) return kErrFormat;
+    seen[c] += 1;
+  }
+  for (int c = 0; c < 4; ++c) if (seen[c] != counts[c]) return kErrFormat;
+  return kOk;
+}
+
+// Receiver-side injection (paper Sec. 4.2.2): dense fp16 K/V from a card.  Token t's row
+// is found through the card's own bits and slot tables.
+int qkv_ref_unpack_dequant(const uint8_t* card, uint64_t card_bytes, const RefDesc* expect,
+                           uint16_t* k_out, uint16_t* v_out) {
+  if (!card || !expect || !k_out || !v_out) return kErrNull;
+  RefDesc d{};
+  int64_t counts[4];
+  Layout lay;
+  int rc = parse_header(card, card_bytes, &d, counts, &lay);
+  if (rc) return rc;
+  if (d.layers != expect->layers || d.kv_heads != expect->kv_heads || d.head_dim != expect->head_dim ||
+      d.group_size != expect->group_size || d.tokens != expect->tokens) return kErrFormat;
+  if (get_u32(card + 188) != 0) return kErrFormat;      // a card with another grouping needs its own call
+  rc = validate_tables(card, lay, d, counts);
+  if (rc) return rc;
+  unpack_per_token(card, lay, d, counts, 0, lay.planes, k_out, v_out);
+  return kOk;
+}
+
+// ---- keys grouped per channel -------------------------------------------------------------------
+//
+// Variant for uniform cards (every token at the same width 2, 4 or 8), after the per-channel key /
+// per-token value scheme the paper cites as related work (Sec. 2, KIVI): key outliers sit in a few
+// channels, so a key group runs along the tokens of one channel instead of along the channels of one
+// token.  Values keep their per-token groups.  Reading taken here: group size 32 both ways, tokens a
+// multiple of 32; key group (plane p, token block tb, channel d) holds tokens 32 tb .. 32 tb + 31 of
+// channel d; the same quantizer as everywhere else.  The card keeps its layout and sizes - a key
+// plane's code section is [token block][channel][32 codes], its pair section [token block][channel] -
+// and says so in bit 0 of the header's flags word.
+
+static int uniform_class(const RefDesc* desc, const int64_t counts[4]) {
+  if (desc->group_size != 32 || desc->tokens % 32 != 0) return -1;
+  for (int c = 0; c < 3; ++c) if (counts[c] == desc->tokens) return c;
+  return -1;
+}
+
+int qkv_ref_quantize_pack_kc(const RefDesc* desc, const uint16_t* k, const uint16_t* v, const uint8_t* bits,
+                             const int64_t counts[4], uint8_t* card, uint64_t capacity) {
+  if (!k || !v || !bits || !card) return kErrNull;
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  rc = check_counts(desc, counts);
+  if (rc) return rc;
+  const int c = uniform_class(desc, counts);
+  if (c < 0) return kErrShape;
+  rc = qkv_ref_quantize_pack(desc, k, v, bits, counts, card, capacity);      // header, tables, value planes
+  if (rc) return rc;
+  put_u32(card + 188, 1);                                                    // flags: keys per channel
+  const Layout lay = make_layout(*desc, counts);
+  const int64_t T = desc->tokens;
+  const int D = desc->head_dim, w = kWidth[c];
+  const uint64_t key_planes = (uint64_t)desc->layers * (uint64_t)desc->kv_heads;
+  const uint64_t group_bytes = 32u * (uint64_t)w / 8u;
+  uint16_t x[32];
+  uint8_t codes[32];
+  for (uint64_t p = 0; p < key_planes; ++p) {
+    const uint16_t* plane = k + p * (uint64_t)T * D;
+    for (int64_t tb = 0; tb < T / 32; ++tb) {
+      for (int d = 0; d < D; ++d) {
+        for (int i = 0; i < 32; ++i) x[i] = plane[(uint64_t)(32 * tb + i) * D + d];
+        uint16_t sh, zh;
+        quantize_group(x, 32, w, &sh, &zh, codes);
+        const uint64_t g = (p * (uint64_t)(T / 32) + (uint64_t)tb) * (uint64_t)D + (uint64_t)d;
+        pack_codes(codes, 32, w, card + lay.off_codes[c] + g * group_bytes);
+        uint8_t* m = card + lay.off_meta[c] + g * 4;
+        m[0] = (uint8_t)(sh & 0xff); m[1] = (uint8_t)(sh >> 8); m[2] = (uint8_t)(zh & 0xff); m[3] = (uint8_t)(zh >> 8);
+      }
+    }
+  }
+  return kOk;
+}
+
+int qkv_ref_unpack_dequant_kc(const uint8_t* card, uint64_t card_bytes, const RefDesc* expect,
+                              uint16_t* k_out, uint16_t* v_out) {
+  if (!card || !expect || !k_out || !v_out) return kErrNull;
+  RefDesc d{};
+  int64_t counts[4];
+  Layout lay;
+  int rc = parse_header(card, card_bytes, &d, counts, &lay);
+  if (rc) return rc;
+  if (d.layers != expect->layers || d.kv_heads != expect->kv_heads || d.head_dim != expect->head_dim ||
+      d.group_size != expect->group_size || d.tokens != expect->tokens) return kErrFormat;
+  if (get_u32(card + 188) != 1) return kErrFormat;
+  const int c = uniform_class(&d, counts);
+  if (c < 0) return kErrFormat;
+  rc = validate_tables(card, lay, d, counts);
+  if (rc) return rc;
+  const int64_t T = d.tokens;
+  const int D = d.head_dim, w = kWidth[c];
+  const uint64_t key_planes = (uint64_t)d.layers * (uint64_t)d.kv_heads;
+  unpack_per_token(card, lay, d, counts, key_planes, lay.planes, k_out, v_out);       // values
+  const uint64_t group_bytes = 32u * (uint64_t)w / 8u;
+  uint8_t codes[32];
+  for (uint64_t p = 0; p < key_planes; ++p) {
+    uint16_t* plane = k_out + p * (uint64_t)T * D;
+    for (int64_t tb = 0; tb < T / 32; ++tb) {
+      for (int dd = 0; dd < D; ++dd) {
+        const uint64_t g = (p * (uint64_t)(T / 32) + (uint64_t)tb) * (uint64_t)D + (uint64_t)dd;
+        unpack_codes(card + lay.off_codes[c] + g * group_bytes, 32, w, codes);
+        const uint8_t* m = card + lay.off_meta[c] + g * 4;
+        const uint16_t sh = (uint16_t)(m[0] | (m[1] << 8)), zh = (uint16_t)(m[2] | (m[3] << 8));
+        for (int i = 0; i < 32; ++i) plane[(uint64_t)(32 * tb + i) * D + dd] = dequantize_one(codes[i], sh, zh);
       }
     }
   }

@@ -208,6 +208,31 @@ def quantize_pack(desc, k, v, bits, counts, capacity=None):
     return card
 
 
+def quantize_pack_kc(desc, k, v, bits, counts, capacity=None):
+    """Uniform card with keys grouped per channel (values per token); same arguments as quantize_pack."""
+    k = _as_u16(k)
+    v = _as_u16(v)
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    c = _counts_arr(counts)
+    if capacity is None:
+        capacity = card_bytes(desc, counts)
+    card = np.zeros(capacity, dtype=np.uint8)
+    _check(lib().qkv_ref_quantize_pack_kc(ctypes.byref(desc), _ptr(k), _ptr(v), _ptr(bits), _ptr(c), _ptr(card),
+                                          ctypes.c_uint64(capacity)), "quantize_pack_kc")
+    return card
+
+
+def unpack_dequant_kc(card, expect):
+    """Returns (k, v) as uint16 arrays shaped [L, H, T, D] from a card with keys grouped per channel."""
+    card = np.ascontiguousarray(card, dtype=np.uint8)
+    shape = (expect.layers, expect.kv_heads, expect.tokens, expect.head_dim)
+    k = np.zeros(shape, dtype=np.uint16)
+    v = np.zeros(shape, dtype=np.uint16)
+    _check(lib().qkv_ref_unpack_dequant_kc(_ptr(card), ctypes.c_uint64(card.size), ctypes.byref(expect), _ptr(k), _ptr(v)),
+           "unpack_dequant_kc")
+    return k, v
+
+
 def card_peek(card):
     card = np.ascontiguousarray(card, dtype=np.uint8)
     d = RefDesc()
