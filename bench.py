@@ -189,6 +189,10 @@ def main():
     kv_bytes = K.numel() * 2 + V.numel() * 2
     moved = kv_bytes + card_bytes          # algorithmic bytes of either direction
 
+    kc = bool(cfg.get("keys_per_channel"))            # uniform card with the keys grouped per channel
+    do_pack = qkv.quantize_pack_kc if kc else qkv.quantize_pack
+    do_unpack = qkv.unpack_dequant_kc if kc else qkv.unpack_dequant
+
     def step(events=None):
         i = turn[0] % nsets
         turn[0] += 1
@@ -199,14 +203,18 @@ def main():
             qkv.assign_bits(scores, budget, bits=bits)
         if events is not None:
             events[1].record()
-        if events is None:
-            qkv.quantize_pack(desc, K, V, bits, counts, card)
+        if events is None or kc:
+            if events is not None:
+                events[4].record()
+            do_pack(desc, K, V, bits, counts, card)
+            if events is not None:
+                events[2].record()
         else:                                       # the same two launches, with an event between them
             qkv.card_plan(desc, bits, counts, card)
             events[4].record()
             qkv.card_fill(desc, K, V, counts, card)
             events[2].record()
-        qkv.unpack_dequant(card, desc, K_out, V_out)
+        do_unpack(card, desc, K_out, V_out)
         if events is not None:
             events[3].record()
 
@@ -271,7 +279,7 @@ def main():
     # beyond the handoff itself: one decode step's attention taken directly over the card
     # (32 query heads on 8 kv heads as in Llama-3.1-8B), timed on its own
     attend = None
-    if D == 128:
+    if D == 128 and not kc:
         rep = 4
         qv = qkv_synth.normal(cfg["data_seed"] + 17, 9, 0, L * H * rep * D, dev).view(L, H * rep, D).to(torch.float16)
         a_out = torch.empty((L, H * rep, D), dtype=torch.float32, device=dev)
@@ -297,7 +305,7 @@ def main():
     # injection into per-layer caches (one key and one value tensor per layer, room for a prefix), with and
     # without realigning the keys, in one call and layer by layer
     inject = None
-    if L <= 64:
+    if L <= 64 and not kc:
         prefix, cap = 64, T + 64
         if args.inject_layout == "dense":
             prefix, cap = 0, T

@@ -82,6 +82,9 @@ extern "C" {
 #define QKV_CARD_ALIGN          256u
 
 /* bits in the status words written by the kernels */
+/* Header flags. */
+#define QKV_FLAG_KEYS_PER_CHANNEL 1u   /* uniform card whose key groups run along the tokens of a channel */
+
 #define QKV_STATUS_BAD_BITS     0x1u  /* a bits[] value was not 2, 4, 8 or 16 (treated as 2)   */
 #define QKV_STATUS_BAD_COUNTS   0x2u  /* counts[] passed by the host differ from the histogram */
 #define QKV_STATUS_BAD_HEADER   0x4u  /* unpack: magic / version / shape / sizes do not match  */
@@ -121,7 +124,7 @@ typedef struct qkv_card_header {
   uint64_t sender_id;       /* 168                                              */
   int64_t  position_offset; /* 176                                              */
   float    avg_bits;        /* 184  (float)((double)sum of b(t) / (double)T)    */
-  uint32_t flags;           /* 188  0 in layout v1                              */
+  uint32_t flags;           /* 188  0, or QKV_FLAG_KEYS_PER_CHANNEL             */
   uint32_t status;          /* 192  QKV_STATUS_* bits set by the packing kernels */
   uint8_t  reserved[60];    /* 196  zero                                        */
 } qkv_card_header_t;
@@ -265,6 +268,28 @@ int qkv_card_fill(const qkv_desc_t* desc, const void* k_dev, const void* v_dev, 
  */
 int qkv_unpack_dequant(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect,
                        void* k_out_dev, void* v_out_dev, uint32_t* status_dev, void* stream);
+
+/*
+ * Variant for uniform cards (every token at the same width 2, 4 or 8) with the keys grouped per
+ * channel, after the per-channel key / per-token value scheme the paper cites as related work
+ * (Sec. 2): key outliers live in a few channels, so a key group holds the 32 tokens
+ * 32 tb .. 32 tb + 31 of ONE channel instead of 32 channels of one token; values keep per-token
+ * groups.  Same quantizer, same card layout and sizes; in the key planes a code section reads
+ * [plane][token block][channel][32 codes] and a pair section [plane][token block][channel]; the
+ * header's flags word holds QKV_FLAG_KEYS_PER_CHANNEL.
+ *
+ * qkv_quantize_pack_kc / qkv_unpack_dequant_kc take the arguments of qkv_quantize_pack /
+ * qkv_unpack_dequant and behave like them, with these extra conditions (QKV_ERR_SHAPE otherwise):
+ * group_size 32, head_dim 64 or 128, tokens a multiple of 32 (of 64 at head_dim 64); and
+ * (QKV_ERR_COUNTS) counts naming exactly one of the widths 2, 4, 8 for all tokens.  A card of
+ * one grouping handed to the other grouping's calls (qkv_unpack_dequant, qkv_inject_layers and
+ * qkv_card_attend read per-token groups only) is refused on the device: QKV_STATUS_BAD_HEADER,
+ * nothing written.
+ */
+int qkv_quantize_pack_kc(const qkv_desc_t* desc, const void* k_dev, const void* v_dev, const uint8_t* bits_dev,
+                         const int64_t counts[4], void* card_dev, uint64_t card_capacity, void* stream);
+int qkv_unpack_dequant_kc(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect,
+                          void* k_out_dev, void* v_out_dev, uint32_t* status_dev, void* stream);
 
 /*
  * Receiver-side injection into per-layer caches (paper Sec. 4.2.2: the receiver rebuilds fp16

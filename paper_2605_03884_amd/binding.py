@@ -111,6 +111,10 @@ def lib():
     L.qkv_card_fill.argtypes = [ctypes.POINTER(Desc), vp, vp, i64p, vp, ctypes.c_uint64, vp]
     L.qkv_inject_layers.restype = ctypes.c_int
     L.qkv_inject_layers.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), ctypes.POINTER(Inject), vp, vp]
+    L.qkv_quantize_pack_kc.restype = ctypes.c_int
+    L.qkv_quantize_pack_kc.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, i64p, vp, ctypes.c_uint64, vp]
+    L.qkv_unpack_dequant_kc.restype = ctypes.c_int
+    L.qkv_unpack_dequant_kc.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, vp, vp, vp]
     L.qkv_unpack_dequant.restype = ctypes.c_int
     L.qkv_unpack_dequant.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, vp, vp, vp]
     L.qkv_card_attend_workspace.restype = ctypes.c_int
@@ -224,6 +228,15 @@ def quantize_pack(desc, k, v, bits, counts, card, stream=None):
     return card
 
 
+def quantize_pack_kc(desc, k, v, bits, counts, card, stream=None):
+    """quantize_pack for a uniform card with the keys grouped per channel."""
+    _check(lib().qkv_quantize_pack_kc(ctypes.byref(desc), _dev_ptr(k, torch.float16, "k"), _dev_ptr(v, torch.float16, "v"),
+                                      _dev_ptr(bits, torch.uint8, "bits"), _counts(counts),
+                                      _dev_ptr(card, torch.uint8, "card"), card.numel(), _stream(stream)),
+           "qkv_quantize_pack_kc")
+    return card
+
+
 def card_plan(desc, bits, counts, card, stream=None):
     """First half of quantize_pack: header, tables and pads."""
     _check(lib().qkv_card_plan(ctypes.byref(desc), _dev_ptr(bits, torch.uint8, "bits"), _counts(counts),
@@ -246,6 +259,16 @@ def unpack_dequant(card, expect, k_out, v_out, status=None, card_nbytes=None, st
     _check(lib().qkv_unpack_dequant(_dev_ptr(card, torch.uint8, "card"), n, ctypes.byref(expect),
                                     _dev_ptr(k_out, torch.float16, "k_out"), _dev_ptr(v_out, torch.float16, "v_out"),
                                     sp, _stream(stream)), "qkv_unpack_dequant")
+    return k_out, v_out
+
+
+def unpack_dequant_kc(card, expect, k_out, v_out, status=None, card_nbytes=None, stream=None):
+    """unpack_dequant for a uniform card with the keys grouped per channel."""
+    n = card.numel() if card_nbytes is None else int(card_nbytes)
+    sp = ctypes.c_void_p(0) if status is None else _dev_ptr(status, None, "status")
+    _check(lib().qkv_unpack_dequant_kc(_dev_ptr(card, torch.uint8, "card"), n, ctypes.byref(expect),
+                                       _dev_ptr(k_out, torch.float16, "k_out"), _dev_ptr(v_out, torch.float16, "v_out"),
+                                       sp, _stream(stream)), "qkv_unpack_dequant_kc")
     return k_out, v_out
 
 

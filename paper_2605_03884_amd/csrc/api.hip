@@ -231,7 +231,7 @@ int prepare_card(const qkv_desc_t* desc, const int64_t counts[4], const void* ca
 }
 
 int plan_card(const qkv_desc_t* desc, const uint8_t* bits_dev, const CardGeom& g, const uint64_t n[4], uint8_t* card,
-              hipStream_t s) {
+              hipStream_t s, uint32_t flags = 0) {
   qkv_card_header_t h;
   std::memset(&h, 0, sizeof(h));
   static const uint8_t magic[8] = {'Q', 'K', 'V', 'C', 'A', 'R', 'D', 0};
@@ -253,7 +253,7 @@ int plan_card(const qkv_desc_t* desc, const uint8_t* bits_dev, const CardGeom& g
   h.sender_id = desc->sender_id;
   h.position_offset = desc->position_offset;
   h.avg_bits = (float)((double)code_bits / (double)h.tokens);   // achieved average bit width (Sec. 4.2.1)
-  h.flags = 0;
+  h.flags = flags;
   h.status = 0;
   return launch_classify(bits_dev, g, h, card, s) == hipSuccess ? QKV_OK : QKV_ERR_HIP;
 }
@@ -278,7 +278,7 @@ int qkv_card_fill(const qkv_desc_t* desc, const void* k_dev, const void* v_dev, 
   const int rc = prepare_card(desc, counts, card_dev, card_capacity, g, n);
   if (rc) return rc;
   if (reinterpret_cast<uintptr_t>(k_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(v_dev) % 16 != 0) return QKV_ERR_ALIGN;
-  return launch_pack(g, k_dev, v_dev, static_cast<uint8_t*>(card_dev), static_cast<hipStream_t>(stream)) == hipSuccess
+  return launch_pack(g, k_dev, v_dev, static_cast<uint8_t*>(card_dev), false, static_cast<hipStream_t>(stream)) == hipSuccess
              ? QKV_OK : QKV_ERR_HIP;
 }
 
@@ -294,15 +294,48 @@ int qkv_quantize_pack(const qkv_desc_t* desc, const void* k_dev, const void* v_d
   uint8_t* card = static_cast<uint8_t*>(card_dev);
   rc = plan_card(desc, bits_dev, g, n, card, s);
   if (rc) return rc;
-  if (launch_pack(g, k_dev, v_dev, card, s) != hipSuccess) return QKV_ERR_HIP;
+  if (launch_pack(g, k_dev, v_dev, card, false, s) != hipSuccess) return QKV_ERR_HIP;
   return QKV_OK;
 }
 
-int qkv_unpack_dequant(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, void* k_out_dev,
-                       void* v_out_dev, uint32_t* status_dev, void* stream) {
-  if (!card_dev || !expect || !k_out_dev || !v_out_dev) return QKV_ERR_NULL;
-  const int rc = check_desc(expect);
+namespace {
+// Shapes the per-channel key tiles are written for.
+int check_keys_per_channel(const qkv_desc_t* d) {
+  if (d->group_size != 32 || (d->head_dim != 64 && d->head_dim != 128)) return QKV_ERR_SHAPE;
+  if (d->tokens % (d->head_dim == 64 ? 64 : 32) != 0) return QKV_ERR_SHAPE;
+  return QKV_OK;
+}
+}  // namespace
+
+int qkv_quantize_pack_kc(const qkv_desc_t* desc, const void* k_dev, const void* v_dev, const uint8_t* bits_dev,
+                         const int64_t counts[4], void* card_dev, uint64_t card_capacity, void* stream) {
+  if (!desc || !k_dev || !v_dev || !bits_dev || !counts || !card_dev) return QKV_ERR_NULL;
+  CardGeom g;
+  uint64_t n[4];
+  int rc = prepare_card(desc, counts, card_dev, card_capacity, g, n);
   if (rc) return rc;
+  rc = check_keys_per_channel(desc);
+  if (rc) return rc;
+  if (counts[0] != desc->tokens && counts[1] != desc->tokens && counts[2] != desc->tokens) return QKV_ERR_COUNTS;
+  if (reinterpret_cast<uintptr_t>(k_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(v_dev) % 16 != 0) return QKV_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint8_t* card = static_cast<uint8_t*>(card_dev);
+  rc = plan_card(desc, bits_dev, g, n, card, s, QKV_FLAG_KEYS_PER_CHANNEL);
+  if (rc) return rc;
+  if (launch_pack(g, k_dev, v_dev, card, true, s) != hipSuccess) return QKV_ERR_HIP;
+  return QKV_OK;
+}
+
+namespace {
+int unpack_any(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, void* k_out_dev, void* v_out_dev,
+               uint32_t* status_dev, bool keys_per_channel, void* stream) {
+  if (!card_dev || !expect || !k_out_dev || !v_out_dev) return QKV_ERR_NULL;
+  int rc = check_desc(expect);
+  if (rc) return rc;
+  if (keys_per_channel) {
+    rc = check_keys_per_channel(expect);
+    if (rc) return rc;
+  }
   if (card_bytes < QKV_CARD_HEADER_BYTES) return QKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(k_out_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(v_out_dev) % 16 != 0 ||
       reinterpret_cast<uintptr_t>(card_dev) % QKV_CARD_ALIGN != 0 || reinterpret_cast<uintptr_t>(status_dev) % 4 != 0)
@@ -311,9 +344,20 @@ int qkv_unpack_dequant(const void* card_dev, uint64_t card_bytes, const qkv_desc
   CardGeom g;
   build_geom(g, expect->layers, expect->kv_heads, expect->head_dim, expect->group_size, expect->tokens, zero);
   if (launch_unpack(static_cast<const uint8_t*>(card_dev), card_bytes, g, k_out_dev, v_out_dev, status_dev,
-                    static_cast<hipStream_t>(stream)) != hipSuccess)
+                    keys_per_channel, static_cast<hipStream_t>(stream)) != hipSuccess)
     return QKV_ERR_HIP;
   return QKV_OK;
+}
+}  // namespace
+
+int qkv_unpack_dequant(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, void* k_out_dev,
+                       void* v_out_dev, uint32_t* status_dev, void* stream) {
+  return unpack_any(card_dev, card_bytes, expect, k_out_dev, v_out_dev, status_dev, false, stream);
+}
+
+int qkv_unpack_dequant_kc(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, void* k_out_dev,
+                          void* v_out_dev, uint32_t* status_dev, void* stream) {
+  return unpack_any(card_dev, card_bytes, expect, k_out_dev, v_out_dev, status_dev, true, stream);
 }
 
 int qkv_inject_layers(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, const qkv_inject_t* where,

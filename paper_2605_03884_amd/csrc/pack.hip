@@ -181,11 +181,55 @@ __device__ inline void encode_span(const uint32_t (&w)[16], float neg_mn, float 
   for (int o = 0; o < W; ++o) out[o] -= magic_carry<W>();
 }
 
+// One span of 32 values (16 packed pairs): the extrema of its group (reduced over the GS lanes that share
+// it), scale and reciprocal as the quantizer defines them, and the span's codes.  Returns the pair as it
+// is stored: fp16 scale, then fp16 zero.
+template <int W, int GS>
+__device__ inline uint32_t quantize_span(const uint32_t (&w)[16], uint32_t (&out)[W]) {
+  constexpr float QMAXF = (float)((1 << W) - 1);
+  constexpr float RCPQ = 1.0f / QMAXF;           // correctly rounded at compile time
+  // extrema of the span, then of the group
+  uint32_t m = pk_min(pk_min3(pk_min3(w[0], w[1], w[2]), pk_min3(w[3], w[4], w[5]), pk_min3(w[6], w[7], w[8])),
+                      pk_min3(pk_min3(w[9], w[10], w[11]), pk_min3(w[12], w[13], w[14]), w[15]));
+  uint32_t M = pk_max(pk_max3(pk_max3(w[0], w[1], w[2]), pk_max3(w[3], w[4], w[5]), pk_max3(w[6], w[7], w[8])),
+                      pk_max3(pk_max3(w[9], w[10], w[11]), pk_max3(w[12], w[13], w[14]), w[15]));
+  m = pk_min_halves(m);
+  M = pk_max_halves(M);
+  if (GS >= 2) { m = pk_min(m, dpp<kQuadXor1>(m)); M = pk_max(M, dpp<kQuadXor1>(M)); }
+  if (GS >= 4) { m = pk_min(m, dpp<kQuadXor2>(m)); M = pk_max(M, dpp<kQuadXor2>(M)); }
+  const uint32_t mn_h = m & 0xFFFFu;
+
+  // scale = fp16(range / qmax), inv = 1 / scale: fp32, correctly rounded.
+  // Quotient: q0 = range * (1/qmax) is within one ulp, its exact residual corrects it.
+  const float fmn = half_bits_to_float(mn_h);
+  const float fmx = half_bits_to_float(M & 0xFFFFu);
+  const float range = fmx - fmn;
+  const float q0 = range * RCPQ;
+  float s32 = __builtin_fmaf(__builtin_fmaf(-q0, QMAXF, range), RCPQ, q0);
+  // Keep the fp32 quotient and its conversion apart: fused into one fma-and-convert
+  // instruction the value would be rounded once, straight to fp16, which differs from
+  // rounding to fp32 first whenever the fp32 result lands on an fp16 midpoint.
+  asm("" : "+v"(s32));
+  const uint32_t s_h = float_to_half_bits(s32);
+  const float s = half_bits_to_float(s_h);
+  // Reciprocal: the hardware estimate is within one ulp; s has 11 significant bits, so 1/s
+  // is never closer than 2^-12 ulp to a rounding boundary and one residual step lands on
+  // the correctly rounded value.
+  const float y0 = __builtin_amdgcn_rcpf(s);
+  const float y1 = __builtin_fmaf(__builtin_fmaf(-s, y0, 1.0f), y0, y0);
+  const float inv = (s > 0.0f) ? y1 : 0.0f;
+
+  // The clamp to qmax can only act when the stored scale is an fp16 subnormal; otherwise
+  // d * inv <= qmax * (1 + 2^-11 + ...) already rounds to at most qmax.
+  const bool needs_clamp = (s_h - 1u) < 0x3FFu;
+  if (__builtin_amdgcn_ballot_w64(needs_clamp) != 0) encode_span<W, true>(w, -fmn, inv, out);
+  else encode_span<W, false>(w, -fmn, inv, out);
+  return s_h | (mn_h << 16);
+}
+
 template <int W, int G, bool KEEP>
 __device__ inline void pack_tile(const PackArgs& a, int c, uint32_t r0, uint32_t n_rows, uint32_t lane, u32x4* lds) {
   constexpr int GS = G / 32;                     // spans (lanes) per group
-  constexpr float QMAXF = (float)((1 << W) - 1);
-  constexpr float RCPQ = 1.0f / QMAXF;           // correctly rounded at compile time
   const CardGeom& g = a.g;
   const uint32_t lpr_shift = g.lpr_shift;
   const uint32_t tile_rows = kTileChunks >> lpr_shift;
@@ -213,43 +257,8 @@ __device__ inline void pack_tile(const PackArgs& a, int c, uint32_t r0, uint32_t
       const u32x4 t = lds[4 * sp + (j ^ x)];
       w[4 * j + 0] = t.x; w[4 * j + 1] = t.y; w[4 * j + 2] = t.z; w[4 * j + 3] = t.w;
     }
-    // extrema of the span, then of the group
-    uint32_t m = pk_min(pk_min3(pk_min3(w[0], w[1], w[2]), pk_min3(w[3], w[4], w[5]), pk_min3(w[6], w[7], w[8])),
-                        pk_min3(pk_min3(w[9], w[10], w[11]), pk_min3(w[12], w[13], w[14]), w[15]));
-    uint32_t M = pk_max(pk_max3(pk_max3(w[0], w[1], w[2]), pk_max3(w[3], w[4], w[5]), pk_max3(w[6], w[7], w[8])),
-                        pk_max3(pk_max3(w[9], w[10], w[11]), pk_max3(w[12], w[13], w[14]), w[15]));
-    m = pk_min_halves(m);
-    M = pk_max_halves(M);
-    if (GS >= 2) { m = pk_min(m, dpp<kQuadXor1>(m)); M = pk_max(M, dpp<kQuadXor1>(M)); }
-    if (GS >= 4) { m = pk_min(m, dpp<kQuadXor2>(m)); M = pk_max(M, dpp<kQuadXor2>(M)); }
-    const uint32_t mn_h = m & 0xFFFFu;
-
-    // scale = fp16(range / qmax), inv = 1 / scale: fp32, correctly rounded.
-    // Quotient: q0 = range * (1/qmax) is within one ulp, its exact residual corrects it.
-    const float fmn = half_bits_to_float(mn_h);
-    const float fmx = half_bits_to_float(M & 0xFFFFu);
-    const float range = fmx - fmn;
-    const float q0 = range * RCPQ;
-    float s32 = __builtin_fmaf(__builtin_fmaf(-q0, QMAXF, range), RCPQ, q0);
-    // Keep the fp32 quotient and its conversion apart: fused into one fma-and-convert
-    // instruction the value would be rounded once, straight to fp16, which differs from
-    // rounding to fp32 first whenever the fp32 result lands on an fp16 midpoint.
-    asm("" : "+v"(s32));
-    const uint32_t s_h = float_to_half_bits(s32);
-    const float s = half_bits_to_float(s_h);
-    // Reciprocal: the hardware estimate is within one ulp; s has 11 significant bits, so 1/s
-    // is never closer than 2^-12 ulp to a rounding boundary and one residual step lands on
-    // the correctly rounded value.
-    const float y0 = __builtin_amdgcn_rcpf(s);
-    const float y1 = __builtin_fmaf(__builtin_fmaf(-s, y0, 1.0f), y0, y0);
-    const float inv = (s > 0.0f) ? y1 : 0.0f;
-
-    // The clamp to qmax can only act when the stored scale is an fp16 subnormal; otherwise
-    // d * inv <= qmax * (1 + 2^-11 + ...) already rounds to at most qmax.
     uint32_t out[W];
-    const bool needs_clamp = (s_h - 1u) < 0x3FFu;
-    if (__builtin_amdgcn_ballot_w64(needs_clamp) != 0) encode_span<W, true>(w, -fmn, inv, out);
-    else encode_span<W, false>(w, -fmn, inv, out);
+    const uint32_t pair = quantize_span<W, GS>(w, out);
 
     const uint64_t gsp = span0 + sp;
     if (gsp < seg_spans) {
@@ -257,12 +266,62 @@ __device__ inline void pack_tile(const PackArgs& a, int c, uint32_t r0, uint32_t
       if (W == 2) card_store<KEEP>(reinterpret_cast<u32x2*>(dst), (u32x2){out[0], out[1]});
       if (W >= 4) card_store<KEEP>(reinterpret_cast<u32x4*>(dst), (u32x4){out[0], out[1], out[2], out[3]});
       if (W == 8) card_store<KEEP>(reinterpret_cast<u32x4*>(dst + 16), (u32x4){out[4], out[5], out[6], out[7]});
-      if ((sp & (GS - 1)) == 0) card_store<KEEP>(&meta_seg[gsp / GS], s_h | (mn_h << 16));   // fp16 scale first, then fp16 zero
+      if ((sp & (GS - 1)) == 0) card_store<KEEP>(&meta_seg[gsp / GS], pair);
     }
   }
 }
 
 // ---- one tile of the fp16 segment: rows copied bit for bit ---------------------------------
+
+// A tile of key rows of a uniform card with groups per channel: the tile is gathered into LDS as usual,
+// but a lane then takes, per round, the 32 tokens of one token block for one channel (a column of the
+// tile; 64 lanes read 64 neighbouring channels of a row at a time), quantizes them as one group, and
+// stores codes and pair at [token block][channel].  Head dimensions 64 and 128 only: a tile must hold
+// whole blocks of 32 tokens.
+template <int W, bool KEEP>
+__device__ inline void pack_tile_kc(const PackArgs& a, int c, uint32_t r0, uint32_t n_rows, uint32_t key_rows,
+                                    uint32_t lane, u32x4* lds) {
+  const CardGeom& g = a.g;
+  const uint32_t lpr_shift = g.lpr_shift;
+  const uint32_t tile_rows = kTileChunks >> lpr_shift;
+  const uint64_t my_row = tile_row_address(a, c, r0, n_rows, lane, tile_rows);
+  u32x4 data[kTileIters];
+  load_tile(my_row, lane, lpr_shift, data);
+  const uint32_t wslot = swizzle(lane);
+#pragma unroll
+  for (int k = 0; k < kTileIters; ++k) lds[k * kWaveSize + wslot] = data[k];
+
+  const uint16_t* lds16 = reinterpret_cast<const uint16_t*>(lds);
+  uint8_t* codes_seg = a.card + g.off_codes[c];
+  uint32_t* meta_seg = reinterpret_cast<uint32_t*>(a.card + g.off_meta[c]);
+  const uint32_t D = g.head_dim;
+#pragma unroll 1
+  for (int round = 0; round < kTileRounds; ++round) {
+    const uint32_t sp = round * kWaveSize + lane;
+    const uint32_t d = sp & (D - 1u);                       // channel
+    const uint32_t tbl = sp >> (lpr_shift + 3u);            // token block inside the tile (head_dim 64: two)
+    uint32_t w[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const uint32_t qa = ((32u * tbl + 2u * j) << lpr_shift) + (d >> 3);      // chunk of (token 2j, channel d)
+      const uint32_t qb = qa + (1u << lpr_shift);
+      const uint32_t xa = lds16[swizzle(qa) * 8u + (d & 7u)];
+      const uint32_t xb = lds16[swizzle(qb) * 8u + (d & 7u)];
+      w[j] = xa | (xb << 16);
+    }
+    uint32_t out[W];
+    const uint32_t pair = quantize_span<W, 1>(w, out);
+    const uint32_t blk = r0 / 32u + tbl;                    // token block inside the segment: planes follow each other
+    if (32u * blk < key_rows) {
+      const uint64_t grp = (uint64_t)blk * D + d;
+      uint8_t* dst = codes_seg + grp * (4u * W);
+      if (W == 2) card_store<KEEP>(reinterpret_cast<u32x2*>(dst), (u32x2){out[0], out[1]});
+      if (W >= 4) card_store<KEEP>(reinterpret_cast<u32x4*>(dst), (u32x4){out[0], out[1], out[2], out[3]});
+      if (W == 8) card_store<KEEP>(reinterpret_cast<u32x4*>(dst + 16), (u32x4){out[4], out[5], out[6], out[7]});
+      card_store<KEEP>(&meta_seg[grp], pair);
+    }
+  }
+}
 
 template <bool KEEP>
 __device__ inline void copy_tile(const PackArgs& a, uint32_t r0, uint32_t n_rows, uint32_t lane) {
@@ -284,7 +343,8 @@ __device__ inline void copy_tile(const PackArgs& a, uint32_t r0, uint32_t n_rows
 
 // ---- grid ----------------------------------------------------------------------------------------
 
-template <int G, bool KEEP>
+// KC: the card is uniform and its key planes (the first half of every segment) are grouped per channel.
+template <int G, bool KEEP, bool KC>
 __global__ __launch_bounds__(kBlockThreads) void pack_kernel(PackArgs a) {
   __shared__ u32x4 lds[kWavesPerBlock][kTileChunks];
   const uint32_t lane = threadIdx.x & 63u;
@@ -303,6 +363,12 @@ __global__ __launch_bounds__(kBlockThreads) void pack_kernel(PackArgs a) {
     const uint32_t first = (gw + n_waves - cum) % n_waves;
     for (uint32_t i = first; i < tiles; i += n_waves) {
       const uint32_t r0 = i * tile_rows;
+      if (KC && c < 3 && r0 < (n_rows >> 1)) {                 // key rows: the host made sure no tile straddles the halves
+        if (c == 0) pack_tile_kc<2, KEEP>(a, 0, r0, n_rows, n_rows >> 1, lane, my_lds);
+        if (c == 1) pack_tile_kc<4, KEEP>(a, 1, r0, n_rows, n_rows >> 1, lane, my_lds);
+        if (c == 2) pack_tile_kc<8, KEEP>(a, 2, r0, n_rows, n_rows >> 1, lane, my_lds);
+        continue;
+      }
       if (c == 0) pack_tile<2, G, KEEP>(a, 0, r0, n_rows, lane, my_lds);
       if (c == 1) pack_tile<4, G, KEEP>(a, 1, r0, n_rows, lane, my_lds);
       if (c == 2) pack_tile<8, G, KEEP>(a, 2, r0, n_rows, lane, my_lds);
@@ -314,7 +380,8 @@ __global__ __launch_bounds__(kBlockThreads) void pack_kernel(PackArgs a) {
 
 }  // namespace
 
-hipError_t launch_pack(const CardGeom& geom, const void* k, const void* v, uint8_t* card, hipStream_t stream) {
+hipError_t launch_pack(const CardGeom& geom, const void* k, const void* v, uint8_t* card, bool keys_per_channel,
+                       hipStream_t stream) {
   PackArgs a;
   a.g = geom;
   a.k = static_cast<const uint8_t*>(k);
@@ -329,13 +396,18 @@ hipError_t launch_pack(const CardGeom& geom, const void* k, const void* v, uint8
   if (tiles == 0) return hipSuccess;
   const dim3 grid(grid_blocks(tiles)), block(kBlockThreads);
   const bool keep = geom.total <= kCacheResidentCardBytes;
+  if (keys_per_channel) {                        // group size 32 only (checked by the caller)
+    if (keep) hipLaunchKernelGGL((pack_kernel<32, true, true>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((pack_kernel<32, false, true>), grid, block, 0, stream, a);
+    return hipGetLastError();
+  }
   switch (geom.group_size * 2 + (keep ? 1 : 0)) {
-    case 65: hipLaunchKernelGGL((pack_kernel<32, true>), grid, block, 0, stream, a); break;
-    case 64: hipLaunchKernelGGL((pack_kernel<32, false>), grid, block, 0, stream, a); break;
-    case 129: hipLaunchKernelGGL((pack_kernel<64, true>), grid, block, 0, stream, a); break;
-    case 128: hipLaunchKernelGGL((pack_kernel<64, false>), grid, block, 0, stream, a); break;
-    case 257: hipLaunchKernelGGL((pack_kernel<128, true>), grid, block, 0, stream, a); break;
-    default: hipLaunchKernelGGL((pack_kernel<128, false>), grid, block, 0, stream, a); break;
+    case 65: hipLaunchKernelGGL((pack_kernel<32, true, false>), grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((pack_kernel<32, false, false>), grid, block, 0, stream, a); break;
+    case 129: hipLaunchKernelGGL((pack_kernel<64, true, false>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((pack_kernel<64, false, false>), grid, block, 0, stream, a); break;
+    case 257: hipLaunchKernelGGL((pack_kernel<128, true, false>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((pack_kernel<128, false, false>), grid, block, 0, stream, a); break;
   }
   return hipGetLastError();
 }

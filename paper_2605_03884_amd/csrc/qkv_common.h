@@ -132,9 +132,10 @@ int grid_blocks(uint64_t tiles);
 // Kernel launchers (one per source file).  All enqueue on `stream` and return a hipError_t.
 hipError_t launch_classify(const uint8_t* bits, const CardGeom& geom, const qkv_card_header_t& header,
                            uint8_t* card, hipStream_t stream);
-hipError_t launch_pack(const CardGeom& geom, const void* k, const void* v, uint8_t* card, hipStream_t stream);
+hipError_t launch_pack(const CardGeom& geom, const void* k, const void* v, uint8_t* card, bool keys_per_channel,
+                       hipStream_t stream);
 hipError_t launch_unpack(const uint8_t* card, uint64_t card_bytes, const CardGeom& expect, void* k_out, void* v_out,
-                         uint32_t* status, hipStream_t stream);
+                         uint32_t* status, bool keys_per_channel, hipStream_t stream);
 hipError_t launch_inject(const uint8_t* card, uint64_t card_bytes, const CardGeom& expect, uint32_t layer_begin,
                          uint32_t layer_count, void* const* k_layers, void* const* v_layers, uint64_t head_stride_bytes,
                          uint64_t token_stride_bytes, const float (*cos_sin)[2], uint32_t* status, hipStream_t stream);

@@ -22,15 +22,15 @@ __device__ inline V card_load(const V* p) {
   return KEEP ? *p : __builtin_nontemporal_load(p);
 }
 
-// True when the header describes a layout-v1 card of the expected shape that fits in
-// card_bytes; fills `g` from the header's class counts.  Uniform over the grid.
+// True when the header describes a layout-v1 card of the expected shape and grouping (flags word) that
+// fits in card_bytes; fills `g` from the header's class counts.  Uniform over the grid.
 __device__ inline bool card_geometry_from_header(const uint8_t* card, uint64_t card_bytes, uint32_t layers,
                                                  uint32_t kv_heads, uint32_t head_dim, uint32_t group_size,
-                                                 uint64_t tokens, CardGeom& g) {
+                                                 uint64_t tokens, CardGeom& g, uint32_t want_flags = 0u) {
   const qkv_card_header_t* h = reinterpret_cast<const qkv_card_header_t*>(card);
   const uint32_t* w = reinterpret_cast<const uint32_t*>(card);
   bool ok = w[0] == 0x43564B51u && w[1] == 0x00445241u;          // "QKVC" "ARD\0"
-  ok = ok && h->version == QKV_CARD_VERSION && h->header_bytes == QKV_CARD_HEADER_BYTES;
+  ok = ok && h->version == QKV_CARD_VERSION && h->header_bytes == QKV_CARD_HEADER_BYTES && h->flags == want_flags;
   ok = ok && h->layers == layers && h->kv_heads == kv_heads && h->head_dim == head_dim &&
        h->group_size == group_size && h->tokens == tokens;
   uint64_t counts[4];

@@ -22,6 +22,7 @@ namespace {
 struct UnpackArgs {
   const uint8_t* card;
   uint64_t card_bytes;
+  uint32_t flags;                                    // the grouping the caller expects (header flags word)
   uint32_t layers, kv_heads, head_dim, group_size;   // the shape the outputs were sized for
   uint64_t tokens;
   uint8_t* k_out;
@@ -181,6 +182,54 @@ __device__ inline void unpack_tile(const uint8_t* card, const CardGeom& g, int c
   store_tile(my_row, lane, lpr_shift, data);
 }
 
+// A tile of key rows of a uniform card with groups per channel: a lane decodes the 32 tokens of two
+// neighbouring channels of one token block (their codes and pairs lie side by side in the card), turns
+// "two tokens of one channel" into "two channels of one token" and drops the tile into LDS row by row:
+// each of its 32 stores covers a whole row of the tile across the wave.  The tile then leaves like any
+// other.  Mirror image of the packing kernel's pack_tile_kc.
+template <int W, bool KEEP>
+__device__ inline void unpack_tile_kc(const uint8_t* card, const CardGeom& g, int c, uint32_t r0, uint32_t key_rows,
+                                      uint64_t my_row, uint32_t lane, u32x4* lds) {
+  const uint32_t lpr_shift = g.lpr_shift;
+  const uint32_t D = g.head_dim;
+  const uint32_t cp = lane & ((D >> 1) - 1u);               // channel pair: channels 2 cp, 2 cp + 1
+  const uint32_t tbl = lane >> (lpr_shift + 2u);            // token block inside the tile (head_dim 64: two)
+  const uint32_t blk = r0 / 32u + tbl;
+  uint32_t cw[2][W];
+  u32x2 pairs = (u32x2)(0u);
+#pragma unroll
+  for (int i = 0; i < W; ++i) { cw[0][i] = 0; cw[1][i] = 0; }
+  if (32u * blk < key_rows) {
+    const uint64_t grp = (uint64_t)blk * D + 2u * cp;       // and grp + 1
+    const u32x4* src = reinterpret_cast<const u32x4*>(card + g.off_codes[c] + grp * (4u * W));
+    uint32_t flat[2 * W];
+#pragma unroll
+    for (int h = 0; h < W / 2; ++h) {
+      const u32x4 t = card_load<KEEP>(src + h);
+      flat[4 * h] = t.x; flat[4 * h + 1] = t.y; flat[4 * h + 2] = t.z; flat[4 * h + 3] = t.w;
+    }
+#pragma unroll
+    for (int i = 0; i < W; ++i) { cw[0][i] = flat[i]; cw[1][i] = flat[W + i]; }
+    pairs = card_load<KEEP>(reinterpret_cast<const u32x2*>(card + g.off_meta[c]) + (grp >> 1));
+  }
+  uint32_t xa[16], xb[16];                                  // x[j] = tokens 2j, 2j+1 of the block, channel 2 cp / 2 cp + 1
+  decode_span<W>(cw[0], half_bits_to_float(pairs.x & 0xFFFFu), half_bits_to_float(pairs.x >> 16), xa);
+  decode_span<W>(cw[1], half_bits_to_float(pairs.y & 0xFFFFu), half_bits_to_float(pairs.y >> 16), xb);
+  uint32_t* lds32 = reinterpret_cast<uint32_t*>(lds);
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const uint32_t qa = ((32u * tbl + 2u * j) << lpr_shift) + (cp >> 2);      // chunk of (token 2j, channels 2 cp, 2 cp + 1)
+    const uint32_t qb = qa + (1u << lpr_shift);
+    lds32[swizzle(qa) * 4u + (cp & 3u)] = __builtin_amdgcn_perm(xb[j], xa[j], 0x05040100u);
+    lds32[swizzle(qb) * 4u + (cp & 3u)] = __builtin_amdgcn_perm(xb[j], xa[j], 0x07060302u);
+  }
+  u32x4 data[kTileIters];
+  const uint32_t rslot = swizzle(lane);
+#pragma unroll
+  for (int k = 0; k < kTileIters; ++k) data[k] = lds[k * kWaveSize + rslot];
+  store_tile(my_row, lane, lpr_shift, data);
+}
+
 template <bool KEEP, bool ROPE>
 __device__ inline void copy_tile(const uint8_t* card, const CardGeom& g, uint32_t r0, uint32_t n_rows, uint64_t my_row,
                                  uint32_t lane, const RopeLane& rope) {
@@ -210,20 +259,52 @@ __device__ inline void copy_tile(const uint8_t* card, const CardGeom& g, uint32_
 // Writes the header verdict; runs before the unpacking grid on the same stream.
 __global__ void unpack_status_kernel(UnpackArgs a) {
   CardGeom g;
-  const bool ok = card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, g);
+  const bool ok = card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, g,
+                                            a.flags);
   if (threadIdx.x == 0 && blockIdx.x == 0) *a.status = ok ? 0u : QKV_STATUS_BAD_HEADER;
 }
 
-template <int G, bool KEEP>
+// The tiles of width class C, dealt to the waves round-robin from the segment's end, continuing where
+// the previous class stopped.
+template <int C, int G, bool KEEP, bool KC>
+__device__ inline void unpack_class(const UnpackArgs& a, const CardGeom& g, uint32_t gw, uint32_t n_waves, uint32_t lane,
+                                    u32x4* lds, uint32_t& cum, uint32_t& bad) {
+  const uint32_t n_rows = g.planes * g.n[C];
+  if (n_rows == 0) return;
+  const uint32_t tile_rows = kTileChunks >> g.lpr_shift;
+  const uint32_t tiles = (n_rows + tile_rows - 1) / tile_rows;
+  const uint32_t first = (gw + n_waves - cum) % n_waves;
+  const RopeLane no_rope = {};
+  for (uint32_t i = first; i < tiles; i += n_waves) {
+    const uint32_t r0 = (tiles - 1 - i) * tile_rows;
+    const uint64_t my_row = tile_row_address(a, g, C, r0, n_rows, lane, tile_rows, bad);
+    if constexpr (C == 3) {
+      copy_tile<KEEP, false>(a.card, g, r0, n_rows, my_row, lane, no_rope);
+    } else {
+      constexpr int W = C == 0 ? 2 : C == 1 ? 4 : 8;
+      if (KC && r0 < (n_rows >> 1)) unpack_tile_kc<W, KEEP>(a.card, g, C, r0, n_rows >> 1, my_row, lane, lds);   // key rows
+      else unpack_tile<W, G, KEEP, false>(a.card, g, C, r0, n_rows, my_row, lane, lds, no_rope);
+    }
+  }
+  cum = (cum + tiles) % n_waves;
+}
+
+// KC: a uniform card whose key planes (the first half of every segment) are grouped per channel.
+template <int G, bool KEEP, bool KC>
 __global__ __launch_bounds__(kBlockThreads) void unpack_kernel(UnpackArgs a) {
   __shared__ u32x4 lds[kWavesPerBlock][kTileChunks];
   CardGeom g;
-  if (!card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, g)) return;          // uniform over the grid: every wave leaves
+  if (!card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, g,
+                                 KC ? QKV_FLAG_KEYS_PER_CHANNEL : 0u)) return;          // uniform over the grid: every wave leaves
+  if (KC) {                                      // the shapes the per-channel tiles are written for
+    const bool uniform = g.n[0] == g.tokens || g.n[1] == g.tokens || g.n[2] == g.tokens;
+    const uint32_t tile_tokens = kTileChunks >> g.lpr_shift;
+    if (!uniform || g.group_size != 32u || g.head_dim > 128u || g.tokens % max(32u, tile_tokens) != 0u) return;
+  }
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t wave = threadIdx.x >> 6;
   const uint32_t gw = blockIdx.x * kWavesPerBlock + wave;
   const uint32_t n_waves = gridDim.x * kWavesPerBlock;
-  const uint32_t tile_rows = kTileChunks >> g.lpr_shift;
   u32x4* my_lds = lds[wave];
 
   // The card is walked from its end to its start: right after packing, its tail is what the
@@ -231,23 +312,10 @@ __global__ __launch_bounds__(kBlockThreads) void unpack_kernel(UnpackArgs a) {
   // front to back; cards that fit, or that are several times larger, are indifferent).
   uint32_t bad = 0;
   uint32_t cum = 0;
-  const RopeLane no_rope = {};
-#pragma unroll
-  for (int c = 3; c >= 0; --c) {
-    const uint32_t n_rows = g.planes * g.n[c];
-    if (n_rows == 0) continue;
-    const uint32_t tiles = (n_rows + tile_rows - 1) / tile_rows;
-    const uint32_t first = (gw + n_waves - cum) % n_waves;
-    for (uint32_t i = first; i < tiles; i += n_waves) {
-      const uint32_t r0 = (tiles - 1 - i) * tile_rows;
-      const uint64_t my_row = tile_row_address(a, g, c, r0, n_rows, lane, tile_rows, bad);
-      if (c == 0) unpack_tile<2, G, KEEP, false>(a.card, g, 0, r0, n_rows, my_row, lane, my_lds, no_rope);
-      if (c == 1) unpack_tile<4, G, KEEP, false>(a.card, g, 1, r0, n_rows, my_row, lane, my_lds, no_rope);
-      if (c == 2) unpack_tile<8, G, KEEP, false>(a.card, g, 2, r0, n_rows, my_row, lane, my_lds, no_rope);
-      if (c == 3) copy_tile<KEEP, false>(a.card, g, r0, n_rows, my_row, lane, no_rope);
-    }
-    cum = (cum + tiles) % n_waves;
-  }
+  unpack_class<3, G, KEEP, KC>(a, g, gw, n_waves, lane, my_lds, cum, bad);
+  unpack_class<2, G, KEEP, KC>(a, g, gw, n_waves, lane, my_lds, cum, bad);
+  unpack_class<1, G, KEEP, KC>(a, g, gw, n_waves, lane, my_lds, cum, bad);
+  unpack_class<0, G, KEEP, KC>(a, g, gw, n_waves, lane, my_lds, cum, bad);
   if (bad && a.status) atomicOr(a.status, QKV_STATUS_BAD_ORDER);
 }
 
@@ -342,10 +410,11 @@ __global__ __launch_bounds__(kBlockThreads) void inject_kernel(InjectArgs a) {
 }  // namespace
 
 hipError_t launch_unpack(const uint8_t* card, uint64_t card_bytes, const CardGeom& expect, void* k_out, void* v_out,
-                         uint32_t* status, hipStream_t stream) {
+                         uint32_t* status, bool keys_per_channel, hipStream_t stream) {
   UnpackArgs a;
   a.card = card;
   a.card_bytes = card_bytes;
+  a.flags = keys_per_channel ? QKV_FLAG_KEYS_PER_CHANNEL : 0u;
   a.layers = expect.layers; a.kv_heads = expect.kv_heads; a.head_dim = expect.head_dim; a.group_size = expect.group_size;
   a.tokens = expect.tokens;
   a.k_out = static_cast<uint8_t*>(k_out);
@@ -362,13 +431,18 @@ hipError_t launch_unpack(const uint8_t* card, uint64_t card_bytes, const CardGeo
   const uint64_t tiles = (rows + tile_rows - 1) / tile_rows + 3;
   const dim3 grid(grid_blocks(tiles)), block(kBlockThreads);
   const bool keep = card_bytes <= kCacheResidentCardBytes;
+  if (keys_per_channel) {                        // group size 32 only (checked by the caller)
+    if (keep) hipLaunchKernelGGL((unpack_kernel<32, true, true>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((unpack_kernel<32, false, true>), grid, block, 0, stream, a);
+    return hipGetLastError();
+  }
   switch (expect.group_size * 2 + (keep ? 1 : 0)) {
-    case 65: hipLaunchKernelGGL((unpack_kernel<32, true>), grid, block, 0, stream, a); break;
-    case 64: hipLaunchKernelGGL((unpack_kernel<32, false>), grid, block, 0, stream, a); break;
-    case 129: hipLaunchKernelGGL((unpack_kernel<64, true>), grid, block, 0, stream, a); break;
-    case 128: hipLaunchKernelGGL((unpack_kernel<64, false>), grid, block, 0, stream, a); break;
-    case 257: hipLaunchKernelGGL((unpack_kernel<128, true>), grid, block, 0, stream, a); break;
-    default: hipLaunchKernelGGL((unpack_kernel<128, false>), grid, block, 0, stream, a); break;
+    case 65: hipLaunchKernelGGL((unpack_kernel<32, true, false>), grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((unpack_kernel<32, false, false>), grid, block, 0, stream, a); break;
+    case 129: hipLaunchKernelGGL((unpack_kernel<64, true, false>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((unpack_kernel<64, false, false>), grid, block, 0, stream, a); break;
+    case 257: hipLaunchKernelGGL((unpack_kernel<128, true, false>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((unpack_kernel<128, false, false>), grid, block, 0, stream, a); break;
   }
   return hipGetLastError();
 }
@@ -398,7 +472,7 @@ hipError_t launch_inject(const uint8_t* card, uint64_t card_bytes, const CardGeo
   }
   if (status) {
     UnpackArgs u;
-    u.card = card; u.card_bytes = card_bytes;
+    u.card = card; u.card_bytes = card_bytes; u.flags = 0;
     u.layers = expect.layers; u.kv_heads = expect.kv_heads; u.head_dim = expect.head_dim; u.group_size = expect.group_size;
     u.tokens = expect.tokens;
     u.k_out = nullptr; u.v_out = nullptr; u.status = status;

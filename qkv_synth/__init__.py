@@ -155,6 +155,8 @@ CONFIGS = {
                               data_seed=4001, bits=("constant", 4)),
     "llama8b_8k_u2_g64": dict(layers=32, kv_heads=8, tokens=8192, head_dim=128, group_size=64, kind="llama",
                               data_seed=4001, bits=("constant", 2)),
+    "llama8b_8k_u4_g32_kc": dict(layers=32, kv_heads=8, tokens=8192, head_dim=128, group_size=32, kind="llama",
+                                 data_seed=4001, bits=("constant", 4), keys_per_channel=True),
     "llama8b_32k_hops": dict(layers=32, kv_heads=8, tokens=32768, head_dim=128, group_size=32, kind="llama",
                              data_seed=5001, bits=("hops", (5003, 5004, 5005, 5006), (6.0, 4.0, 3.0, 2.0))),
 }

@@ -39,7 +39,7 @@ def widths_for(cfg, dev):
 
 
 @pytest.mark.parametrize("name", ["llama8b_1k_b5", "llama8b_1k_b4", "llama8b_8k_b3", "llama8b_8k_u4_g64",
-                                  "llama8b_8k_u2_g64"])
+                                  "llama8b_8k_u2_g64", "llama8b_8k_u4_g32_kc"])
 def test_benchmark_workload_whole_card_and_cache(name):
     cfg = qkv_synth.CONFIGS[name]
     L, H, T, D, G = cfg["layers"], cfg["kv_heads"], cfg["tokens"], cfg["head_dim"], cfg["group_size"]
@@ -49,13 +49,14 @@ def test_benchmark_workload_whole_card_and_cache(name):
     desc = qkv.Desc.make(L, H, T, D, G, model_id=8, sender_id=1, position_offset=5)
     n = qkv.card_bytes(desc, counts)
     card = torch.full((n + 256,), 0x5A, dtype=torch.uint8, device=DEV)
+    kc = bool(cfg.get("keys_per_channel"))          # uniform card, keys grouped per channel
     say("%s: pack" % name)
-    qkv.quantize_pack(desc, K, V, bits, counts, card)
+    (qkv.quantize_pack_kc if kc else qkv.quantize_pack)(desc, K, V, bits, counts, card)
     K_out = torch.empty_like(K)
     V_out = torch.empty_like(V)
     status = torch.ones(1, dtype=torch.int32, device=DEV)
     say("%s: unpack" % name)
-    qkv.unpack_dequant(card, desc, K_out, V_out, status=status, card_nbytes=n)
+    (qkv.unpack_dequant_kc if kc else qkv.unpack_dequant)(card, desc, K_out, V_out, status=status, card_nbytes=n)
     torch.cuda.synchronize()
     assert int(status.item()) == 0
     assert int((card[n:] != 0x5A).sum()) == 0, "bytes behind the card were written"
@@ -63,13 +64,15 @@ def test_benchmark_workload_whole_card_and_cache(name):
     say("%s: oracle" % name)
     rd = ref.make_desc(L, H, T, D, G, 8, 1, 5)
     bits_h = bits.cpu().numpy()
-    want = ref.quantize_pack(rd, K.cpu().numpy(), V.cpu().numpy(), bits_h, counts)
+    want = (ref.quantize_pack_kc if kc else ref.quantize_pack)(rd, K.cpu().numpy(), V.cpu().numpy(), bits_h, counts)
     got = card[:n].cpu().numpy()
     diff = np.flatnonzero(got != want)
     assert diff.size == 0, "card differs at %d bytes, first offset %d" % (diff.size, int(diff[0]))
-    wk, wv = ref.unpack_dequant(want, rd)
+    wk, wv = (ref.unpack_dequant_kc if kc else ref.unpack_dequant)(want, rd)
     assert np.array_equal(K_out.cpu().numpy().view(np.uint16), wk)
     assert np.array_equal(V_out.cpu().numpy().view(np.uint16), wv)
+    if kc:
+        return
     # the decoded cache stays within scale/2 (+ output rounding) of the input for quantized tokens: spot check
     t = int(np.flatnonzero(bits_h != 16)[0])
     x = K[0, 0, t].float().cpu().numpy()
