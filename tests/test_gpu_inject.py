@@ -198,3 +198,29 @@ def test_inject_host_errors():
     assert call(0, 1, nbytes=100) == -5
     assert L.qkv_inject_layers(card.data_ptr(), card.numel(), ctypes.byref(desc), None, None, None) == -1
     torch.cuda.synchronize()
+
+
+def test_random_shapes_ranges_and_shifts():
+    rng = np.random.default_rng(2024)
+    for case in range(24):
+        D = int(rng.choice([64, 128, 256]))
+        G = int(rng.choice([g for g in (32, 64, 128) if g <= D]))
+        L = int(rng.integers(1, 6))
+        H = int(rng.integers(1, 5))
+        T = int(rng.integers(1, 700))
+        lb = int(rng.integers(0, L))
+        n = int(rng.integers(1, L - lb + 1))
+        prefix = int(rng.integers(0, 50))
+        cap = prefix + T + int(rng.integers(0, 30))
+        rope = None if case % 3 == 0 else (float(rng.choice([10000.0, 500000.0, 1e6])), int(rng.integers(-5000, 100000)))
+        kind = ["choice", "budget", "uniform"][case % 3]
+        if kind == "choice":
+            bits = qkv_synth.make_bits_uniform_choice(T, 3000 + case).numpy()
+        elif kind == "budget":
+            bits, _ = ref.assign_bits(qkv_synth.make_scores(T, 3100 + case).numpy(), float(rng.choice([2.5, 3.0, 5.0, 9.0])))
+        else:
+            bits = np.full(T, int(rng.choice([2, 4, 8, 16])), np.uint8)
+        desc, rdesc, card, host = make_card(L, H, T, D, G, 3200 + case, bits=bits)
+        check(desc, rdesc, card, host, lb, n, cap, prefix, rope,
+              "inject random %d: L=%d H=%d T=%d D=%d G=%d layers [%d,%d) prefix=%d rope=%s %s"
+              % (case, L, H, T, D, G, lb, lb + n, prefix, rope, kind))

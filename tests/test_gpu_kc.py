@@ -146,3 +146,15 @@ def test_kc_host_errors():
     d = qkv.Desc.make(1, 1, 48, 128, 32)
     assert L.qkv_unpack_dequant_kc(card.data_ptr(), card.numel(), ctypes.byref(d), K.data_ptr(), K.data_ptr(), None, None) == -2
     torch.cuda.synchronize()
+
+
+def test_random_shapes():
+    rng = np.random.default_rng(77)
+    for case in range(12):
+        D = int(rng.choice([64, 128]))
+        step = 64 if D == 64 else 32
+        T = step * int(rng.integers(1, 40))
+        L = int(rng.integers(1, 5))
+        H = int(rng.integers(1, 5))
+        width = int(rng.choice([2, 4, 8]))
+        run(L, H, T, D, width, 500 + case, "kc random %d: L=%d H=%d T=%d D=%d width=%d" % (case, L, H, T, D, width))
