@@ -282,9 +282,9 @@ int qkv_unpack_dequant(const void* card_dev, uint64_t card_bytes, const qkv_desc
  * qkv_unpack_dequant and behave like them, with these extra conditions (QKV_ERR_SHAPE otherwise):
  * group_size 32, head_dim 64 or 128, tokens a multiple of 32 (of 64 at head_dim 64); and
  * (QKV_ERR_COUNTS) counts naming exactly one of the widths 2, 4, 8 for all tokens.  A card of
- * one grouping handed to the other grouping's calls (qkv_unpack_dequant, qkv_inject_layers and
- * qkv_card_attend read per-token groups only) is refused on the device: QKV_STATUS_BAD_HEADER,
- * nothing written.
+ * one grouping handed to the other grouping's call is refused on the device (QKV_STATUS_BAD_HEADER,
+ * nothing written); qkv_inject_layers takes either grouping (its keys_per_channel field says
+ * which), qkv_card_attend reads per-token groups only.
  */
 int qkv_quantize_pack_kc(const qkv_desc_t* desc, const void* k_dev, const void* v_dev, const uint8_t* bits_dev,
                          const int64_t counts[4], void* card_dev, uint64_t card_capacity, void* stream);
@@ -332,6 +332,8 @@ typedef struct qkv_inject {
   int64_t head_stride, token_stride;  /* in fp16 elements */
   double rope_base;                 /* 0: no realignment */
   int64_t rope_delta;               /* positions to move the keys by */
+  int32_t keys_per_channel;         /* 1: the card was made by qkv_quantize_pack_kc (its shape rules apply), else 0 */
+  int32_t reserved;                 /* 0 */
 } qkv_inject_t;
 
 int qkv_inject_layers(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect,

@@ -38,11 +38,11 @@ def rope_rotate(rows_u16, cos_t, sin_t):
     return out
 
 
-def inject_layers(card, desc, k_layers, v_layers, layer_begin, prefix, rope=None):
+def inject_layers(card, desc, k_layers, v_layers, layer_begin, prefix, rope=None, keys_per_channel=False):
     """Writes layers layer_begin .. layer_begin + len(k_layers) - 1 of the card into the given per-layer
     uint16 arrays [kv_heads, capacity, head_dim] at token positions prefix .. prefix + T - 1.
-    rope: None or (base, delta)."""
-    K, V = ref.unpack_dequant(card, desc)                    # [L, H, T, D] uint16
+    rope: None or (base, delta).  keys_per_channel: the card is a uniform card with per-channel key groups."""
+    K, V = (ref.unpack_dequant_kc if keys_per_channel else ref.unpack_dequant)(card, desc)      # [L, H, T, D] uint16
     T, D = desc.tokens, desc.head_dim
     table = rope_table(D, rope[0], rope[1]) if rope is not None else None
     for i, (kl, vl) in enumerate(zip(k_layers, v_layers)):

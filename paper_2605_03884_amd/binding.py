@@ -65,6 +65,8 @@ class Inject(ctypes.Structure):
         ("token_stride", ctypes.c_int64),
         ("rope_base", ctypes.c_double),
         ("rope_delta", ctypes.c_int64),
+        ("keys_per_channel", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
     ]
 
 
@@ -273,7 +275,7 @@ def unpack_dequant_kc(card, expect, k_out, v_out, status=None, card_nbytes=None,
 
 
 def inject_layers(card, expect, k_layers, v_layers, layer_begin=0, rope_base=0.0, rope_delta=0, status=None,
-                  card_nbytes=None, stream=None):
+                  card_nbytes=None, stream=None, keys_per_channel=False):
     """Layers layer_begin .. layer_begin + len(k_layers) - 1 of the card into per-layer tensors.
 
     k_layers, v_layers: lists of device float16 tensors (views are fine) of shape [kv_heads, >= tokens, head_dim]
@@ -293,7 +295,8 @@ def inject_layers(card, expect, k_layers, v_layers, layer_begin=0, rope_base=0.0
             raise ValueError("layer tensors must share their strides and have contiguous rows")
     kp = (ctypes.c_void_p * count)(*[t.data_ptr() for t in k_layers])
     vp_ = (ctypes.c_void_p * count)(*[t.data_ptr() for t in v_layers])
-    where = Inject(int(layer_begin), count, kp, vp_, ref_strides[0], ref_strides[1], float(rope_base), int(rope_delta))
+    where = Inject(int(layer_begin), count, kp, vp_, ref_strides[0], ref_strides[1], float(rope_base), int(rope_delta),
+                   1 if keys_per_channel else 0, 0)
     sp = ctypes.c_void_p(0) if status is None else _dev_ptr(status, None, "status")
     _check(lib().qkv_inject_layers(_dev_ptr(card, torch.uint8, "card"), n, ctypes.byref(expect), ctypes.byref(where),
                                    sp, _stream(stream)), "qkv_inject_layers")

@@ -374,6 +374,11 @@ int qkv_inject_layers(const void* card_dev, uint64_t card_bytes, const qkv_desc_
   if (!(where->rope_base >= 0.0) || !std::isfinite(where->rope_base) || where->rope_delta <= -(1ll << 31) ||
       where->rope_delta >= (1ll << 31))
     return QKV_ERR_SHAPE;
+  if (where->keys_per_channel != 0) {
+    if (where->keys_per_channel != 1) return QKV_ERR_SHAPE;
+    const int rk = check_keys_per_channel(expect);
+    if (rk) return rk;
+  }
   if (card_bytes < QKV_CARD_HEADER_BYTES) return QKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(card_dev) % QKV_CARD_ALIGN != 0 || reinterpret_cast<uintptr_t>(status_dev) % 4 != 0)
     return QKV_ERR_ALIGN;
@@ -399,7 +404,7 @@ int qkv_inject_layers(const void* card_dev, uint64_t card_bytes, const qkv_desc_
   build_geom(g, expect->layers, expect->kv_heads, expect->head_dim, expect->group_size, expect->tokens, zero);
   if (launch_inject(static_cast<const uint8_t*>(card_dev), card_bytes, g, (uint32_t)where->layer_begin,
                     (uint32_t)where->layer_count, where->k_layers, where->v_layers, (uint64_t)where->head_stride * 2u,
-                    (uint64_t)where->token_stride * 2u, rope ? cos_sin : nullptr, status_dev,
+                    (uint64_t)where->token_stride * 2u, rope ? cos_sin : nullptr, where->keys_per_channel == 1, status_dev,
                     static_cast<hipStream_t>(stream)) != hipSuccess)
     return QKV_ERR_HIP;
   return QKV_OK;

@@ -187,9 +187,9 @@ __device__ inline void unpack_tile(const uint8_t* card, const CardGeom& g, int c
 // "two tokens of one channel" into "two channels of one token" and drops the tile into LDS row by row:
 // each of its 32 stores covers a whole row of the tile across the wave.  The tile then leaves like any
 // other.  Mirror image of the packing kernel's pack_tile_kc.
-template <int W, bool KEEP>
+template <int W, bool KEEP, bool ROPE>
 __device__ inline void unpack_tile_kc(const uint8_t* card, const CardGeom& g, int c, uint32_t r0, uint32_t key_rows,
-                                      uint64_t my_row, uint32_t lane, u32x4* lds) {
+                                      uint64_t my_row, uint32_t lane, u32x4* lds, const RopeLane& rope) {
   const uint32_t lpr_shift = g.lpr_shift;
   const uint32_t D = g.head_dim;
   const uint32_t cp = lane & ((D >> 1) - 1u);               // channel pair: channels 2 cp, 2 cp + 1
@@ -227,6 +227,11 @@ __device__ inline void unpack_tile_kc(const uint8_t* card, const CardGeom& g, in
   const uint32_t rslot = swizzle(lane);
 #pragma unroll
   for (int k = 0; k < kTileIters; ++k) data[k] = lds[k * kWaveSize + rslot];
+  if (ROPE) {
+    const uint32_t pslot = swizzle(lane ^ rope.partner);
+#pragma unroll
+    for (int k = 0; k < kTileIters; ++k) data[k] = rotate_chunk(data[k], lds[k * kWaveSize + pslot], rope);
+  }
   store_tile(my_row, lane, lpr_shift, data);
 }
 
@@ -282,7 +287,7 @@ __device__ inline void unpack_class(const UnpackArgs& a, const CardGeom& g, uint
       copy_tile<KEEP, false>(a.card, g, r0, n_rows, my_row, lane, no_rope);
     } else {
       constexpr int W = C == 0 ? 2 : C == 1 ? 4 : 8;
-      if (KC && r0 < (n_rows >> 1)) unpack_tile_kc<W, KEEP>(a.card, g, C, r0, n_rows >> 1, my_row, lane, lds);   // key rows
+      if (KC && r0 < (n_rows >> 1)) unpack_tile_kc<W, KEEP, false>(a.card, g, C, r0, n_rows >> 1, my_row, lane, lds, no_rope);   // key rows
       else unpack_tile<W, G, KEEP, false>(a.card, g, C, r0, n_rows, my_row, lane, lds, no_rope);
     }
   }
@@ -346,7 +351,7 @@ __device__ inline uint64_t inject_row_address(const InjectArgs& a, const CardGeo
 // One (class, K or V) range of the card's rows for the layer range: its tiles are dealt to the
 // waves round-robin, continuing where the previous range stopped.  (K and V as separate
 // instances of this code measure faster than one instance looping over both.)
-template <int C, int KV, int G, bool KEEP, bool ROPE>
+template <int C, int KV, int G, bool KEEP, bool ROPE, bool KC>
 __device__ inline void inject_range(const InjectArgs& a, const CardGeom& g, const RopeLane& rope, uint32_t gw,
                                     uint32_t n_waves, uint32_t lane, u32x4* lds, uint32_t& cum, uint32_t& bad) {
   const uint32_t n = g.n[C];
@@ -365,17 +370,24 @@ __device__ inline void inject_range(const InjectArgs& a, const CardGeom& g, cons
       copy_tile<KEEP, rot>(a.card, g, r0, seg_hi, my_row, lane, rope);
     } else {
       constexpr int W = C == 0 ? 2 : C == 1 ? 4 : 8;
-      unpack_tile<W, G, KEEP, rot>(a.card, g, C, r0, seg_hi, my_row, lane, lds, rope);
+      if (KC && KV == 0) unpack_tile_kc<W, KEEP, rot>(a.card, g, C, r0, (g.planes >> 1) * n, my_row, lane, lds, rope);
+      else unpack_tile<W, G, KEEP, rot>(a.card, g, C, r0, seg_hi, my_row, lane, lds, rope);
     }
   }
   cum = (cum + tiles) % n_waves;
 }
 
-template <int G, bool KEEP, bool ROPE>
+template <int G, bool KEEP, bool ROPE, bool KC>
 __global__ __launch_bounds__(kBlockThreads) void inject_kernel(InjectArgs a) {
   __shared__ u32x4 lds[kWavesPerBlock][kTileChunks];
   CardGeom g;
-  if (!card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, g)) return;
+  if (!card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, g,
+                                 KC ? QKV_FLAG_KEYS_PER_CHANNEL : 0u)) return;
+  if (KC) {                                      // the shapes the per-channel tiles are written for
+    const bool uniform = g.n[0] == g.tokens || g.n[1] == g.tokens || g.n[2] == g.tokens;
+    const uint32_t tile_tokens = kTileChunks >> g.lpr_shift;
+    if (!uniform || g.group_size != 32u || g.head_dim > 128u || g.tokens % max(32u, tile_tokens) != 0u) return;
+  }
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t wave = threadIdx.x >> 6;
   const uint32_t gw = blockIdx.x * kWavesPerBlock + wave;
@@ -396,14 +408,14 @@ __global__ __launch_bounds__(kBlockThreads) void inject_kernel(InjectArgs a) {
 
   // from the card's end to its start, as the dense kernel does
   uint32_t bad = 0, cum = 0;
-  inject_range<3, 1, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
-  inject_range<3, 0, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
-  inject_range<2, 1, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
-  inject_range<2, 0, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
-  inject_range<1, 1, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
-  inject_range<1, 0, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
-  inject_range<0, 1, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
-  inject_range<0, 0, G, KEEP, ROPE>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<3, 1, G, KEEP, ROPE, KC>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<3, 0, G, KEEP, ROPE, KC>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<2, 1, G, KEEP, ROPE, KC>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<2, 0, G, KEEP, ROPE, KC>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<1, 1, G, KEEP, ROPE, KC>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<1, 0, G, KEEP, ROPE, KC>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<0, 1, G, KEEP, ROPE, KC>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
+  inject_range<0, 0, G, KEEP, ROPE, KC>(a, g, rope, gw, n_waves, lane, my_lds, cum, bad);
   if (bad && a.status) atomicOr(a.status, QKV_STATUS_BAD_ORDER);
 }
 
@@ -449,7 +461,8 @@ hipError_t launch_unpack(const uint8_t* card, uint64_t card_bytes, const CardGeo
 
 hipError_t launch_inject(const uint8_t* card, uint64_t card_bytes, const CardGeom& expect, uint32_t layer_begin,
                          uint32_t layer_count, void* const* k_layers, void* const* v_layers, uint64_t head_stride_bytes,
-                         uint64_t token_stride_bytes, const float (*cos_sin)[2], uint32_t* status, hipStream_t stream) {
+                         uint64_t token_stride_bytes, const float (*cos_sin)[2], bool keys_per_channel, uint32_t* status,
+                         hipStream_t stream) {
   InjectArgs a;
   a.card = card;
   a.card_bytes = card_bytes;
@@ -472,7 +485,7 @@ hipError_t launch_inject(const uint8_t* card, uint64_t card_bytes, const CardGeo
   }
   if (status) {
     UnpackArgs u;
-    u.card = card; u.card_bytes = card_bytes; u.flags = 0;
+    u.card = card; u.card_bytes = card_bytes; u.flags = keys_per_channel ? QKV_FLAG_KEYS_PER_CHANNEL : 0u;
     u.layers = expect.layers; u.kv_heads = expect.kv_heads; u.head_dim = expect.head_dim; u.group_size = expect.group_size;
     u.tokens = expect.tokens;
     u.k_out = nullptr; u.v_out = nullptr; u.status = status;
@@ -486,20 +499,29 @@ hipError_t launch_inject(const uint8_t* card, uint64_t card_bytes, const CardGeo
   const uint64_t tiles = (rows + tile_rows - 1) / tile_rows + 8;
   const dim3 grid(grid_blocks(tiles)), block(kBlockThreads);
   const bool keep = card_bytes <= kCacheResidentCardBytes;
+  if (keys_per_channel) {                        // group size 32 only (checked by the caller)
+    switch ((keep ? 2 : 0) + (a.rope ? 1 : 0)) {
+      case 3: hipLaunchKernelGGL((inject_kernel<32, true, true, true>), grid, block, 0, stream, a); break;
+      case 2: hipLaunchKernelGGL((inject_kernel<32, true, false, true>), grid, block, 0, stream, a); break;
+      case 1: hipLaunchKernelGGL((inject_kernel<32, false, true, true>), grid, block, 0, stream, a); break;
+      default: hipLaunchKernelGGL((inject_kernel<32, false, false, true>), grid, block, 0, stream, a); break;
+    }
+    return hipGetLastError();
+  }
   const int variant = (int)expect.group_size * 4 + (keep ? 2 : 0) + (a.rope ? 1 : 0);
   switch (variant) {
-    case 131: hipLaunchKernelGGL((inject_kernel<32, true, true>), grid, block, 0, stream, a); break;
-    case 130: hipLaunchKernelGGL((inject_kernel<32, true, false>), grid, block, 0, stream, a); break;
-    case 129: hipLaunchKernelGGL((inject_kernel<32, false, true>), grid, block, 0, stream, a); break;
-    case 128: hipLaunchKernelGGL((inject_kernel<32, false, false>), grid, block, 0, stream, a); break;
-    case 259: hipLaunchKernelGGL((inject_kernel<64, true, true>), grid, block, 0, stream, a); break;
-    case 258: hipLaunchKernelGGL((inject_kernel<64, true, false>), grid, block, 0, stream, a); break;
-    case 257: hipLaunchKernelGGL((inject_kernel<64, false, true>), grid, block, 0, stream, a); break;
-    case 256: hipLaunchKernelGGL((inject_kernel<64, false, false>), grid, block, 0, stream, a); break;
-    case 515: hipLaunchKernelGGL((inject_kernel<128, true, true>), grid, block, 0, stream, a); break;
-    case 514: hipLaunchKernelGGL((inject_kernel<128, true, false>), grid, block, 0, stream, a); break;
-    case 513: hipLaunchKernelGGL((inject_kernel<128, false, true>), grid, block, 0, stream, a); break;
-    default: hipLaunchKernelGGL((inject_kernel<128, false, false>), grid, block, 0, stream, a); break;
+    case 131: hipLaunchKernelGGL((inject_kernel<32, true, true, false>), grid, block, 0, stream, a); break;
+    case 130: hipLaunchKernelGGL((inject_kernel<32, true, false, false>), grid, block, 0, stream, a); break;
+    case 129: hipLaunchKernelGGL((inject_kernel<32, false, true, false>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((inject_kernel<32, false, false, false>), grid, block, 0, stream, a); break;
+    case 259: hipLaunchKernelGGL((inject_kernel<64, true, true, false>), grid, block, 0, stream, a); break;
+    case 258: hipLaunchKernelGGL((inject_kernel<64, true, false, false>), grid, block, 0, stream, a); break;
+    case 257: hipLaunchKernelGGL((inject_kernel<64, false, true, false>), grid, block, 0, stream, a); break;
+    case 256: hipLaunchKernelGGL((inject_kernel<64, false, false, false>), grid, block, 0, stream, a); break;
+    case 515: hipLaunchKernelGGL((inject_kernel<128, true, true, false>), grid, block, 0, stream, a); break;
+    case 514: hipLaunchKernelGGL((inject_kernel<128, true, false, false>), grid, block, 0, stream, a); break;
+    case 513: hipLaunchKernelGGL((inject_kernel<128, false, true, false>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((inject_kernel<128, false, false, false>), grid, block, 0, stream, a); break;
   }
   return hipGetLastError();
 }

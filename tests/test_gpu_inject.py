@@ -181,10 +181,10 @@ def test_inject_host_errors():
     kc, vc = caches(4, 2, 64, 128)
     L = qkv.lib()
 
-    def call(lb, n, hs=64 * 128, ts=128, base=0.0, delta=0, kptrs=None, card_ptr=None, nbytes=None):
+    def call(lb, n, hs=64 * 128, ts=128, base=0.0, delta=0, kptrs=None, card_ptr=None, nbytes=None, per_channel=0):
         kp = (ctypes.c_void_p * max(n, 1))(*(kptrs if kptrs is not None else [kc[i % 4].data_ptr() for i in range(max(n, 1))]))
         vp = (ctypes.c_void_p * max(n, 1))(*[vc[i % 4].data_ptr() for i in range(max(n, 1))])
-        w = qkv.Inject(lb, n, kp, vp, hs, ts, base, delta)
+        w = qkv.Inject(lb, n, kp, vp, hs, ts, base, delta, per_channel, 0)
         return L.qkv_inject_layers(card.data_ptr() if card_ptr is None else card_ptr, card.numel() if nbytes is None else nbytes,
                                    ctypes.byref(desc), ctypes.byref(w), None, None)
 
@@ -196,6 +196,8 @@ def test_inject_host_errors():
     assert call(0, 1, kptrs=[None]) == -1
     assert call(0, 1, card_ptr=card.data_ptr() + 16) == -6
     assert call(0, 1, nbytes=100) == -5
+    assert call(0, 1, per_channel=2) == -2
+    assert call(0, 1, per_channel=1) == 0                 # shape fits the per-channel rules; the device refuses the card's grouping
     assert L.qkv_inject_layers(card.data_ptr(), card.numel(), ctypes.byref(desc), None, None, None) == -1
     torch.cuda.synchronize()
 

@@ -112,9 +112,13 @@ def test_the_two_groupings_refuse_each_other_on_the_device():
     torch.cuda.synchronize()
     assert int(status.item()) == qkv.STATUS_BAD_HEADER
     assert bool((ko.view(torch.int16) == canary).all()) and bool((vo.view(torch.int16) == canary).all())
-    # injection and attention read per-token groups only
+    # injection must be told the grouping; attention reads per-token groups only
     status.zero_()
     qkv.inject_layers(card_kc, desc, [ko[0], ko[1]], [vo[0], vo[1]], 0, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == qkv.STATUS_BAD_HEADER and bool((ko.view(torch.int16) == canary).all())
+    status.zero_()
+    qkv.inject_layers(card_pt, desc, [ko[0], ko[1]], [vo[0], vo[1]], 0, status=status, keys_per_channel=True)
     torch.cuda.synchronize()
     assert int(status.item()) == qkv.STATUS_BAD_HEADER and bool((ko.view(torch.int16) == canary).all())
     q = torch.zeros((2, 8, 128), dtype=torch.float16, device=DEV)
@@ -158,3 +162,32 @@ def test_random_shapes():
         H = int(rng.integers(1, 5))
         width = int(rng.choice([2, 4, 8]))
         run(L, H, T, D, width, 500 + case, "kc random %d: L=%d H=%d T=%d D=%d width=%d" % (case, L, H, T, D, width))
+
+
+@pytest.mark.parametrize("D,T", [(128, 96), (64, 128)])
+@pytest.mark.parametrize("width", [2, 4, 8])
+def test_injection_of_per_channel_cards_with_realignment(D, T, width):
+    from oracle import inject_ref
+    L, H = 4, 2
+    say("kc inject D=%d T=%d width=%d" % (D, T, width))
+    K, V, bits, counts, desc, rdesc = problem(L, H, T, D, width, 900 + D + width)
+    card = torch.empty(qkv.card_bytes(desc, counts), dtype=torch.uint8, device=DEV)
+    qkv.quantize_pack_kc(desc, K.to(DEV), V.to(DEV), torch.from_numpy(bits).to(DEV), counts, card)
+    torch.cuda.synchronize()
+    host = card.cpu().numpy()
+    canary, prefix, cap = 0x7E11, 5, T + 9
+    for lb, n, rope in ((0, 4, None), (1, 2, (10000.0, 77)), (3, 1, (500000.0, -3)), (0, 4, (10000.0, 4096))):
+        kc_ = [torch.zeros((H, cap, D), dtype=torch.int16, device=DEV).fill_(canary).view(torch.float16) for _ in range(n)]
+        vc_ = [torch.zeros((H, cap, D), dtype=torch.int16, device=DEV).fill_(canary).view(torch.float16) for _ in range(n)]
+        status = torch.ones(1, dtype=torch.int32, device=DEV)
+        qkv.inject_layers(card, desc, [k[:, prefix:prefix + T] for k in kc_], [v[:, prefix:prefix + T] for v in vc_], lb,
+                          rope_base=rope[0] if rope else 0.0, rope_delta=rope[1] if rope else 0, status=status,
+                          keys_per_channel=True)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        wk = [np.full((H, cap, D), canary, np.uint16) for _ in range(n)]
+        wv = [np.full((H, cap, D), canary, np.uint16) for _ in range(n)]
+        inject_ref.inject_layers(host, rdesc, wk, wv, lb, prefix, rope, keys_per_channel=True)
+        for i in range(n):
+            assert np.array_equal(kc_[i].view(torch.int16).cpu().numpy().view(np.uint16), wk[i]), (lb, n, rope, i)
+            assert np.array_equal(vc_[i].view(torch.int16).cpu().numpy().view(np.uint16), wv[i]), (lb, n, rope, i)
