@@ -360,6 +360,12 @@ int qkv_inject_layers(const void* card_dev, uint64_t card_bytes, const qkv_desc_
  *             aligned; contents on entry and exit are unspecified.
  * When the header does not match, out / lse are left untouched (status_dev says so).
  * Asynchronous on `stream`.
+ *
+ * Several new tokens at once (a speculative window, a short suffix): every card token precedes
+ * all of them, so no mask is needed and a "query head" may just as well be a (token, head) pair.
+ * With S tokens and R = query heads per kv head, S * R <= 16, lay q out as
+ * [layers][kv_heads][S][R][128] and pass q_heads = kv_heads * S * R; out and lse come back in
+ * the same order.  The card is then read once for all S tokens.
  */
 int qkv_card_attend_workspace(const qkv_desc_t* expect, int32_t q_heads, uint64_t* bytes_out);
 int qkv_card_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect,

@@ -210,3 +210,32 @@ def test_benchmark_shape_8k():
     err_l = float(np.abs(lse.cpu().numpy() - want_lse).max())
     print("        max |do| %.3g (bound %.3g)   max |dlse| %.3g (bound %.3g)" % (err_o, tol_o, err_l, tol_l), flush=True)
     assert err_o <= tol_o and err_l <= tol_l
+
+
+def test_several_query_tokens_in_one_pass():
+    """Three new tokens x four query heads per kv head as twelve "heads": one pass over the card, each token's
+    slice against the oracle."""
+    L, H, R, S, T, D, G = 2, 2, 4, 3, 900, 128, 32
+    say("attend: %d query tokens in one pass" % S)
+    K, V = qkv_synth.make_kv(L, H, T, D, 801, "llama")
+    bits = qkv_synth.make_bits_uniform_choice(T, 802).numpy()
+    counts = ref.count_bits(bits).tolist()
+    rd = ref.make_desc(L, H, T, D, G)
+    card = ref.quantize_pack(rd, K.numpy().view(np.uint16), V.numpy().view(np.uint16), bits, counts)
+    desc = qkv.Desc.make(L, H, T, D, G)
+    q_tok = np.random.default_rng(803).standard_normal((S, L, H * R, D)).astype(np.float16)      # per token [L][Hq][D]
+    # [S][L][H][R][D] -> [L][H][S][R][D]
+    q_all = np.ascontiguousarray(q_tok.reshape(S, L, H, R, D).transpose(1, 2, 0, 3, 4)).reshape(L, H * S * R, D)
+    out = torch.empty((L, H * S * R, D), dtype=torch.float32, device=DEV)
+    lse = torch.empty((L, H * S * R), dtype=torch.float32, device=DEV)
+    status = torch.ones(1, dtype=torch.int32, device=DEV)
+    qkv.card_attend(torch.from_numpy(card).to(DEV), desc, torch.from_numpy(q_all).to(DEV), D ** -0.5, out, lse=lse, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    got_o = out.cpu().numpy().reshape(L, H, S, R, D)
+    got_l = lse.cpu().numpy().reshape(L, H, S, R)
+    for s_ in range(S):
+        want_o, want_l = attend_ref.card_attend(card, rd, q_tok[s_], D ** -0.5)
+        tol_o, tol_l = bounds(card, rd, q_tok[s_], D ** -0.5)
+        assert np.abs(got_o[:, :, s_].reshape(L, H * R, D) - want_o).max() <= tol_o
+        assert np.abs(got_l[:, :, s_].reshape(L, H * R) - want_l).max() <= tol_l
