@@ -55,6 +55,9 @@ __device__ inline uint32_t gain_key(float score, float per_bit) {
   return ~__float_as_uint(s * per_bit);
 }
 
+// KPT > 0: each thread keeps the scores of its KPT consecutive tokens in registers (needs T <= KPT * kThreads);
+// KPT == 0: any T, scores re-read on every sweep.
+template <int KPT>
 __global__ __launch_bounds__(kThreads) void greedy_kernel(const float* __restrict__ scores, uint32_t T,
                                                           uint32_t spare, uint8_t* __restrict__ bits,
                                                           unsigned long long* __restrict__ counts4) {
@@ -67,9 +70,23 @@ __global__ __launch_bounds__(kThreads) void greedy_kernel(const float* __restric
   const uint32_t lane = tid & 63u, wave = tid >> 6;
   const float per_bit[3] = {(float)(2.0 / 15.0), (float)(4.0 / 255.0), (float)(32.0 / 65535.0)};
 
-  const uint32_t per = (T + kThreads - 1) / kThreads;       // thread tid owns the tokens [t0, t1)
+  const uint32_t per = KPT > 0 ? (uint32_t)KPT : (T + kThreads - 1) / kThreads;   // thread tid owns the tokens [t0, t1)
   const uint32_t t0 = min(tid * per, T);
   const uint32_t t1 = min(t0 + per, T);
+  float mine[KPT > 0 ? KPT : 1];
+  if (KPT > 0) {
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) mine[i] = (t0 + i < t1) ? scores[t0 + i] : 0.0f;
+  }
+  // visits every owned token's score
+  auto for_each_score = [&](auto&& f) {
+    if (KPT > 0) {
+#pragma unroll
+      for (int i = 0; i < KPT; ++i) if (t0 + i < t1) f(mine[i], t0 + i);
+    } else {
+      for (uint32_t t = t0; t < t1; ++t) f(scores[t], t);
+    }
+  };
   // `spare` counts units of 2 bits; the upgrades weigh 1, 2, 4.  If all 7T fit, nothing is selected.
   const bool everything = spare >= 7u * T;
 
@@ -79,11 +96,10 @@ __global__ __launch_bounds__(kThreads) void greedy_kernel(const float* __restric
     for (uint32_t i = tid; i < 256 * kCopies; i += kThreads) wide[i] = 0;
     if (tid < 4) class_tot[tid] = 0;
     __syncthreads();
-    for (uint32_t t = t0; t < t1; ++t) {
-      const float s = scores[t];
+    for_each_score([&](float s, uint32_t) {
 #pragma unroll
       for (int l = 0; l < 3; ++l) atomicAdd(&wide[(gain_key(s, per_bit[l]) >> 24) * kCopies + (lane & 31u)], 1u << l);
-    }
+    });
     __syncthreads();
     if (tid < 256) {
       uint32_t sum = 0;
@@ -105,14 +121,13 @@ __global__ __launch_bounds__(kThreads) void greedy_kernel(const float* __restric
       if (tid < 256) hist[tid] = 0;
       __syncthreads();
       const uint32_t high_mask = 0xFFFFFFFFu << (shift + 8);
-      for (uint32_t t = t0; t < t1; ++t) {
-        const float s = scores[t];
+      for_each_score([&](float s, uint32_t) {
 #pragma unroll
         for (int l = 0; l < 3; ++l) {
           const uint32_t key = gain_key(s, per_bit[l]);
           if (((key ^ pre) & high_mask) == 0) atomicAdd(&hist[(key >> shift) & 255u], 1u << l);
         }
-      }
+      });
       __syncthreads();
       if (wave == 0) {
         uint32_t l = sel_left;
@@ -132,11 +147,10 @@ __global__ __launch_bounds__(kThreads) void greedy_kernel(const float* __restric
   uint32_t run[3] = {0, 0, 0}, quota[3] = {0, 0, 0};
   if (!everything) {
     uint32_t eq[3] = {0, 0, 0};
-    for (uint32_t t = t0; t < t1; ++t) {
-      const float s = scores[t];
+    for_each_score([&](float s, uint32_t) {
 #pragma unroll
       for (int l = 0; l < 3; ++l) eq[l] += (gain_key(s, per_bit[l]) == kstar);
-    }
+    });
 #pragma unroll
     for (int l = 0; l < 3; ++l) {
       const uint32_t inc = wave_inclusive_scan(eq[l]);
@@ -168,8 +182,7 @@ __global__ __launch_bounds__(kThreads) void greedy_kernel(const float* __restric
   }
 
   uint32_t cnt[4] = {0, 0, 0, 0};
-  for (uint32_t t = t0; t < t1; ++t) {
-    const float s = scores[t];
+  for_each_score([&](float s, uint32_t t) {
     bool taken[3];
 #pragma unroll
     for (int l = 0; l < 3; ++l) {
@@ -181,7 +194,7 @@ __global__ __launch_bounds__(kThreads) void greedy_kernel(const float* __restric
     const uint32_t c = taken[0] ? (taken[1] ? (taken[2] ? 3u : 2u) : 1u) : 0u;
     bits[t] = (uint8_t)(2u << c);
     cnt[0] += (c == 0); cnt[1] += (c == 1); cnt[2] += (c == 2); cnt[3] += (c == 3);
-  }
+  });
   if (counts4 != nullptr) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -204,7 +217,10 @@ hipError_t launch_controller(const float* features, uint32_t tokens, const qkv_c
 
 hipError_t launch_greedy(const float* scores, uint32_t tokens, uint32_t spare_units, uint8_t* bits,
                          unsigned long long* counts4, hipStream_t stream) {
-  hipLaunchKernelGGL(greedy_kernel, dim3(1), dim3(kThreads), 0, stream, scores, tokens, spare_units, bits, counts4);
+  if (tokens <= 8u * kThreads)
+    hipLaunchKernelGGL(greedy_kernel<8>, dim3(1), dim3(kThreads), 0, stream, scores, tokens, spare_units, bits, counts4);
+  else
+    hipLaunchKernelGGL(greedy_kernel<0>, dim3(1), dim3(kThreads), 0, stream, scores, tokens, spare_units, bits, counts4);
   return hipGetLastError();
 }
 
