@@ -340,6 +340,29 @@ int qkv_inject_layers(const void* card_dev, uint64_t card_bytes, const qkv_desc_
                       const qkv_inject_t* where, uint32_t* status_dev, void* stream);
 
 /*
+ * One hop of a multi-hop chain without the dense cache in between (paper Sec. 3.2, challenge 3:
+ * error accumulates as a cache is forwarded from agent to agent; Sec. 4.2: the card is what
+ * travels).  Builds, from an incoming card and new bit widths, exactly the card that
+ * qkv_quantize_pack would build from the cache qkv_unpack_dequant rebuilds - byte for byte -
+ * but moves only the two cards' bytes: every span is decoded and quantized again in registers.
+ *   card_in_dev, card_in_bytes: the incoming card (device, 256-byte aligned, per-token groups);
+ *               validated on the device like qkv_unpack_dequant does.
+ *   desc:       host; shape of both cards (must match the incoming header) and the identifiers
+ *               and position offset that go into the outgoing header.
+ *   bits_dev, counts: the new widths, as for qkv_quantize_pack.
+ *   card_out_dev, card_out_capacity: as for qkv_quantize_pack; must not overlap the incoming card.
+ *   status_dev: device uint32_t, may be NULL.  0, or QKV_STATUS_BAD_HEADER when the incoming
+ *               card was refused (the outgoing card then holds header and tables but no rows),
+ *               QKV_STATUS_BAD_ORDER or-ed in when a corrupt table entry of the incoming card was
+ *               skipped (its rows are then zeros).
+ * Asynchronous on `stream`; allocates nothing.
+ * Errors: as qkv_quantize_pack.
+ */
+int qkv_requantize(const void* card_in_dev, uint64_t card_in_bytes, const qkv_desc_t* desc,
+                   const uint8_t* bits_dev, const int64_t counts[4], void* card_out_dev,
+                   uint64_t card_out_capacity, uint32_t* status_dev, void* stream);
+
+/*
  * Decode-step attention of one new query token directly over a card, without rebuilding
  * the dense cache (paper Sec. 4.3: consuming a foreign quantized cache inside attention,
  * which the paper names as its long-term goal).  For every layer l and query head hq, with

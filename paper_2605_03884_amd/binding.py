@@ -117,6 +117,8 @@ def lib():
     L.qkv_quantize_pack_kc.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, i64p, vp, ctypes.c_uint64, vp]
     L.qkv_unpack_dequant_kc.restype = ctypes.c_int
     L.qkv_unpack_dequant_kc.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, vp, vp, vp]
+    L.qkv_requantize.restype = ctypes.c_int
+    L.qkv_requantize.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, i64p, vp, ctypes.c_uint64, vp, vp]
     L.qkv_unpack_dequant.restype = ctypes.c_int
     L.qkv_unpack_dequant.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, vp, vp, vp]
     L.qkv_card_attend_workspace.restype = ctypes.c_int
@@ -237,6 +239,17 @@ def quantize_pack_kc(desc, k, v, bits, counts, card, stream=None):
                                       _dev_ptr(card, torch.uint8, "card"), card.numel(), _stream(stream)),
            "qkv_quantize_pack_kc")
     return card
+
+
+def requantize(card_in, desc, bits, counts, card_out, status=None, card_in_nbytes=None, stream=None):
+    """The card that quantize_pack would build from unpack_dequant(card_in), at the new widths, card to card."""
+    n = card_in.numel() if card_in_nbytes is None else int(card_in_nbytes)
+    sp = ctypes.c_void_p(0) if status is None else _dev_ptr(status, None, "status")
+    _check(lib().qkv_requantize(_dev_ptr(card_in, torch.uint8, "card_in"), n, ctypes.byref(desc),
+                                _dev_ptr(bits, torch.uint8, "bits"), _counts(counts),
+                                _dev_ptr(card_out, torch.uint8, "card_out"), card_out.numel(), sp, _stream(stream)),
+           "qkv_requantize")
+    return card_out
 
 
 def card_plan(desc, bits, counts, card, stream=None):

@@ -298,6 +298,26 @@ int qkv_quantize_pack(const qkv_desc_t* desc, const void* k_dev, const void* v_d
   return QKV_OK;
 }
 
+int qkv_requantize(const void* card_in_dev, uint64_t card_in_bytes, const qkv_desc_t* desc, const uint8_t* bits_dev,
+                   const int64_t counts[4], void* card_out_dev, uint64_t card_out_capacity, uint32_t* status_dev,
+                   void* stream) {
+  if (!card_in_dev || !desc || !bits_dev || !counts || !card_out_dev) return QKV_ERR_NULL;
+  CardGeom g;
+  uint64_t n[4];
+  int rc = prepare_card(desc, counts, card_out_dev, card_out_capacity, g, n);
+  if (rc) return rc;
+  if (card_in_bytes < QKV_CARD_HEADER_BYTES) return QKV_ERR_CAPACITY;
+  if (reinterpret_cast<uintptr_t>(card_in_dev) % QKV_CARD_ALIGN != 0 || reinterpret_cast<uintptr_t>(status_dev) % 4 != 0)
+    return QKV_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  uint8_t* card = static_cast<uint8_t*>(card_out_dev);
+  rc = plan_card(desc, bits_dev, g, n, card, s);
+  if (rc) return rc;
+  if (launch_requant(static_cast<const uint8_t*>(card_in_dev), card_in_bytes, g, card, status_dev, s) != hipSuccess)
+    return QKV_ERR_HIP;
+  return QKV_OK;
+}
+
 namespace {
 // Shapes the per-channel key tiles are written for.
 int check_keys_per_channel(const qkv_desc_t* d) {

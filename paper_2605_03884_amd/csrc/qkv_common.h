@@ -140,6 +140,8 @@ hipError_t launch_inject(const uint8_t* card, uint64_t card_bytes, const CardGeo
                          uint32_t layer_count, void* const* k_layers, void* const* v_layers, uint64_t head_stride_bytes,
                          uint64_t token_stride_bytes, const float (*cos_sin)[2], bool keys_per_channel, uint32_t* status,
                          hipStream_t stream);
+hipError_t launch_requant(const uint8_t* card_in, uint64_t card_in_bytes, const CardGeom& out, uint8_t* card_out,
+                          uint32_t* status, hipStream_t stream);
 hipError_t launch_assign(const float* scores, uint32_t tokens, const uint32_t cuts[3], uint8_t* bits,
                          hipStream_t stream);
 void attend_plan(uint64_t tokens, uint32_t rep, uint64_t pairs, uint32_t* chunk, uint32_t* max_tasks);

@@ -1,0 +1,195 @@
+// requant.hip — one hop of a multi-hop chain without the dense cache in between (paper Sec. 3.2,
+// challenge 3: a cache is forwarded from agent to agent; Sec. 4.2: a card is what travels).
+//
+// An agent that forwards a card at new bit widths would otherwise rebuild the dense fp16 cache
+// (injection) and build the next card from it (card creation): 2 x (dense + card) bytes of traffic.
+// Here every span of 32 values is read from the incoming card, decoded with the injection kernel's
+// decoder, quantized with the card-creation kernel's quantizer and stored into the outgoing card; the
+// dense values only ever exist in registers.  The result is, byte for byte, the card that creation
+// would build from the injected cache.
+//
+// Work decomposition: the outgoing card's segments are walked as in card creation, a wave taking 128
+// spans at a time (64 lanes x 2 rounds).  A lane finds its span's token through the outgoing card's
+// order[] (written by the classification kernel just before, on the same stream) and the token's old
+// width and slot through the incoming card's tables.  Neighbouring rows of an outgoing tile may have
+// had different old widths, so the decoders run one after the other under lane masks; the work is
+// bound by instruction issue, not by memory, and needs no LDS.
+//
+// The incoming card is untrusted: header and offsets are rebuilt and checked on the device, table
+// entries are bounded before they are used.
+#include "qkv_common.h"
+#include "qkv_encode.h"
+
+namespace qkv {
+namespace {
+
+struct RequantArgs {
+  const uint8_t* card_in;
+  uint64_t card_in_bytes;
+  uint32_t layers, kv_heads, head_dim, group_size;
+  uint64_t tokens;
+  CardGeom out;                 // the outgoing card's geometry (host-known counts)
+  uint8_t* card_out;
+  uint32_t* status;             // may be null
+};
+
+__global__ void requant_status_kernel(RequantArgs a) {
+  CardGeom g;
+  const bool ok = card_geometry_from_header(a.card_in, a.card_in_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size,
+                                            a.tokens, g);
+  if (threadIdx.x == 0 && blockIdx.x == 0) *a.status = ok ? 0u : QKV_STATUS_BAD_HEADER;
+}
+
+// The 32 values (16 packed pairs) of span q of row (plane p, token t) of the incoming card; zeros and
+// `bad` when the card's tables point outside it.
+template <int G, bool KEEP>
+__device__ __forceinline__ void load_decoded_span(const uint8_t* card, const CardGeom& in, uint32_t p, uint32_t t, uint32_t q,
+                                         uint32_t spr_shift, uint32_t (&w)[16], uint32_t& bad) {
+  constexpr int GS = G / 32;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) w[i] = 0;
+  const uint32_t width = card[in.off_bits + t];
+  const uint32_t slot = reinterpret_cast<const uint32_t*>(card + in.off_slot)[t];
+  const int co = (width == 2) ? 0 : (width == 4) ? 1 : (width == 8) ? 2 : (width == 16) ? 3 : -1;
+  if (co < 0) { bad = 1; return; }
+  const uint32_t n_old = (co == 0) ? in.n[0] : (co == 1) ? in.n[1] : (co == 2) ? in.n[2] : in.n[3];
+  if (slot >= n_old) { bad = 1; return; }
+  const uint64_t gsp = (((uint64_t)p * n_old + slot) << spr_shift) + q;
+  if (co == 3) {
+    const u32x4* src = reinterpret_cast<const u32x4*>(card + in.off_fp16 + gsp * 64u);
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+      const u32x4 v = card_load<KEEP>(src + h);
+      w[4 * h] = v.x; w[4 * h + 1] = v.y; w[4 * h + 2] = v.z; w[4 * h + 3] = v.w;
+    }
+    return;
+  }
+  const uint64_t off_codes = (co == 0) ? in.off_codes[0] : (co == 1) ? in.off_codes[1] : in.off_codes[2];
+  const uint64_t off_meta = (co == 0) ? in.off_meta[0] : (co == 1) ? in.off_meta[1] : in.off_meta[2];
+  const uint32_t pair = card_load<KEEP>(reinterpret_cast<const uint32_t*>(card + off_meta) + gsp / GS);
+  const float s = half_bits_to_float(pair & 0xFFFFu);
+  const float z = half_bits_to_float(pair >> 16);
+  if (co == 0) {
+    const u32x2 v = card_load<KEEP>(reinterpret_cast<const u32x2*>(card + off_codes + gsp * 8u));
+    const uint32_t cw[2] = {v.x, v.y};
+    decode_span<2>(cw, s, z, w);
+  } else if (co == 1) {
+    const u32x4 v = card_load<KEEP>(reinterpret_cast<const u32x4*>(card + off_codes + gsp * 16u));
+    const uint32_t cw[4] = {v.x, v.y, v.z, v.w};
+    decode_span<4>(cw, s, z, w);
+  } else {
+    const u32x4* src = reinterpret_cast<const u32x4*>(card + off_codes + gsp * 32u);
+    const u32x4 v0 = card_load<KEEP>(src), v1 = card_load<KEEP>(src + 1);
+    const uint32_t cw[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+    decode_span<8>(cw, s, z, w);
+  }
+}
+
+// The spans of outgoing class C, 128 per wave and turn, dealt round-robin and continuing where the
+// previous class stopped.
+template <int C, int G, bool KEEP>
+__device__ __forceinline__ void requant_class(const RequantArgs& a, const CardGeom& in, uint32_t gw, uint32_t n_waves, uint32_t lane,
+                                     uint32_t& cum, uint32_t& bad) {
+  constexpr int GS = G / 32;
+  const CardGeom& out = a.out;
+  const uint32_t n_new = out.n[C];
+  if (n_new == 0) return;
+  const uint32_t spr_shift = out.lpr_shift - 2u;                       // log2(spans per row)
+  const uint64_t seg_spans = ((uint64_t)out.planes * n_new) << spr_shift;
+  const uint32_t tiles = (uint32_t)((seg_spans + 2u * kWaveSize - 1u) / (2u * kWaveSize));
+  const uint32_t* order_out = reinterpret_cast<const uint32_t*>(a.card_out + out.off_order) + out.base[C];
+  const uint32_t first = (gw + n_waves - cum) % n_waves;
+  for (uint32_t i = first; i < tiles; i += n_waves) {
+#pragma unroll 1
+    for (int round = 0; round < 2; ++round) {
+      const uint64_t gsp = (uint64_t)i * (2u * kWaveSize) + round * kWaveSize + lane;
+      const bool live = gsp < seg_spans;
+      uint32_t w[16];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) w[k] = 0;
+      if (live) {
+        const uint32_t r = (uint32_t)(gsp >> spr_shift);
+        const uint32_t q = (uint32_t)gsp & ((1u << spr_shift) - 1u);
+        const uint32_t p = r / n_new;
+        const uint32_t j = r - p * n_new;
+        const uint32_t t = order_out[j];
+        if (t < out.tokens) load_decoded_span<G, KEEP>(a.card_in, in, p, t, q, spr_shift, w, bad);
+        else bad = 1;
+      }
+      if constexpr (C == 3) {
+        if (live) {
+          u32x4* dst = reinterpret_cast<u32x4*>(a.card_out + out.off_fp16 + gsp * 64u);
+#pragma unroll
+          for (int h = 0; h < 4; ++h) card_store<KEEP>(dst + h, (u32x4){w[4 * h], w[4 * h + 1], w[4 * h + 2], w[4 * h + 3]});
+        }
+      } else {
+        constexpr int W = C == 0 ? 2 : C == 1 ? 4 : 8;
+        uint32_t codes[W];
+        const uint32_t pair = quantize_span<W, GS>(w, codes);        // every lane takes part: groups span lanes
+        if (live) {
+          uint8_t* dst = a.card_out + out.off_codes[C] + gsp * (4u * W);
+          if (W == 2) card_store<KEEP>(reinterpret_cast<u32x2*>(dst), (u32x2){codes[0], codes[1]});
+          if (W >= 4) card_store<KEEP>(reinterpret_cast<u32x4*>(dst), (u32x4){codes[0], codes[1], codes[2], codes[3]});
+          if (W == 8) card_store<KEEP>(reinterpret_cast<u32x4*>(dst + 16), (u32x4){codes[4], codes[5], codes[6], codes[7]});
+          if ((gsp & (GS - 1)) == 0)
+            card_store<KEEP>(reinterpret_cast<uint32_t*>(a.card_out + out.off_meta[C]) + gsp / GS, pair);
+        }
+      }
+    }
+  }
+  cum = (cum + tiles) % n_waves;
+}
+
+template <int G, bool KEEP>
+__global__ __launch_bounds__(kBlockThreads) void requant_kernel(RequantArgs a) {
+  CardGeom in;
+  if (!card_geometry_from_header(a.card_in, a.card_in_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, in))
+    return;                                   // uniform over the grid
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t gw = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  const uint32_t n_waves = gridDim.x * kWavesPerBlock;
+  uint32_t bad = 0, cum = 0;
+  requant_class<0, G, KEEP>(a, in, gw, n_waves, lane, cum, bad);
+  requant_class<1, G, KEEP>(a, in, gw, n_waves, lane, cum, bad);
+  requant_class<2, G, KEEP>(a, in, gw, n_waves, lane, cum, bad);
+  requant_class<3, G, KEEP>(a, in, gw, n_waves, lane, cum, bad);
+  if (bad && a.status) atomicOr(a.status, QKV_STATUS_BAD_ORDER);
+}
+
+}  // namespace
+
+hipError_t launch_requant(const uint8_t* card_in, uint64_t card_in_bytes, const CardGeom& out, uint8_t* card_out,
+                          uint32_t* status, hipStream_t stream) {
+  RequantArgs a;
+  a.card_in = card_in;
+  a.card_in_bytes = card_in_bytes;
+  a.layers = out.layers; a.kv_heads = out.kv_heads; a.head_dim = out.head_dim; a.group_size = out.group_size;
+  a.tokens = out.tokens;
+  a.out = out;
+  a.card_out = card_out;
+  a.status = status;
+  if (status) {
+    hipLaunchKernelGGL(requant_status_kernel, dim3(1), dim3(kWaveSize), 0, stream, a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  uint64_t tiles = 0;
+  for (int c = 0; c < 4; ++c) {
+    const uint64_t spans = ((uint64_t)out.planes * out.n[c]) << (out.lpr_shift - 2u);
+    tiles += (spans + 2u * kWaveSize - 1u) / (2u * kWaveSize);
+  }
+  if (tiles == 0) return hipSuccess;
+  const dim3 grid(grid_blocks(tiles)), block(kBlockThreads);
+  const bool keep = out.total <= kCacheResidentCardBytes && card_in_bytes <= kCacheResidentCardBytes;
+  switch (out.group_size * 2 + (keep ? 1 : 0)) {
+    case 65: hipLaunchKernelGGL((requant_kernel<32, true>), grid, block, 0, stream, a); break;
+    case 64: hipLaunchKernelGGL((requant_kernel<32, false>), grid, block, 0, stream, a); break;
+    case 129: hipLaunchKernelGGL((requant_kernel<64, true>), grid, block, 0, stream, a); break;
+    case 128: hipLaunchKernelGGL((requant_kernel<64, false>), grid, block, 0, stream, a); break;
+    case 257: hipLaunchKernelGGL((requant_kernel<128, true>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((requant_kernel<128, false>), grid, block, 0, stream, a); break;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace qkv

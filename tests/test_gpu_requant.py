@@ -1,0 +1,146 @@
+"""GPU parity of qkv_requantize (card to card, one hop of a chain) through the C ABI.  The oracle is the chain
+itself, written out: rebuild the dense cache from the incoming card, build the next card from it.  Bar:
+every byte of the outgoing card."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_03884_amd as qkv
+import qkv_synth
+from oracle import ref
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def oracle_hop(card_in, rd_in, rd_out, bits_new, counts_new):
+    k, v = ref.unpack_dequant(card_in, rd_in)
+    return ref.quantize_pack(rd_out, k, v, bits_new, counts_new)
+
+
+def run(L, H, T, D, G, bits_a, bits_b, seed, label):
+    say(label)
+    K, V = qkv_synth.make_kv(L, H, T, D, seed, "llama")
+    ca, cb = ref.count_bits(bits_a).tolist(), ref.count_bits(bits_b).tolist()
+    rd_a = ref.make_desc(L, H, T, D, G, 1, 2, 3)
+    rd_b = ref.make_desc(L, H, T, D, G, 7, 8, 9)
+    card_a = ref.quantize_pack(rd_a, K.numpy().view(np.uint16), V.numpy().view(np.uint16), bits_a, ca)
+    want = oracle_hop(card_a, rd_a, rd_b, bits_b, cb)
+    desc_b = qkv.Desc.make(L, H, T, D, G, model_id=7, sender_id=8, position_offset=9)
+    n = qkv.card_bytes(desc_b, cb)
+    out = torch.full((n + 256,), 0xA5, dtype=torch.uint8, device=DEV)
+    status = torch.full((1,), 0x7777, dtype=torch.int32, device=DEV)
+    qkv.requantize(torch.from_numpy(card_a).to(DEV), desc_b, torch.from_numpy(bits_b).to(DEV), cb, out[:n], status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    got = out.cpu().numpy()
+    assert np.all(got[n:] == 0xA5)
+    diff = np.flatnonzero(got[:n] != want)
+    assert diff.size == 0, (label, "differs at %d bytes, first %d" % (diff.size, int(diff[0])))
+    return out[:n], desc_b
+
+
+@pytest.mark.parametrize("D,G", [(128, 32), (128, 64), (128, 128), (64, 32), (64, 64), (256, 32), (256, 128)])
+def test_mixed_to_mixed(D, G):
+    T = 333
+    a = qkv_synth.make_bits_uniform_choice(T, 11).numpy()
+    b = qkv_synth.make_bits_uniform_choice(T, 12).numpy()
+    run(2, 3, T, D, G, a, b, 20 + D + G, "requant mixed D=%d G=%d" % (D, G))
+
+
+@pytest.mark.parametrize("wa", [2, 4, 8, 16])
+@pytest.mark.parametrize("wb", [2, 4, 8, 16])
+def test_uniform_to_uniform(wa, wb):
+    T = 200
+    run(1, 2, T, 128, 32, np.full(T, wa, np.uint8), np.full(T, wb, np.uint8), 40 + wa + wb, "requant %d -> %d bits" % (wa, wb))
+
+
+def test_budget_chain_of_four_hops():
+    """The multi-hop recipe at small size: budgets 6, 4, 3, 2 with fresh scores per hop; the card of every hop
+    must equal the oracle's chain through the dense cache."""
+    L, H, T, D, G = 2, 2, 2000, 128, 32
+    say("requant chain of four hops")
+    K, V = qkv_synth.make_kv(L, H, T, D, 61, "llama")
+    rd = ref.make_desc(L, H, T, D, G)
+    desc = qkv.Desc.make(L, H, T, D, G)
+    bits0, _ = ref.assign_bits(qkv_synth.make_scores(T, 62).numpy(), 6.0)
+    c0 = ref.count_bits(bits0).tolist()
+    card_h = ref.quantize_pack(rd, K.numpy().view(np.uint16), V.numpy().view(np.uint16), bits0, c0)
+    card_d = torch.from_numpy(card_h).to(DEV)
+    for hop, budget in enumerate((4.0, 3.0, 2.0)):
+        bits, _ = ref.assign_bits(qkv_synth.make_scores(T, 63 + hop).numpy(), budget)
+        c = ref.count_bits(bits).tolist()
+        card_h = oracle_hop(card_h, rd, rd, bits, c)
+        nxt = torch.empty(qkv.card_bytes(desc, c), dtype=torch.uint8, device=DEV)
+        qkv.requantize(card_d, desc, torch.from_numpy(bits).to(DEV), c, nxt)
+        torch.cuda.synchronize()
+        assert np.array_equal(nxt.cpu().numpy(), card_h), hop
+        card_d = nxt
+
+
+def test_random_shapes():
+    rng = np.random.default_rng(5)
+    for case in range(16):
+        D = int(rng.choice([64, 128, 256]))
+        G = int(rng.choice([g for g in (32, 64, 128) if g <= D]))
+        L, H, T = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.integers(1, 600))
+        a = qkv_synth.make_bits_uniform_choice(T, 700 + case).numpy()
+        b, _ = ref.assign_bits(qkv_synth.make_scores(T, 720 + case).numpy(), float(rng.choice([2.0, 2.7, 4.0, 8.0, 16.0])))
+        run(L, H, T, D, G, a, b, 740 + case, "requant random %d: L=%d H=%d T=%d D=%d G=%d" % (case, L, H, T, D, G))
+
+
+def test_refused_and_corrupt_incoming_cards():
+    say("requant corrupt incoming cards")
+    T = 128
+    a = qkv_synth.make_bits_uniform_choice(T, 81).numpy()
+    out, desc = run(1, 2, T, 128, 32, a, a, 82, "requant base for corruption")
+    K, V = qkv_synth.make_kv(1, 2, T, 128, 82, "llama")
+    ca = ref.count_bits(a).tolist()
+    rd = ref.make_desc(1, 2, T, 128, 32, 1, 2, 3)
+    card_a = torch.from_numpy(ref.quantize_pack(rd, K.numpy().view(np.uint16), V.numpy().view(np.uint16), a, ca)).to(DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    bad = card_a.clone()
+    bad[3] = 0
+    dst = torch.full((out.numel(),), 0x5A, dtype=torch.uint8, device=DEV)
+    qkv.requantize(bad, desc, torch.from_numpy(a).to(DEV), ca, dst, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == qkv.STATUS_BAD_HEADER
+    off = ref.card_offsets(rd, ca)
+    # slot entries out of range: flagged, no access outside the card (rows come out as zeros)
+    bad = card_a.clone()
+    bad[off["slot"]:off["slot"] + 4 * T].view(torch.int32)[5] = 1 << 30
+    status.zero_()
+    qkv.requantize(bad, desc, torch.from_numpy(a).to(DEV), ca, dst, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == qkv.STATUS_BAD_ORDER
+    # a card with per-channel keys is not an incoming card for this call
+    b4 = np.full(T, 4, np.uint8)
+    kc = torch.empty(qkv.card_bytes(desc, [0, T, 0, 0]), dtype=torch.uint8, device=DEV)
+    qkv.quantize_pack_kc(desc, K.to(DEV), V.to(DEV), torch.from_numpy(b4).to(DEV), [0, T, 0, 0], kc)
+    status.zero_()
+    qkv.requantize(kc, desc, torch.from_numpy(a).to(DEV), ca, dst, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == qkv.STATUS_BAD_HEADER
+
+
+def test_requantize_host_errors():
+    L = qkv.lib()
+    card = torch.zeros(1 << 16, dtype=torch.uint8, device=DEV)
+    out = torch.zeros(1 << 20, dtype=torch.uint8, device=DEV)
+    bits = torch.full((64,), 4, dtype=torch.uint8, device=DEV)
+    d = qkv.Desc.make(1, 1, 64, 128, 32)
+    c = (ctypes.c_int64 * 4)(0, 64, 0, 0)
+    assert L.qkv_requantize(card.data_ptr(), card.numel(), ctypes.byref(d), bits.data_ptr(), c, out.data_ptr(), out.numel(), None, None) == 0
+    assert L.qkv_requantize(None, card.numel(), ctypes.byref(d), bits.data_ptr(), c, out.data_ptr(), out.numel(), None, None) == -1
+    assert L.qkv_requantize(card.data_ptr(), 100, ctypes.byref(d), bits.data_ptr(), c, out.data_ptr(), out.numel(), None, None) == -5
+    assert L.qkv_requantize(card.data_ptr(), card.numel(), ctypes.byref(d), bits.data_ptr(), c, out.data_ptr(), 1000, None, None) == -5
+    assert L.qkv_requantize(card.data_ptr() + 16, card.numel() - 16, ctypes.byref(d), bits.data_ptr(), c, out.data_ptr(), out.numel(), None, None) == -6
+    c2 = (ctypes.c_int64 * 4)(0, 63, 0, 0)
+    assert L.qkv_requantize(card.data_ptr(), card.numel(), ctypes.byref(d), bits.data_ptr(), c2, out.data_ptr(), out.numel(), None, None) == -7
+    torch.cuda.synchronize()
