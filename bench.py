@@ -104,6 +104,7 @@ def hop_report(qkv, cfg, K, V, desc, dev):
     src_k, src_v = K, V
     out = []
     k_out, v_out = torch.empty_like(K), torch.empty_like(V)
+    prev_card = None
 
     def snr_db(ref_t, got_t):
         num = den = 0.0
@@ -127,7 +128,19 @@ def hop_report(qkv, cfg, K, V, desc, dev):
             torch.cuda.synchronize()
         moved = K.numel() * 4 + card.numel()
         pack_ms, unpack_ms = ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])
-        out.append({"hop": hop + 1, "budget": budget, "counts_2_4_8_16": counts, "card_bytes": card.numel(),
+        requant = None
+        if prev_card is not None:                       # the same hop card to card, without the dense cache
+            direct = torch.empty_like(card)
+            for rep in range(3):
+                ev[0].record()
+                qkv.requantize(prev_card, desc, bits, counts, direct)
+                ev[1].record()
+                torch.cuda.synchronize()
+            requant = {"ms": round(ev[0].elapsed_time(ev[1]), 4), "equals_chain_card": bool(torch.equal(direct, card)),
+                       "chain_ms": round(prev_unpack_ms + pack_ms, 4)}
+            del direct
+        prev_card, prev_unpack_ms = card, unpack_ms
+        out.append({"hop": hop + 1, "budget": budget, "counts_2_4_8_16": counts, "card_bytes": card.numel(), "requantize": requant,
                     "quantize_pack_ms": round(pack_ms, 4), "unpack_dequant_ms": round(unpack_ms, 4),
                     "pct_hbm_peak": [round(100 * moved / (pack_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 1),
                                      round(100 * moved / (unpack_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 1)],
@@ -136,7 +149,6 @@ def hop_report(qkv, cfg, K, V, desc, dev):
             src_k, src_v = torch.empty_like(K), torch.empty_like(V)
         src_k.copy_(k_out)
         src_v.copy_(v_out)
-        del card
     return out
 
 
@@ -348,6 +360,31 @@ def main():
                   "frac_hbm_peak_realigned": round(moved / (rope_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del per_layer, kls, vls
 
+    # forwarding the card at a lower budget, card to card (one hop of a chain), against the chain it replaces
+    requant = None
+    if scores is not None and not kc:
+        b2, c2 = qkv.assign_bits(qkv_synth.make_scores(T, cfg["data_seed"] + 31, dev), max(2.0, budget - 0.5))
+        nxt = torch.empty(qkv.card_bytes(desc, c2), dtype=torch.uint8, device=dev)
+        nxt2 = torch.empty_like(nxt)
+        n_rq = max(10, args.steps // 4)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        rq_ms = chain_ms = 0.0
+        for it in range(3 + n_rq):
+            ev[0].record()
+            qkv.requantize(card, desc, b2, c2, nxt)
+            ev[1].record()
+            qkv.unpack_dequant(card, desc, K_out, V_out)
+            qkv.quantize_pack(desc, K_out, V_out, b2, c2, nxt2)
+            ev[2].record()
+            torch.cuda.synchronize()
+            if it >= 3:
+                rq_ms += ev[0].elapsed_time(ev[1]) / n_rq
+                chain_ms += ev[1].elapsed_time(ev[2]) / n_rq
+        requant = {"call": "qkv_requantize", "to_budget": max(2.0, budget - 0.5), "ms": round(rq_ms, 4),
+                   "chain_unpack_then_pack_ms": round(chain_ms, 4), "equal": bool(torch.equal(nxt, nxt2)),
+                   "card_bytes_in_out": [card_bytes, nxt.numel()]}
+        del nxt, nxt2
+
     # the controller in front of the handoff: features -> scores -> widths (objective-greedy), timed on its own
     feats = qkv_synth.make_features(T, cfg["data_seed"] + 23, dev)
     params = qkv.Controller.make(*[a.cpu() for a in qkv_synth.make_controller(cfg["data_seed"] + 24)])
@@ -418,6 +455,7 @@ def main():
         "card_attend": attend,
         "controller": controller,
         "inject_layers": inject,
+        "requantize": requant,
     }
     if not args.no_cpu:
         layers = args.cpu_layers if args.cpu_layers > 0 else (L * 8192) // max(T, 8192)

@@ -40,49 +40,54 @@ __global__ void requant_status_kernel(RequantArgs a) {
   if (threadIdx.x == 0 && blockIdx.x == 0) *a.status = ok ? 0u : QKV_STATUS_BAD_HEADER;
 }
 
-// The 32 values (16 packed pairs) of span q of row (plane p, token t) of the incoming card; zeros and
-// `bad` when the card's tables point outside it.
-template <int G, bool KEEP>
-__device__ __forceinline__ void load_decoded_span(const uint8_t* card, const CardGeom& in, uint32_t p, uint32_t t, uint32_t q,
-                                         uint32_t spr_shift, uint32_t (&w)[16], uint32_t& bad) {
+// The 32 values (16 packed pairs) of span q of the row (plane p, slot) of old class CO of the incoming card.
+// One instance per old class, so that every geometry field is picked at compile time.
+template <int CO, int G, bool KEEP>
+__device__ __forceinline__ void decode_old_class(const uint8_t* card, const CardGeom& in, uint32_t p, uint32_t slot,
+                                                 uint32_t q, uint32_t spr_shift, uint32_t (&w)[16], uint32_t& bad) {
   constexpr int GS = G / 32;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) w[i] = 0;
-  const uint32_t width = card[in.off_bits + t];
-  const uint32_t slot = reinterpret_cast<const uint32_t*>(card + in.off_slot)[t];
-  const int co = (width == 2) ? 0 : (width == 4) ? 1 : (width == 8) ? 2 : (width == 16) ? 3 : -1;
-  if (co < 0) { bad = 1; return; }
-  const uint32_t n_old = (co == 0) ? in.n[0] : (co == 1) ? in.n[1] : (co == 2) ? in.n[2] : in.n[3];
+  const uint32_t n_old = in.n[CO];
   if (slot >= n_old) { bad = 1; return; }
   const uint64_t gsp = (((uint64_t)p * n_old + slot) << spr_shift) + q;
-  if (co == 3) {
+  if constexpr (CO == 3) {
     const u32x4* src = reinterpret_cast<const u32x4*>(card + in.off_fp16 + gsp * 64u);
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
       const u32x4 v = card_load<KEEP>(src + h);
       w[4 * h] = v.x; w[4 * h + 1] = v.y; w[4 * h + 2] = v.z; w[4 * h + 3] = v.w;
     }
-    return;
-  }
-  const uint64_t off_codes = (co == 0) ? in.off_codes[0] : (co == 1) ? in.off_codes[1] : in.off_codes[2];
-  const uint64_t off_meta = (co == 0) ? in.off_meta[0] : (co == 1) ? in.off_meta[1] : in.off_meta[2];
-  const uint32_t pair = card_load<KEEP>(reinterpret_cast<const uint32_t*>(card + off_meta) + gsp / GS);
-  const float s = half_bits_to_float(pair & 0xFFFFu);
-  const float z = half_bits_to_float(pair >> 16);
-  if (co == 0) {
-    const u32x2 v = card_load<KEEP>(reinterpret_cast<const u32x2*>(card + off_codes + gsp * 8u));
-    const uint32_t cw[2] = {v.x, v.y};
-    decode_span<2>(cw, s, z, w);
-  } else if (co == 1) {
-    const u32x4 v = card_load<KEEP>(reinterpret_cast<const u32x4*>(card + off_codes + gsp * 16u));
-    const uint32_t cw[4] = {v.x, v.y, v.z, v.w};
-    decode_span<4>(cw, s, z, w);
   } else {
-    const u32x4* src = reinterpret_cast<const u32x4*>(card + off_codes + gsp * 32u);
-    const u32x4 v0 = card_load<KEEP>(src), v1 = card_load<KEEP>(src + 1);
-    const uint32_t cw[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-    decode_span<8>(cw, s, z, w);
+    constexpr int W = CO == 0 ? 2 : CO == 1 ? 4 : 8;
+    const uint32_t pair = card_load<KEEP>(reinterpret_cast<const uint32_t*>(card + in.off_meta[CO]) + gsp / GS);
+    const float s = half_bits_to_float(pair & 0xFFFFu);
+    const float z = half_bits_to_float(pair >> 16);
+    const uint8_t* src = card + in.off_codes[CO] + gsp * (4u * W);
+    uint32_t cw[W];
+    if constexpr (W == 2) {
+      const u32x2 v = card_load<KEEP>(reinterpret_cast<const u32x2*>(src));
+      cw[0] = v.x; cw[1] = v.y;
+    } else {
+#pragma unroll
+      for (int h = 0; h < W / 4; ++h) {
+        const u32x4 v = card_load<KEEP>(reinterpret_cast<const u32x4*>(src) + h);
+        cw[4 * h] = v.x; cw[4 * h + 1] = v.y; cw[4 * h + 2] = v.z; cw[4 * h + 3] = v.w;
+      }
+    }
+    decode_span<W>(cw, s, z, w);
   }
+}
+
+// Span q of the row (plane p, old width, old slot) of the incoming card; zeros and `bad` when the card's
+// tables point outside it.  Lanes of a wave may take different branches.
+template <int G, bool KEEP>
+__device__ __forceinline__ void load_decoded_span(const uint8_t* card, const CardGeom& in, uint32_t p, uint32_t width,
+                                                  uint32_t slot, uint32_t q, uint32_t spr_shift, uint32_t (&w)[16],
+                                                  uint32_t& bad) {
+  if (width == 2) decode_old_class<0, G, KEEP>(card, in, p, slot, q, spr_shift, w, bad);
+  else if (width == 4) decode_old_class<1, G, KEEP>(card, in, p, slot, q, spr_shift, w, bad);
+  else if (width == 8) decode_old_class<2, G, KEEP>(card, in, p, slot, q, spr_shift, w, bad);
+  else if (width == 16) decode_old_class<3, G, KEEP>(card, in, p, slot, q, spr_shift, w, bad);
+  else bad = 1;
 }
 
 // The spans of outgoing class C, 128 per wave and turn, dealt round-robin and continuing where the
@@ -100,6 +105,23 @@ __device__ __forceinline__ void requant_class(const RequantArgs& a, const CardGe
   const uint32_t* order_out = reinterpret_cast<const uint32_t*>(a.card_out + out.off_order) + out.base[C];
   const uint32_t first = (gw + n_waves - cum) % n_waves;
   for (uint32_t i = first; i < tiles; i += n_waves) {
+    // both rounds' table look-ups first (order[] of the outgoing card, then width and slot in the incoming
+    // one: two dependent loads), so that their latencies overlap
+    uint32_t tok[2], width[2], slot[2];
+#pragma unroll
+    for (int round = 0; round < 2; ++round) {
+      const uint64_t gsp = (uint64_t)i * (2u * kWaveSize) + round * kWaveSize + lane;
+      tok[round] = 0xFFFFFFFFu; width[round] = 0; slot[round] = 0;
+      if (gsp < seg_spans) {
+        const uint32_t r = (uint32_t)(gsp >> spr_shift);
+        const uint32_t t = order_out[r % n_new];
+        tok[round] = t;
+        if (t < out.tokens) {
+          width[round] = a.card_in[in.off_bits + t];
+          slot[round] = reinterpret_cast<const uint32_t*>(a.card_in + in.off_slot)[t];
+        }
+      }
+    }
 #pragma unroll 1
     for (int round = 0; round < 2; ++round) {
       const uint64_t gsp = (uint64_t)i * (2u * kWaveSize) + round * kWaveSize + lane;
@@ -111,9 +133,10 @@ __device__ __forceinline__ void requant_class(const RequantArgs& a, const CardGe
         const uint32_t r = (uint32_t)(gsp >> spr_shift);
         const uint32_t q = (uint32_t)gsp & ((1u << spr_shift) - 1u);
         const uint32_t p = r / n_new;
-        const uint32_t j = r - p * n_new;
-        const uint32_t t = order_out[j];
-        if (t < out.tokens) load_decoded_span<G, KEEP>(a.card_in, in, p, t, q, spr_shift, w, bad);
+        const uint32_t tk = round == 0 ? tok[0] : tok[1];
+        if (tk < out.tokens)
+          load_decoded_span<G, KEEP>(a.card_in, in, p, round == 0 ? width[0] : width[1], round == 0 ? slot[0] : slot[1], q,
+                                     spr_shift, w, bad);
         else bad = 1;
       }
       if constexpr (C == 3) {
