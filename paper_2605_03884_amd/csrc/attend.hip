@@ -151,35 +151,9 @@ __device__ inline void decode_fetched(const SpanData<W, G>& d, uint32_t (&out)[1
   }
 }
 
-// 2-bit spans decoded by selection instead of arithmetic: a group has only four decoded values
-// x_k = fp16(fma(k, scale, zero)), computed once per span; a table in LDS, indexed by a byte of
-// four codes, holds the two byte selectors that pick (x_c0, x_c1) and (x_c2, x_c3) out of the
-// eight bytes {x_0 .. x_3}.  About one vector instruction per value instead of three.
-__device__ inline void build_select_table(u32x2* table, uint32_t lane) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t b = lane * 4u + i;
-    const uint32_t c0 = b & 3u, c1 = (b >> 2) & 3u, c2 = (b >> 4) & 3u, c3 = b >> 6;
-    table[b] = (u32x2){0x01000100u + 2u * (c0 * 0x0101u + c1 * 0x01010000u),
-                       0x01000100u + 2u * (c2 * 0x0101u + c3 * 0x01010000u)};
-  }
-}
-
 template <int G>
 __device__ inline void decode_fetched_select(const SpanData<2, G>& d, const u32x2* table, uint32_t (&out)[16]) {
-  const float s = half_bits_to_float(d.pair & 0xFFFFu);
-  const float z = half_bits_to_float(d.pair >> 16);
-  const uint32_t x01 = decode_pair(0.0f, 1.0f, s, z);
-  const uint32_t x23 = decode_pair(2.0f, 3.0f, s, z);
-#pragma unroll
-  for (int w = 0; w < 2; ++w) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const u32x2 sel = table[(d.cw[w] >> (8 * j)) & 0xFFu];
-      out[8 * w + 2 * j] = __builtin_amdgcn_perm(x23, x01, sel.x);
-      out[8 * w + 2 * j + 1] = __builtin_amdgcn_perm(x23, x01, sel.y);
-    }
-  }
+  decode_span2_select(d.cw, half_bits_to_float(d.pair & 0xFFFFu), half_bits_to_float(d.pair >> 16), table, out);
 }
 
 // ---- value pass helpers -----------------------------------------------------------------------

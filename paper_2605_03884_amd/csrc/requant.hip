@@ -13,7 +13,7 @@
 // order[] (written by the classification kernel just before, on the same stream) and the token's old
 // width and slot through the incoming card's tables.  Neighbouring rows of an outgoing tile may have
 // had different old widths, so the decoders run one after the other under lane masks; the work is
-// bound by instruction issue, not by memory, and needs no LDS.
+// bound by instruction issue, not by memory.  The only LDS is the selector table of the 2-bit decoder.
 //
 // The incoming card is untrusted: header and offsets are rebuilt and checked on the device, table
 // entries are bounded before they are used.
@@ -44,7 +44,8 @@ __global__ void requant_status_kernel(RequantArgs a) {
 // One instance per old class, so that every geometry field is picked at compile time.
 template <int CO, int G, bool KEEP>
 __device__ __forceinline__ void decode_old_class(const uint8_t* card, const CardGeom& in, uint32_t p, uint32_t slot,
-                                                 uint32_t q, uint32_t spr_shift, uint32_t (&w)[16], uint32_t& bad) {
+                                                 uint32_t q, uint32_t spr_shift, const u32x2* table, uint32_t (&w)[16],
+                                                 uint32_t& bad) {
   constexpr int GS = G / 32;
   const uint32_t n_old = in.n[CO];
   if (slot >= n_old) { bad = 1; return; }
@@ -73,7 +74,8 @@ __device__ __forceinline__ void decode_old_class(const uint8_t* card, const Card
         cw[4 * h] = v.x; cw[4 * h + 1] = v.y; cw[4 * h + 2] = v.z; cw[4 * h + 3] = v.w;
       }
     }
-    decode_span<W>(cw, s, z, w);
+    if constexpr (W == 2) decode_span2_select(cw, s, z, table, w);      // most spans at low budgets: by selection
+    else decode_span<W>(cw, s, z, w);
   }
 }
 
@@ -81,12 +83,12 @@ __device__ __forceinline__ void decode_old_class(const uint8_t* card, const Card
 // tables point outside it.  Lanes of a wave may take different branches.
 template <int G, bool KEEP>
 __device__ __forceinline__ void load_decoded_span(const uint8_t* card, const CardGeom& in, uint32_t p, uint32_t width,
-                                                  uint32_t slot, uint32_t q, uint32_t spr_shift, uint32_t (&w)[16],
-                                                  uint32_t& bad) {
-  if (width == 2) decode_old_class<0, G, KEEP>(card, in, p, slot, q, spr_shift, w, bad);
-  else if (width == 4) decode_old_class<1, G, KEEP>(card, in, p, slot, q, spr_shift, w, bad);
-  else if (width == 8) decode_old_class<2, G, KEEP>(card, in, p, slot, q, spr_shift, w, bad);
-  else if (width == 16) decode_old_class<3, G, KEEP>(card, in, p, slot, q, spr_shift, w, bad);
+                                                  uint32_t slot, uint32_t q, uint32_t spr_shift, const u32x2* table,
+                                                  uint32_t (&w)[16], uint32_t& bad) {
+  if (width == 2) decode_old_class<0, G, KEEP>(card, in, p, slot, q, spr_shift, table, w, bad);
+  else if (width == 4) decode_old_class<1, G, KEEP>(card, in, p, slot, q, spr_shift, table, w, bad);
+  else if (width == 8) decode_old_class<2, G, KEEP>(card, in, p, slot, q, spr_shift, table, w, bad);
+  else if (width == 16) decode_old_class<3, G, KEEP>(card, in, p, slot, q, spr_shift, table, w, bad);
   else bad = 1;
 }
 
@@ -94,7 +96,7 @@ __device__ __forceinline__ void load_decoded_span(const uint8_t* card, const Car
 // previous class stopped.
 template <int C, int G, bool KEEP>
 __device__ __forceinline__ void requant_class(const RequantArgs& a, const CardGeom& in, uint32_t gw, uint32_t n_waves, uint32_t lane,
-                                     uint32_t& cum, uint32_t& bad) {
+                                     const u32x2* table, uint32_t& cum, uint32_t& bad) {
   constexpr int GS = G / 32;
   const CardGeom& out = a.out;
   const uint32_t n_new = out.n[C];
@@ -105,6 +107,13 @@ __device__ __forceinline__ void requant_class(const RequantArgs& a, const CardGe
   const uint32_t* order_out = reinterpret_cast<const uint32_t*>(a.card_out + out.off_order) + out.base[C];
   const uint32_t first = (gw + n_waves - cum) % n_waves;
   for (uint32_t i = first; i < tiles; i += n_waves) {
+    // plane of a row of this turn without a division per lane: one division for the turn's first row (the same
+    // in every lane), then at most one plane boundary inside the turn's <= 64 rows when the class has that many
+    const uint32_t row_first = (uint32_t)(((uint64_t)i * (2u * kWaveSize)) >> spr_shift);
+    const uint32_t plane_first = row_first / n_new;
+    const uint32_t next_plane_row = (plane_first + 1u) * n_new;
+    const bool few = n_new < 2u * kWaveSize;
+    auto plane_of = [&](uint32_t r) -> uint32_t { return few ? r / n_new : plane_first + (r >= next_plane_row ? 1u : 0u); };
     // both rounds' table look-ups first (order[] of the outgoing card, then width and slot in the incoming
     // one: two dependent loads), so that their latencies overlap
     uint32_t tok[2], width[2], slot[2];
@@ -114,7 +123,7 @@ __device__ __forceinline__ void requant_class(const RequantArgs& a, const CardGe
       tok[round] = 0xFFFFFFFFu; width[round] = 0; slot[round] = 0;
       if (gsp < seg_spans) {
         const uint32_t r = (uint32_t)(gsp >> spr_shift);
-        const uint32_t t = order_out[r % n_new];
+        const uint32_t t = order_out[r - plane_of(r) * n_new];
         tok[round] = t;
         if (t < out.tokens) {
           width[round] = a.card_in[in.off_bits + t];
@@ -132,11 +141,11 @@ __device__ __forceinline__ void requant_class(const RequantArgs& a, const CardGe
       if (live) {
         const uint32_t r = (uint32_t)(gsp >> spr_shift);
         const uint32_t q = (uint32_t)gsp & ((1u << spr_shift) - 1u);
-        const uint32_t p = r / n_new;
+        const uint32_t p = plane_of(r);
         const uint32_t tk = round == 0 ? tok[0] : tok[1];
         if (tk < out.tokens)
           load_decoded_span<G, KEEP>(a.card_in, in, p, round == 0 ? width[0] : width[1], round == 0 ? slot[0] : slot[1], q,
-                                     spr_shift, w, bad);
+                                     spr_shift, table, w, bad);
         else bad = 1;
       }
       if constexpr (C == 3) {
@@ -165,17 +174,21 @@ __device__ __forceinline__ void requant_class(const RequantArgs& a, const CardGe
 
 template <int G, bool KEEP>
 __global__ __launch_bounds__(kBlockThreads) void requant_kernel(RequantArgs a) {
+  __shared__ u32x2 tables[kWavesPerBlock][256];      // selector tables of the 2-bit decoder
   CardGeom in;
   if (!card_geometry_from_header(a.card_in, a.card_in_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size, a.tokens, in))
     return;                                   // uniform over the grid
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t gw = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  const uint32_t wave = threadIdx.x >> 6;
+  const uint32_t gw = blockIdx.x * kWavesPerBlock + wave;
   const uint32_t n_waves = gridDim.x * kWavesPerBlock;
+  build_select_table(tables[wave], lane);      // each wave its own copy: no barrier, fewer bank conflicts
+  const u32x2* table = tables[wave];
   uint32_t bad = 0, cum = 0;
-  requant_class<0, G, KEEP>(a, in, gw, n_waves, lane, cum, bad);
-  requant_class<1, G, KEEP>(a, in, gw, n_waves, lane, cum, bad);
-  requant_class<2, G, KEEP>(a, in, gw, n_waves, lane, cum, bad);
-  requant_class<3, G, KEEP>(a, in, gw, n_waves, lane, cum, bad);
+  requant_class<0, G, KEEP>(a, in, gw, n_waves, lane, table, cum, bad);
+  requant_class<1, G, KEEP>(a, in, gw, n_waves, lane, table, cum, bad);
+  requant_class<2, G, KEEP>(a, in, gw, n_waves, lane, table, cum, bad);
+  requant_class<3, G, KEEP>(a, in, gw, n_waves, lane, table, cum, bad);
   if (bad && a.status) atomicOr(a.status, QKV_STATUS_BAD_ORDER);
 }
 
