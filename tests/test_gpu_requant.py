@@ -144,3 +144,87 @@ def test_requantize_host_errors():
     c2 = (ctypes.c_int64 * 4)(0, 63, 0, 0)
     assert L.qkv_requantize(card.data_ptr(), card.numel(), ctypes.byref(d), bits.data_ptr(), c2, out.data_ptr(), out.numel(), None, None) == -7
     torch.cuda.synchronize()
+
+
+def test_receiver_side_calls_replay_from_a_captured_graph():
+    """Controller scores, rank-quantile widths, card creation, requantization to a lower budget, layer-wise
+    injection with realignment and attention over the card, captured into one graph; every replay, with eager
+    work and new inputs in between, must reproduce the eager results of the same inputs."""
+    from oracle import inject_ref
+    say("graph replay of controller + pack + requantize + inject + attend")
+    L, H, T, D, G, R = 2, 2, 640, 128, 32, 4
+    desc = qkv.Desc.make(L, H, T, D, G)
+    rd = ref.make_desc(L, H, T, D, G)
+    w1, b1, w2 = [a.numpy() for a in qkv_synth.make_controller(5)]
+    params = qkv.Controller.make(w1, b1, w2)
+    feats = torch.empty((T, 6), dtype=torch.float32, device=DEV)
+    scores = torch.empty(T, dtype=torch.float32, device=DEV)
+    bits = torch.empty(T, dtype=torch.uint8, device=DEV)
+    bits2 = torch.empty(T, dtype=torch.uint8, device=DEV)
+    c1, c2 = qkv.budget_counts(T, 5.0), qkv.budget_counts(T, 3.0)
+    K = torch.empty((L, H, T, D), dtype=torch.float16, device=DEV)
+    V = torch.empty_like(K)
+    card = torch.empty(qkv.card_bytes(desc, c1), dtype=torch.uint8, device=DEV)
+    card2 = torch.empty(qkv.card_bytes(desc, c2), dtype=torch.uint8, device=DEV)
+    kl = [torch.empty((H, T + 8, D), dtype=torch.float16, device=DEV) for _ in range(L)]
+    vl = [torch.empty((H, T + 8, D), dtype=torch.float16, device=DEV) for _ in range(L)]
+    q = torch.empty((L, H * R, D), dtype=torch.float16, device=DEV)
+    out = torch.empty((L, H * R, D), dtype=torch.float32, device=DEV)
+    ws = torch.empty(qkv.card_attend_workspace(desc, H * R), dtype=torch.uint8, device=DEV)
+    status = torch.zeros(3, dtype=torch.int32, device=DEV)
+
+    def work():
+        qkv.controller_scores(feats, params, scores)
+        qkv.assign_bits(scores, 5.0, bits=bits)
+        qkv.quantize_pack(desc, K, V, bits, c1, card)
+        qkv.assign_bits(scores, 3.0, bits=bits2)
+        qkv.requantize(card, desc, bits2, c2, card2, status=status[0:1])
+        qkv.inject_layers(card2, desc, [k[:, 8:] for k in kl], [v[:, 8:] for v in vl], 0, rope_base=10000.0, rope_delta=8,
+                          status=status[1:2])
+        qkv.card_attend(card2, desc, q, D ** -0.5, out, workspace=ws, status=status[2:3])
+
+    def fill(seed):
+        feats.copy_(qkv_synth.make_features(T, seed, DEV))
+        k, v = qkv_synth.make_kv(L, H, T, D, seed + 1, "llama", device=DEV)
+        K.copy_(k); V.copy_(v)
+        q.copy_(qkv_synth.normal(seed + 2, 3, 0, L * H * R * D, DEV).view(L, H * R, D).to(torch.float16))
+
+    fill(900)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        work()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        work()
+    for rep, seed in enumerate((900, 910, 920, 900)):
+        fill(seed)                                   # eager work between the replays
+        for t in [card, card2, out] + kl + vl:
+            t.zero_()
+        status.fill_(9)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [0, 0, 0], rep
+        got = (card.clone(), card2.clone(), out.clone(), [k.clone() for k in kl], [v.clone() for v in vl])
+        for t in [card, card2, out] + kl + vl:
+            t.zero_()
+        work()                                       # the same inputs, eagerly
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], card) and torch.equal(got[1], card2) and torch.equal(got[2], out), rep
+        assert all(torch.equal(a, b) for a, b in zip(got[3], kl)) and all(torch.equal(a, b) for a, b in zip(got[4], vl)), rep
+    # and the last eager result against the oracle's chain
+    ws_ = ref.controller_scores(feats.cpu().numpy(), w1, b1, w2)
+    wb1, wc1 = ref.assign_bits(ws_, 5.0)
+    wb2, wc2 = ref.assign_bits(ws_, 3.0)
+    wcard = ref.quantize_pack(rd, K.cpu().numpy().view(np.uint16), V.cpu().numpy().view(np.uint16), wb1, wc1)
+    assert np.array_equal(card.cpu().numpy(), wcard)
+    wcard2 = oracle_hop(wcard, rd, rd, wb2, wc2)
+    assert np.array_equal(card2.cpu().numpy(), wcard2)
+    wk = [np.zeros((H, T + 8, D), np.uint16) for _ in range(L)]
+    wv = [np.zeros((H, T + 8, D), np.uint16) for _ in range(L)]
+    inject_ref.inject_layers(wcard2, rd, wk, wv, 0, 8, (10000.0, 8))
+    for l in range(L):
+        assert np.array_equal(kl[l].view(torch.int16).cpu().numpy().view(np.uint16), wk[l])
+        assert np.array_equal(vl[l].view(torch.int16).cpu().numpy().view(np.uint16), wv[l])
