@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 # Bytes between L2 and the memory fabric per launch, from the FETCH_SIZE and WRITE_SIZE counters
 # scaled by what a plain 512 MiB copy reads on them (profiles/pack_unpack_llama8b_8k_b3_hbm_traffic.txt).
 MEASURED_TRAFFIC = {
-    "llama8b_8k_b3": {"pack": 1341463244, "unpack": 1342126488},
+    "llama8b_8k_b3": {"pack": 1341465395, "unpack": 1342183220},
 }
 
 
@@ -167,6 +167,9 @@ def main():
                     help="where the per-layer injection writes: one allocation per layer tensor with room for a 64-token "
                          "prefix (as frameworks keep their caches), views of one pooled allocation, or the dense output "
                          "tensors of the handoff itself (same addresses as qkv_unpack_dequant)")
+    ap.add_argument("--handoff-only", action="store_true",
+                    help="time the handoff alone and skip the blocks around it (attention, injection, requantization, "
+                         "controller): for profiles in which every launch of a kernel belongs to the timed step")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a captured graph (reported beside the eager figure)")
     ap.add_argument("--cpu-layers", type=int, default=0,
@@ -291,7 +294,7 @@ def main():
     # beyond the handoff itself: one decode step's attention taken directly over the card
     # (32 query heads on 8 kv heads as in Llama-3.1-8B), timed on its own
     attend = None
-    if D == 128 and not kc:
+    if D == 128 and not kc and not args.handoff_only:
         rep = 4
         qv = qkv_synth.normal(cfg["data_seed"] + 17, 9, 0, L * H * rep * D, dev).view(L, H * rep, D).to(torch.float16)
         a_out = torch.empty((L, H * rep, D), dtype=torch.float32, device=dev)
@@ -317,7 +320,7 @@ def main():
     # injection into per-layer caches (one key and one value tensor per layer, room for a prefix), with and
     # without realigning the keys, in one call and layer by layer
     inject = None
-    if L <= 64 and not kc:
+    if L <= 64 and not kc and not args.handoff_only:
         prefix, cap = 64, T + 64
         if args.inject_layout == "dense":
             prefix, cap = 0, T
@@ -362,7 +365,7 @@ def main():
 
     # forwarding the card at a lower budget, card to card (one hop of a chain), against the chain it replaces
     requant = None
-    if scores is not None and not kc:
+    if scores is not None and not kc and not args.handoff_only:
         b2, c2 = qkv.assign_bits(qkv_synth.make_scores(T, cfg["data_seed"] + 31, dev), max(2.0, budget - 0.5))
         nxt = torch.empty(qkv.card_bytes(desc, c2), dtype=torch.uint8, device=dev)
         nxt2 = torch.empty_like(nxt)
