@@ -152,6 +152,35 @@ def hop_report(qkv, cfg, K, V, desc, dev):
     return out
 
 
+def device_state(dev):
+    """Name, unit counts and clocks of the GPU the run used: the limits HIP reports, and the levels the
+    driver's sysfs files show as active at the end of the run (absent where the files are not readable)."""
+    import glob
+    pr = torch.cuda.get_device_properties(dev)
+    st = {"name": pr.name, "arch": getattr(pr, "gcnArchName", None), "compute_units": pr.multi_processor_count,
+          "hbm_bytes": pr.total_memory}
+    for key in ("clock_rate", "memory_clock_rate", "L2_cache_size"):
+        if hasattr(pr, key):
+            st[key + ("_khz" if key.endswith("rate") else "")] = getattr(pr, key)
+    try:
+        want = "%04x:%02x:%02x" % (pr.pci_domain_id, pr.pci_bus_id, pr.pci_device_id)
+        for card in sorted(glob.glob("/sys/class/drm/card*/device")):
+            if not os.path.basename(os.path.realpath(card)).startswith(want):
+                continue
+            for name, key in (("pp_dpm_sclk", "sclk_active"), ("pp_dpm_mclk", "mclk_active"),
+                              ("power_dpm_force_performance_level", "performance_level")):
+                try:
+                    with open(os.path.join(card, name)) as f:
+                        lines = [ln.strip() for ln in f.read().splitlines() if ln.strip()]
+                except OSError:
+                    continue
+                active = [ln for ln in lines if ln.endswith("*")]
+                st[key] = (active[0].rstrip("* ") if active else lines[0]) if lines else None
+    except (AttributeError, OSError):
+        pass
+    return st
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -455,6 +484,7 @@ def main():
         "ms_per_step_with_events": round(ms_per_step_events, 4),
         "ms_per_step_graph_replay": None if graph_ms is None else round(graph_ms, 4),
         "copy_ceiling_gbs": round(copy_gbs, 1),
+        "device": device_state(dev),
         "card_attend": attend,
         "controller": controller,
         "inject_layers": inject,

@@ -75,7 +75,8 @@ extern "C" {
 #define QKV_ERR_ALIGN     -6  /* a device pointer is not aligned as required                  */
 #define QKV_ERR_COUNTS    -7  /* class counts negative or not summing to tokens               */
 #define QKV_ERR_HIP       -8  /* a HIP runtime call failed                                    */
-#define QKV_ERR_FORMAT    -9  /* card header is not a valid layout-v1 header (peek only)      */
+#define QKV_ERR_FORMAT    -9  /* card header is not a valid layout-v1 header (peek, flags)    */
+#define QKV_ERR_OVERLAP   -10 /* an output buffer overlaps an input that is read meanwhile    */
 
 #define QKV_CARD_VERSION        1u
 #define QKV_CARD_HEADER_BYTES   256u
@@ -356,7 +357,7 @@ int qkv_inject_layers(const void* card_dev, uint64_t card_bytes, const qkv_desc_
  *               QKV_STATUS_BAD_ORDER or-ed in when a corrupt table entry of the incoming card was
  *               skipped (its rows are then zeros).
  * Asynchronous on `stream`; allocates nothing.
- * Errors: as qkv_quantize_pack.
+ * Errors: as qkv_quantize_pack; QKV_ERR_OVERLAP when the two cards' byte ranges intersect.
  */
 int qkv_requantize(const void* card_in_dev, uint64_t card_in_bytes, const qkv_desc_t* desc,
                    const uint8_t* bits_dev, const int64_t counts[4], void* card_out_dev,
@@ -405,6 +406,17 @@ int qkv_card_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t*
 int qkv_card_peek(const void* card_dev, uint64_t card_bytes, qkv_desc_t* desc_out,
                   int64_t counts_out[4], float* avg_bits_out, uint32_t* status_out,
                   void* stream);
+
+/*
+ * The flags word of a card's header: 0, or QKV_FLAG_KEYS_PER_CHANNEL for a card whose keys are
+ * grouped per channel.  It tells a receiver which of qkv_unpack_dequant / qkv_unpack_dequant_kc
+ * (and which keys_per_channel value of qkv_inject_layers) the card is for - the card is
+ * self-describing (paper Sec. 4.2.1).  Validates the header like qkv_card_peek, and also that a
+ * flagged card has a shape and widths that grouping allows; flags_out (host) is written only on
+ * QKV_OK.  SYNCHRONISES `stream`.
+ * Errors: QKV_ERR_NULL, QKV_ERR_FORMAT, QKV_ERR_HIP.
+ */
+int qkv_card_flags(const void* card_dev, uint64_t card_bytes, uint32_t* flags_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -11,6 +11,7 @@ STATUS_BAD_BITS = 0x1
 STATUS_BAD_COUNTS = 0x2
 STATUS_BAD_HEADER = 0x4
 STATUS_BAD_ORDER = 0x8
+FLAG_KEYS_PER_CHANNEL = 0x1
 
 
 class QkvError(RuntimeError):
@@ -129,6 +130,8 @@ def lib():
     L.qkv_card_peek.restype = ctypes.c_int
     L.qkv_card_peek.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), i64p, ctypes.POINTER(ctypes.c_float),
                                 ctypes.POINTER(ctypes.c_uint32), vp]
+    L.qkv_card_flags.restype = ctypes.c_int
+    L.qkv_card_flags.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint32), vp]
     _lib = L
     return L
 
@@ -336,6 +339,15 @@ def card_attend(card, expect, q, softmax_scale, out, lse=None, workspace=None, s
                                  _dev_ptr(out, torch.float32, "out"), lp, _dev_ptr(workspace, torch.uint8, "workspace"),
                                  workspace.numel(), sp, _stream(stream)), "qkv_card_attend")
     return out, lse
+
+
+def card_flags(card, card_nbytes=None, stream=None):
+    """The header's flags word (0 or FLAG_KEYS_PER_CHANNEL) of a valid card.  Synchronises the stream."""
+    n = card.numel() if card_nbytes is None else int(card_nbytes)
+    fl = ctypes.c_uint32(0)
+    _check(lib().qkv_card_flags(_dev_ptr(card, torch.uint8, "card"), n, ctypes.byref(fl), _stream(stream)),
+           "qkv_card_flags")
+    return fl.value
 
 
 def card_peek(card, card_nbytes=None, stream=None):

@@ -99,6 +99,12 @@ bool header_valid(const qkv_card_header_t& h, uint64_t card_bytes, CardGeom& g) 
     sum += h.count[c];
   }
   if (sum != h.tokens) return false;
+  if (h.flags != 0u) {   // the one flag there is: keys grouped per channel, uniform cards of certain shapes only
+    if (h.flags != QKV_FLAG_KEYS_PER_CHANNEL) return false;
+    if (h.group_size != 32 || (h.head_dim != 64 && h.head_dim != 128) || h.tokens % (h.head_dim == 64 ? 64 : 32) != 0)
+      return false;
+    if (h.count[0] != h.tokens && h.count[1] != h.tokens && h.count[2] != h.tokens) return false;
+  }
   build_geom(g, h.layers, h.kv_heads, h.head_dim, h.group_size, h.tokens, h.count);
   if (h.total_bytes != g.total || g.total > card_bytes) return false;
   if (h.off_bits != g.off_bits || h.off_slot != g.off_slot || h.off_order != g.off_order || h.off_fp16 != g.off_fp16)
@@ -129,6 +135,7 @@ const char* qkv_error_string(int code) {
     case QKV_ERR_COUNTS: return "class counts negative or not summing to tokens";
     case QKV_ERR_HIP: return "a HIP runtime call failed";
     case QKV_ERR_FORMAT: return "not a valid layout-v1 card header";
+    case QKV_ERR_OVERLAP: return "input and output buffers overlap";
     default: return "unknown error code";
   }
 }
@@ -309,6 +316,10 @@ int qkv_requantize(const void* card_in_dev, uint64_t card_in_bytes, const qkv_de
   if (card_in_bytes < QKV_CARD_HEADER_BYTES) return QKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(card_in_dev) % QKV_CARD_ALIGN != 0 || reinterpret_cast<uintptr_t>(status_dev) % 4 != 0)
     return QKV_ERR_ALIGN;
+  {   // rows of the new card are written while rows of the old one are still being read
+    const uintptr_t in0 = reinterpret_cast<uintptr_t>(card_in_dev), out0 = reinterpret_cast<uintptr_t>(card_out_dev);
+    if (in0 < out0 + g.total && out0 < in0 + card_in_bytes) return QKV_ERR_OVERLAP;
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
   uint8_t* card = static_cast<uint8_t*>(card_out_dev);
   rc = plan_card(desc, bits_dev, g, n, card, s);
@@ -478,16 +489,33 @@ int qkv_card_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t*
   return QKV_OK;
 }
 
-int qkv_card_peek(const void* card_dev, uint64_t card_bytes, qkv_desc_t* desc_out, int64_t counts_out[4],
-                  float* avg_bits_out, uint32_t* status_out, void* stream) {
+namespace {
+// Copies a card's header to the host (synchronising the stream) and validates it.
+int fetch_header(const void* card_dev, uint64_t card_bytes, void* stream, qkv_card_header_t& h) {
   if (!card_dev) return QKV_ERR_NULL;
   if (card_bytes < QKV_CARD_HEADER_BYTES) return QKV_ERR_FORMAT;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  qkv_card_header_t h;
   if (hipMemcpyAsync(&h, card_dev, sizeof(h), hipMemcpyDeviceToHost, s) != hipSuccess) return QKV_ERR_HIP;
   if (hipStreamSynchronize(s) != hipSuccess) return QKV_ERR_HIP;
   CardGeom g;
-  if (!header_valid(h, card_bytes, g)) return QKV_ERR_FORMAT;
+  return header_valid(h, card_bytes, g) ? QKV_OK : QKV_ERR_FORMAT;
+}
+}  // namespace
+
+int qkv_card_flags(const void* card_dev, uint64_t card_bytes, uint32_t* flags_out, void* stream) {
+  if (!flags_out) return QKV_ERR_NULL;
+  qkv_card_header_t h;
+  const int rc = fetch_header(card_dev, card_bytes, stream, h);
+  if (rc) return rc;
+  *flags_out = h.flags;
+  return QKV_OK;
+}
+
+int qkv_card_peek(const void* card_dev, uint64_t card_bytes, qkv_desc_t* desc_out, int64_t counts_out[4],
+                  float* avg_bits_out, uint32_t* status_out, void* stream) {
+  qkv_card_header_t h;
+  const int rc = fetch_header(card_dev, card_bytes, stream, h);
+  if (rc) return rc;
   if (desc_out) {
     desc_out->layers = (int32_t)h.layers;
     desc_out->kv_heads = (int32_t)h.kv_heads;

@@ -109,6 +109,8 @@ def test_argument_errors_are_reported_before_any_gpu_work():
     assert L.qkv_assign_bits(None, 64, 4.0, None, c, None) == -1
     assert L.qkv_count_bits(None, 64, c, None) == -1
     assert L.qkv_card_peek(None, 0, None, None, None, None, None) == -1
+    fl = ctypes.c_uint32(0)
+    assert L.qkv_card_flags(None, 0, ctypes.byref(fl), None) == -1 and L.qkv_card_flags(None, 0, None, None) == -1
     assert L.qkv_card_attend(None, 0, ctypes.byref(d), None, 8, ctypes.c_float(1.0), None, None, None, 0, None, None) == -1
     ws = ctypes.c_uint64(0)
     assert L.qkv_card_attend_workspace(ctypes.byref(d), 8, ctypes.byref(ws)) == 0 and ws.value > 0

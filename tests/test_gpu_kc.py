@@ -112,6 +112,15 @@ def test_the_two_groupings_refuse_each_other_on_the_device():
     torch.cuda.synchronize()
     assert int(status.item()) == qkv.STATUS_BAD_HEADER
     assert bool((ko.view(torch.int16) == canary).all()) and bool((vo.view(torch.int16) == canary).all())
+    # the header says which grouping a card has
+    assert qkv.card_flags(card_kc) == qkv.FLAG_KEYS_PER_CHANNEL and qkv.card_flags(card_pt) == 0
+    broken = card_kc.clone()
+    broken[188] = 3                                                        # an unknown flag bit
+    with pytest.raises(qkv.QkvError) as err:
+        qkv.card_flags(broken)
+    assert err.value.code == -9
+    with pytest.raises(qkv.QkvError):
+        qkv.card_peek(broken)
     # injection must be told the grouping; attention reads per-token groups only
     status.zero_()
     qkv.inject_layers(card_kc, desc, [ko[0], ko[1]], [vo[0], vo[1]], 0, status=status)

@@ -143,6 +143,12 @@ def test_requantize_host_errors():
     assert L.qkv_requantize(card.data_ptr() + 16, card.numel() - 16, ctypes.byref(d), bits.data_ptr(), c, out.data_ptr(), out.numel(), None, None) == -6
     c2 = (ctypes.c_int64 * 4)(0, 63, 0, 0)
     assert L.qkv_requantize(card.data_ptr(), card.numel(), ctypes.byref(d), bits.data_ptr(), c2, out.data_ptr(), out.numel(), None, None) == -7
+    # the two cards may not share bytes: same buffer, and an outgoing card that starts inside the incoming one
+    assert L.qkv_requantize(out.data_ptr(), out.numel(), ctypes.byref(d), bits.data_ptr(), c, out.data_ptr(), out.numel(), None, None) == -10
+    assert L.qkv_requantize(out.data_ptr(), out.numel(), ctypes.byref(d), bits.data_ptr(), c, out.data_ptr() + 4096, out.numel() - 4096, None, None) == -10
+    need = qkv.card_bytes(d, [0, 64, 0, 0])
+    assert need <= (1 << 19)      # back to back in one buffer is fine
+    assert L.qkv_requantize(out.data_ptr(), 1 << 19, ctypes.byref(d), bits.data_ptr(), c, out.data_ptr() + (1 << 19), 1 << 19, None, None) == 0
     torch.cuda.synchronize()
 
 
