@@ -196,6 +196,9 @@ def main():
                     help="where the per-layer injection writes: one allocation per layer tensor with room for a 64-token "
                          "prefix (as frameworks keep their caches), views of one pooled allocation, or the dense output "
                          "tensors of the handoff itself (same addresses as qkv_unpack_dequant)")
+    ap.add_argument("--beside-forward", action="store_true",
+                    help="also time layer-by-layer injection on a second stream beside a stand-in for the receiver's "
+                         "forward pass over its prefix (library GEMMs), against running the two one after the other")
     ap.add_argument("--handoff-only", action="store_true",
                     help="time the handoff alone and skip the blocks around it (attention, injection, requantization, "
                          "controller): for profiles in which every launch of a kernel belongs to the timed step")
@@ -385,11 +388,60 @@ def main():
                 qkv.inject_layers(card, desc, kls[l:l + 1], vls[l:l + 1], l, rope_base=500000.0, rope_delta=prefix)
 
         layer_ms = timed(by_layer)
+
+        # Layer-at-a-time injection beside the receiver's own forward pass (Sec. 4.2.2: the receiver prefills its
+        # prefix while the foreign cache arrives).  The forward pass is a stand-in: the dense projections of one
+        # Llama-3.1-8B layer (hidden 4096, 14336 wide MLP, bf16, library GEMMs) over the prefix tokens, the same
+        # weights for every layer; layer l of it waits for layer l of the injection, which runs on a second stream.
+        overlap = None
+        if args.beside_forward and args.workload.startswith("llama8b") and prefix > 0:
+            hid, ffn = 4096, 14336
+            g = torch.Generator(device=dev).manual_seed(cfg["data_seed"] + 41)
+            mk = lambda *shape: (torch.randn(*shape, device=dev, generator=g, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+            w_qkv, w_o, w_gu, w_d = mk(hid, hid + 2 * H * D), mk(hid, hid), mk(hid, 2 * ffn), mk(ffn, hid)
+            x0 = mk(prefix, hid)
+
+            def layer_forward(x):
+                x = x + (x @ w_qkv)[:, :hid] @ w_o
+                gu = x @ w_gu
+                return x + (torch.nn.functional.silu(gu[:, :ffn]) * gu[:, ffn:]) @ w_d
+
+            def forward_alone():
+                x = x0
+                for _ in range(L):
+                    x = layer_forward(x)
+
+            def serial():
+                by_layer()
+                forward_alone()
+
+            side = torch.cuda.Stream()
+            main = torch.cuda.current_stream()
+            ready = [torch.cuda.Event() for _ in range(L)]
+
+            def overlapped():
+                side.wait_stream(main)
+                with torch.cuda.stream(side):
+                    for l in range(L):
+                        qkv.inject_layers(card, desc, kls[l:l + 1], vls[l:l + 1], l, rope_base=500000.0, rope_delta=prefix)
+                        ready[l].record(side)
+                x = x0
+                for l in range(L):
+                    main.wait_event(ready[l])
+                    x = layer_forward(x)
+                main.wait_stream(side)
+
+            overlap = {"receiver_forward_stand_in": "dense projections of %d Llama-3.1-8B layers over %d prefix tokens, bf16" % (L, prefix),
+                       "forward_alone_ms": round(timed(forward_alone), 4),
+                       "injection_then_forward_ms": round(timed(serial), 4),
+                       "injection_beside_forward_ms": round(timed(overlapped), 4)}
+            del w_qkv, w_o, w_gu, w_d
         inject = {"call": "qkv_inject_layers", "layers": L, "calls": n_inj, "layout": args.inject_layout,
                   "unpack_dequant_same_loop_ms": round(dense_ms, 4), "one_call_ms": round(plain_ms, 4), "one_call_realigned_ms": round(rope_ms, 4),
                   "layer_by_layer_realigned_ms": round(layer_ms, 4),
                   "frac_hbm_peak": round(moved / (plain_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                  "frac_hbm_peak_realigned": round(moved / (rope_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+                  "frac_hbm_peak_realigned": round(moved / (rope_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                  "beside_receiver_forward": overlap}
         del per_layer, kls, vls
 
     # forwarding the card at a lower budget, card to card (one hop of a chain), against the chain it replaces
