@@ -200,3 +200,106 @@ def test_8k_injection_into_per_layer_caches_realigned():
     for l in sampled:
         assert torch.equal(k1[l].view(torch.int16), kc[l].view(torch.int16))
         assert torch.equal(v1[l].view(torch.int16), vc[l].view(torch.int16))
+
+
+def test_64k_cards_beyond_4_gib_sampled_planes():
+    """Offsets past 2^32 everywhere: 64K tokens of the Llama-8B shape are 4 GiB of keys and 4 GiB of values, and at
+    budget 9 the card is 5.2 GB with a raw 16-bit section that starts below and ends above 4 GiB.  The GPU runs
+    everything; the oracle runs sampled (layer, head) pairs, the last one included, through card creation,
+    injection (dense and per layer), a requantized hop at budget 5 and attention over the card."""
+    from oracle import attend_ref
+    L, H, T, D, G = 32, 8, 65536, 128, 32
+    sampled = [(0, 0), (15, 4), (31, 7)]
+    say("64K: generating")
+    K, V = qkv_synth.make_kv(L, H, T, D, 6001, "llama", device=DEV)
+    ok = {lh: K[lh[0], lh[1]].cpu().numpy().reshape(1, 1, T, D).copy() for lh in sampled}
+    ov = {lh: V[lh[0], lh[1]].cpu().numpy().reshape(1, 1, T, D).copy() for lh in sampled}
+    desc = qkv.Desc.make(L, H, T, D, G, model_id=8, sender_id=2)
+    sd = ref.make_desc(1, 1, T, D, G, 8, 2, 0)
+    K_out, V_out = torch.empty_like(K), torch.empty_like(V)
+
+    def widths(seed, budget):
+        bits, counts = qkv.assign_bits(qkv_synth.make_scores(T, seed, DEV), budget)
+        want_bits, want_counts = ref.assign_bits(qkv_synth.make_scores(T, seed).numpy(), budget)
+        assert counts == want_counts.tolist() and np.array_equal(bits.cpu().numpy(), want_bits)
+        return bits, counts, want_bits
+
+    def compare_planes(card, counts, subs, label):
+        full_off = ref.card_offsets(ref.make_desc(L, H, T, D, G), counts)
+        assert card.numel() == full_off["total"]
+        for (l, h) in sampled:
+            sub_off = ref.card_offsets(sd, counts)
+            for kv, plane in ((0, l * H + h), (1, L * H + l * H + h)):
+                for name, want in plane_rows(subs[(l, h)], sub_off, counts, 2, kv, D, G).items():
+                    if want.size == 0:
+                        continue
+                    start = full_off[name] + want.size * plane
+                    assert np.array_equal(card[start:start + want.size].cpu().numpy(), want), (label, l, h, kv, name)
+
+    say("64K: card at budget 9")
+    bits, counts, want_bits = widths(6002, 9.0)
+    n = qkv.card_bytes(desc, counts)
+    full_off = ref.card_offsets(ref.make_desc(L, H, T, D, G), counts)
+    assert n > (1 << 32) and full_off["fp16"] < (1 << 32)
+    card = torch.empty(n, dtype=torch.uint8, device=DEV)
+    qkv.quantize_pack(desc, K, V, bits, counts, card)
+    status = torch.ones(1, dtype=torch.int32, device=DEV)
+    qkv.unpack_dequant(card, desc, K_out, V_out, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0 and qkv.card_peek(card)[3] == 0
+    subs = {lh: ref.quantize_pack(sd, ok[lh], ov[lh], want_bits, counts) for lh in sampled}
+    compare_planes(card, counts, subs, "card")
+    dense = {}
+    for (l, h) in sampled:
+        wk, wv = ref.unpack_dequant(subs[(l, h)], sd)
+        assert np.array_equal(K_out[l, h].cpu().numpy().view(np.uint16), wk[0, 0]), (l, h, "K")
+        assert np.array_equal(V_out[l, h].cpu().numpy().view(np.uint16), wv[0, 0]), (l, h, "V")
+        dense[(l, h)] = (wk, wv)
+
+    say("64K: the last layers into per-layer caches")
+    prefix = 8
+    kl = [torch.zeros((H, T + prefix, D), dtype=torch.float16, device=DEV) for _ in range(2)]
+    vl = [torch.zeros((H, T + prefix, D), dtype=torch.float16, device=DEV) for _ in range(2)]
+    status.fill_(1)
+    qkv.inject_layers(card, desc, [k[:, prefix:] for k in kl], [v[:, prefix:] for v in vl], L - 2, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    for i in range(2):
+        assert torch.equal(kl[i][:, prefix:], K_out[L - 2 + i]) and torch.equal(vl[i][:, prefix:], V_out[L - 2 + i])
+        assert not bool(kl[i][:, :prefix].any()) and not bool(vl[i][:, :prefix].any())
+    del kl, vl
+
+    say("64K: attention over the card")
+    rep, scale = 4, D ** -0.5
+    q = np.random.default_rng(64).standard_normal((L, H * rep, D)).astype(np.float16)
+    out = torch.empty((L, H * rep, D), dtype=torch.float32, device=DEV)
+    lse = torch.empty((L, H * rep), dtype=torch.float32, device=DEV)
+    status.fill_(1)
+    qkv.card_attend(card, desc, torch.from_numpy(q).to(DEV), scale, out, lse=lse, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    for (l, h) in sampled:
+        qs = q[l:l + 1, h * rep:(h + 1) * rep]
+        want_o, want_lse = attend_ref.card_attend(subs[(l, h)], sd, qs, scale)
+        wk, wv = dense[(l, h)]
+        ds = float((np.abs(wk.view(np.float16).astype(np.float64))[0, 0] @ np.abs(qs[0].astype(np.float64)).T).max())
+        ds *= 128 * 2.0 ** -24 * scale
+        vmax = float(np.abs(wv.view(np.float16).astype(np.float64)).max())
+        base = (T + 8) * 2.0 ** -24 + 2.0 ** -21
+        tol_o, tol_l = min((2 * ds + base) * vmax, 1e-4 * max(1.0, vmax)), min(ds + base, 1e-4)
+        err_o = float(np.abs(out[l, h * rep:(h + 1) * rep].cpu().numpy() - want_o[0]).max())
+        err_l = float(np.abs(lse[l, h * rep:(h + 1) * rep].cpu().numpy() - want_lse[0]).max())
+        print("        (%d, %d) max |do| %.3g (bound %.3g)   max |dlse| %.3g (bound %.3g)" % (l, h, err_o, tol_o, err_l, tol_l),
+              flush=True)
+        assert err_o <= tol_o and err_l <= tol_l
+
+    say("64K: forwarded at budget 5, card to card")
+    bits2, counts2, want_bits2 = widths(6003, 5.0)
+    card2 = torch.empty(qkv.card_bytes(desc, counts2), dtype=torch.uint8, device=DEV)
+    status.fill_(1)
+    qkv.requantize(card, desc, bits2, counts2, card2, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    subs2 = {lh: ref.quantize_pack(sd, dense[lh][0].view(np.float16), dense[lh][1].view(np.float16), want_bits2, counts2)
+             for lh in sampled}
+    compare_planes(card2, counts2, subs2, "forwarded card")
