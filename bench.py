@@ -284,17 +284,21 @@ def main():
             step()
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
+        # one graph holds one step per buffer set, so that a replay rotates the sets as the eager loop does
+        turn[0] = 0
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            step()
-        for _ in range(args.warmup):
+            for _ in range(nsets):
+                step()
+        replays = max(1, args.steps // nsets)
+        for _ in range(max(1, args.warmup // nsets)):
             g.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(replays):
             g.replay()
         torch.cuda.synchronize()
-        graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
+        graph_ms = (time.perf_counter() - t0) / (replays * nsets) * 1e3
 
     # the same K steps again with HIP events around every call (the events cost a few
     # microseconds per step themselves, which is why the figure above is taken without them)
