@@ -507,6 +507,36 @@ def main():
     torch.cuda.synchronize()
     copy_gbs = 2 * K.numel() * 2 / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e9
 
+    # the handoff's memory traffic without its arithmetic, in the same rotation of buffer sets: 8 KiB read and
+    # 2 KiB written per unit where card creation reads fp16 rows and writes a card of a quarter their size, then the
+    # reverse for injection; the same cache policies (rows streamed, the card kept in the memory-side cache)
+    ceiling = None
+    if 0.22 <= card_bytes / kv_bytes <= 0.28:
+        src = torch.empty(kv_bytes, dtype=torch.uint8, device=dev)
+        src[:kv_bytes // 2].copy_(K.view(torch.uint8).reshape(-1))
+        src[kv_bytes // 2:].copy_(V.view(torch.uint8).reshape(-1))
+        small = [torch.empty(kv_bytes // 4, dtype=torch.uint8, device=dev) for _ in range(nsets)]
+        big = [torch.empty(kv_bytes, dtype=torch.uint8, device=dev) for _ in range(nsets)]
+        n_pr = max(10, args.steps // 4)
+        pev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(3 + n_pr)]
+        torch.cuda.synchronize()
+        for it in range(3 + n_pr):                    # queued back to back, like the event-timed steps above
+            i = it % nsets
+            pev[it][0].record()
+            qkv.stream_probe(src, small[i], 8, 2, nontemporal=1)
+            pev[it][1].record()
+            qkv.stream_probe(small[i], big[i], 2, 8, nontemporal=2)
+            pev[it][2].record()
+        torch.cuda.synchronize()
+        pr_ms = [sum(e[0].elapsed_time(e[1]) for e in pev[3:]) / n_pr, sum(e[1].elapsed_time(e[2]) for e in pev[3:]) / n_pr]
+        ceiling = {"call": "qkv_stream_probe", "bytes_per_direction": kv_bytes + kv_bytes // 4,
+                   "creation_like_ms": round(pr_ms[0], 4), "injection_like_ms": round(pr_ms[1], 4),
+                   "creation_like_gbs": round((kv_bytes + kv_bytes // 4) / (pr_ms[0] * 1e-3) / 1e9, 1),
+                   "injection_like_gbs": round((kv_bytes + kv_bytes // 4) / (pr_ms[1] * 1e-3) / 1e9, 1),
+                   "pack_kernel_time_over_probe": round(fill_ms / pr_ms[0], 3),
+                   "unpack_kernel_time_over_probe": round(unpack_ms / pr_ms[1], 3)}
+        del src, small, big
+
     def roof(name, ms, leg):
         a = moved / (ms * 1e-3) / 1e9
         return {"kernel": name, "bound": "hbm", "achieved": round(a, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -540,6 +570,7 @@ def main():
         "ms_per_step_with_events": round(ms_per_step_events, 4),
         "ms_per_step_graph_replay": None if graph_ms is None else round(graph_ms, 4),
         "copy_ceiling_gbs": round(copy_gbs, 1),
+        "traffic_ceiling": ceiling,
         "device": device_state(dev),
         "card_attend": attend,
         "controller": controller,

@@ -418,6 +418,24 @@ int qkv_card_peek(const void* card_dev, uint64_t card_bytes, qkv_desc_t* desc_ou
  */
 int qkv_card_flags(const void* card_dev, uint64_t card_bytes, uint32_t* flags_out, void* stream);
 
+/*
+ * Measurement aid, not part of the method: moves the memory traffic of a handoff without its
+ * arithmetic, in the launch shape of the card kernels (one wave per unit, 128-bit accesses), so
+ * that a benchmark can say what this memory system gives that traffic mix.  Unit u reads
+ * reads_kib KiB at src + u * reads_kib KiB and writes writes_kib KiB at dst + u * writes_kib KiB;
+ * every written word is the exclusive-or of the unit's 16-byte chunks that the writing lane read
+ * (chunk k * 64 + lane, k = 0 .. reads_kib - 1, as four 32-bit words), plus the index of the write
+ * (0 .. writes_kib - 1) in each word.
+ *   reads_kib : writes_kib   8 : 2 (card creation at about 3 bits), 2 : 8 (injection), 8 : 8 (copy).
+ *   nontemporal: bit 0 loads, bit 1 stores bypass the caches' keep policy.
+ *   units_out:  host, may be NULL: the whole units that fit both buffers = units processed.
+ * src_dev, dst_dev: device, 16-byte aligned, not overlapping.  Asynchronous on `stream`.
+ * Errors: QKV_ERR_NULL, QKV_ERR_SHAPE (another mix or flag), QKV_ERR_ALIGN, QKV_ERR_OVERLAP, QKV_ERR_HIP.
+ */
+int qkv_stream_probe(const void* src_dev, uint64_t src_bytes, void* dst_dev, uint64_t dst_bytes,
+                     int32_t reads_kib, int32_t writes_kib, int32_t nontemporal, uint64_t* units_out,
+                     void* stream);
+
 #ifdef __cplusplus
 }
 #endif

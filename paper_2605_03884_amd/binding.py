@@ -132,6 +132,9 @@ def lib():
                                 ctypes.POINTER(ctypes.c_uint32), vp]
     L.qkv_card_flags.restype = ctypes.c_int
     L.qkv_card_flags.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint32), vp]
+    L.qkv_stream_probe.restype = ctypes.c_int
+    L.qkv_stream_probe.argtypes = [vp, ctypes.c_uint64, vp, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                   ctypes.POINTER(ctypes.c_uint64), vp]
     _lib = L
     return L
 
@@ -339,6 +342,16 @@ def card_attend(card, expect, q, softmax_scale, out, lse=None, workspace=None, s
                                  _dev_ptr(out, torch.float32, "out"), lp, _dev_ptr(workspace, torch.uint8, "workspace"),
                                  workspace.numel(), sp, _stream(stream)), "qkv_card_attend")
     return out, lse
+
+
+def stream_probe(src, dst, reads_kib, writes_kib, nontemporal=0, stream=None):
+    """Measurement aid: the traffic of a handoff without its arithmetic.  src, dst: device uint8 tensors.
+    Returns the number of units moved (reads_kib KiB read and writes_kib KiB written each)."""
+    units = ctypes.c_uint64(0)
+    _check(lib().qkv_stream_probe(_dev_ptr(src, torch.uint8, "src"), src.numel(), _dev_ptr(dst, torch.uint8, "dst"), dst.numel(),
+                                  int(reads_kib), int(writes_kib), int(nontemporal), ctypes.byref(units), _stream(stream)),
+           "qkv_stream_probe")
+    return units.value
 
 
 def card_flags(card, card_nbytes=None, stream=None):

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqkvcard.so")
-SOURCES = ["api.hip", "classify.hip", "pack.hip", "unpack.hip", "assign.hip", "attend.hip", "controller.hip", "requant.hip"]
+SOURCES = ["api.hip", "classify.hip", "pack.hip", "unpack.hip", "assign.hip", "attend.hip", "controller.hip", "requant.hip", "probe.hip"]
 
 # -ffp-contract=off: every fused multiply-add in the kernels is written out, none is invented;
 # packed fp32 instructions are switched off on this target.

@@ -489,6 +489,24 @@ int qkv_card_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t*
   return QKV_OK;
 }
 
+int qkv_stream_probe(const void* src_dev, uint64_t src_bytes, void* dst_dev, uint64_t dst_bytes, int32_t reads_kib,
+                     int32_t writes_kib, int32_t nontemporal, uint64_t* units_out, void* stream) {
+  if (!src_dev || !dst_dev) return QKV_ERR_NULL;
+  const bool known = (reads_kib == 8 && writes_kib == 2) || (reads_kib == 2 && writes_kib == 8) ||
+                     (reads_kib == 8 && writes_kib == 8);
+  if (!known || nontemporal < 0 || nontemporal > 3) return QKV_ERR_SHAPE;
+  if (reinterpret_cast<uintptr_t>(src_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(dst_dev) % 16 != 0) return QKV_ERR_ALIGN;
+  {
+    const uintptr_t s0 = reinterpret_cast<uintptr_t>(src_dev), d0 = reinterpret_cast<uintptr_t>(dst_dev);
+    if (s0 < d0 + dst_bytes && d0 < s0 + src_bytes) return QKV_ERR_OVERLAP;
+  }
+  const uint64_t units_r = src_bytes / ((uint64_t)reads_kib * 1024u), units_w = dst_bytes / ((uint64_t)writes_kib * 1024u);
+  const uint64_t units = units_r < units_w ? units_r : units_w;      // whole units that fit both buffers
+  if (units_out) *units_out = units;
+  return launch_stream_probe(src_dev, dst_dev, units, reads_kib, writes_kib, nontemporal, static_cast<hipStream_t>(stream)) ==
+                 hipSuccess ? QKV_OK : QKV_ERR_HIP;
+}
+
 namespace {
 // Copies a card's header to the host (synchronising the stream) and validates it.
 int fetch_header(const void* card_dev, uint64_t card_bytes, void* stream, qkv_card_header_t& h) {

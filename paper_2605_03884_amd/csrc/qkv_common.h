@@ -151,6 +151,8 @@ hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeo
 hipError_t launch_count(const uint8_t* bits, uint64_t tokens, unsigned long long* counts4, hipStream_t stream);
 hipError_t launch_controller(const float* features, uint32_t tokens, const qkv_controller_t& params, float* scores,
                              hipStream_t stream);
+hipError_t launch_stream_probe(const void* src, void* dst, uint64_t units, int reads_kib, int writes_kib, int nontemporal,
+                               hipStream_t stream);
 hipError_t launch_greedy(const float* scores, uint32_t tokens, uint32_t spare_units, uint8_t* bits,
                          unsigned long long* counts4, hipStream_t stream);
 
