@@ -225,7 +225,10 @@ def main():
     if scores is not None:
         bits, counts = qkv.assign_bits(scores, budget)
     else:
-        bits = qkv_synth.make_bits_constant(T, cfg["bits"][1], dev)
+        if cfg["bits"][0] == "choice":
+            bits = qkv_synth.make_bits_uniform_choice(T, cfg["bits"][1], dev)
+        else:
+            bits = qkv_synth.make_bits_constant(T, cfg["bits"][1], dev)
         counts = qkv.count_bits(bits)
     card_bytes = qkv.card_bytes(desc, counts)
     nsets = max(1, args.buffer_sets)
