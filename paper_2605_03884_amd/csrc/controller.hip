@@ -219,6 +219,8 @@ hipError_t launch_greedy(const float* scores, uint32_t tokens, uint32_t spare_un
                          unsigned long long* counts4, hipStream_t stream) {
   if (tokens <= 8u * kThreads)
     hipLaunchKernelGGL(greedy_kernel<8>, dim3(1), dim3(kThreads), 0, stream, scores, tokens, spare_units, bits, counts4);
+  else if (tokens <= 32u * kThreads)
+    hipLaunchKernelGGL(greedy_kernel<32>, dim3(1), dim3(kThreads), 0, stream, scores, tokens, spare_units, bits, counts4);
   else
     hipLaunchKernelGGL(greedy_kernel<0>, dim3(1), dim3(kThreads), 0, stream, scores, tokens, spare_units, bits, counts4);
   return hipGetLastError();

@@ -82,7 +82,7 @@ def score_variants(T, rng):
     }
 
 
-@pytest.mark.parametrize("T", [1, 2, 7, 100, 1023, 1024, 1025, 4097, 8192, 50001])
+@pytest.mark.parametrize("T", [1, 2, 7, 100, 1023, 1024, 1025, 4097, 8192, 8193, 20000, 32768, 32769, 50001])
 def test_greedy_matches_oracle(T):
     say("assign_bits_greedy T=%d" % T)
     rng = np.random.default_rng(T)
