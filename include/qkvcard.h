@@ -321,7 +321,8 @@ int qkv_unpack_dequant_kc(const void* card_dev, uint64_t card_bytes, const qkv_d
  *
  * Validation, status_dev and asynchrony as for qkv_unpack_dequant.  Allocates nothing.
  * Errors: QKV_ERR_NULL, QKV_ERR_SHAPE (layer range outside the card, layer_count < 1 or
- * > QKV_INJECT_MAX_LAYERS, bad strides, rope_base < 0 or not finite, |rope_delta| >= 2^31),
+ * > QKV_INJECT_MAX_LAYERS, bad strides - negative, not multiples of 8, token_stride < head_dim,
+ * token_stride * tokens or head_stride * kv_heads >= 2^46 -, rope_base < 0 or not finite, |rope_delta| >= 2^31),
  * QKV_ERR_GROUP, QKV_ERR_CAPACITY, QKV_ERR_ALIGN, QKV_ERR_HIP.
  */
 #define QKV_INJECT_MAX_LAYERS 64

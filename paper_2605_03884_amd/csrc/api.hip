@@ -402,6 +402,10 @@ int qkv_inject_layers(const void* card_dev, uint64_t card_bytes, const qkv_desc_
   if (where->token_stride < expect->head_dim || where->token_stride % 8 != 0 || where->head_stride < 0 ||
       where->head_stride % 8 != 0 || where->token_stride >= (1ll << 40) || where->head_stride >= (1ll << 40))
     return QKV_ERR_SHAPE;
+  // the farthest element a row address can reach must stay far inside 64-bit byte arithmetic
+  if ((__int128)where->token_stride * expect->tokens >= ((__int128)1 << 46) ||
+      (__int128)where->head_stride * expect->kv_heads >= ((__int128)1 << 46))
+    return QKV_ERR_SHAPE;
   if (!(where->rope_base >= 0.0) || !std::isfinite(where->rope_base) || where->rope_delta <= -(1ll << 31) ||
       where->rope_delta >= (1ll << 31))
     return QKV_ERR_SHAPE;

@@ -199,6 +199,12 @@ def test_inject_host_errors():
     assert call(0, 1, per_channel=2) == -2
     assert call(0, 1, per_channel=1) == 0                 # shape fits the per-channel rules; the device refuses the card's grouping
     assert L.qkv_inject_layers(card.data_ptr(), card.numel(), ctypes.byref(desc), None, None, None) == -1
+    # strides that would carry a row address out of range for the shape are refused before anything is launched
+    huge = qkv.Desc.make(1, 1, 1 << 30, 128, 32)
+    kp = (ctypes.c_void_p * 1)(kc[0].data_ptr())
+    vp = (ctypes.c_void_p * 1)(vc[0].data_ptr())
+    w = qkv.Inject(0, 1, kp, vp, 1 << 20, 1 << 20, 0.0, 0, 0, 0)
+    assert L.qkv_inject_layers(card.data_ptr(), card.numel(), ctypes.byref(huge), ctypes.byref(w), None, None) == -2
     torch.cuda.synchronize()
 
 
