@@ -118,3 +118,42 @@ def test_argument_errors_are_reported_before_any_gpu_work():
     assert L.qkv_card_attend_workspace(ctypes.byref(d), 3, ctypes.byref(ws)) == -2      # not a multiple of kv_heads
     assert L.qkv_card_attend_workspace(ctypes.byref(d), 2 * 17, ctypes.byref(ws)) == -2  # more than 16 query heads per kv head
     assert L.qkv_card_attend_workspace(ctypes.byref(qkv.Desc.make(2, 2, 64, 64, 32)), 8, ctypes.byref(ws)) == -2
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as strict C99 and a C program that links the library gets the
+    host-side answers (version, closed-form card size, budget counts, error strings) without Python in between."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    qkv.lib()                                                   # builds the library if it is not there yet
+    src = tmp_path / "use_qkvcard.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "qkvcard.h"
+int main(void) {
+  qkv_desc_t d;
+  int64_t counts[4] = {6282, 1092, 682, 136}, got[4];
+  uint64_t bytes = 0;
+  memset(&d, 0, sizeof d);
+  d.layers = 32; d.kv_heads = 8; d.head_dim = 128; d.group_size = 32; d.tokens = 8192;
+  if (sizeof(qkv_card_header_t) != QKV_CARD_HEADER_BYTES) return 1;
+  if (qkv_card_bytes(&d, counts, &bytes) != QKV_OK) return 2;
+  if (qkv_budget_counts(8192, 3.0, got) != QKV_OK) return 3;
+  if (memcmp(got, counts, sizeof got) != 0) return 4;
+  if (qkv_budget_counts(8192, 1.0, got) != QKV_ERR_BUDGET) return 5;
+  if (qkv_quantize_pack(&d, NULL, NULL, NULL, counts, NULL, 0, NULL) != QKV_ERR_NULL) return 6;
+  printf("%d %llu %s\n", qkv_version(), (unsigned long long)bytes, qkv_error_string(QKV_ERR_CAPACITY));
+  return 0;
+}
+''')
+    exe = tmp_path / "use_qkvcard"
+    libdir = os.path.dirname(qkv.lib_path())
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", os.path.join(ROOT, "include"), str(src),
+                    "-o", str(exe), "-L", libdir, "-lqkvcard", "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(None, 2)
+    assert int(out[0]) == qkv.version()
+    assert int(out[1]) == 267297024                            # the 8K benchmark card, closed form of the layout
+    assert out[2].strip() == "card buffer too small"
