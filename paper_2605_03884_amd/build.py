@@ -5,6 +5,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqkvcard.so")
+CLIENT_SRC = os.path.join(HERE, "..", "examples", "handoff_client.cpp")
+CLIENT = os.path.join(HERE, "handoff_client")          # a plain HIP host program that links the library
 SOURCES = ["api.hip", "classify.hip", "pack.hip", "unpack.hip", "assign.hip", "attend.hip", "controller.hip", "requant.hip", "probe.hip"]
 
 # -ffp-contract=off: every fused multiply-add in the kernels is written out, none is invented;
@@ -21,7 +23,19 @@ def build(verbose=False):
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
+    build_client(verbose)
     return LIB
+
+
+def build_client(verbose=False):
+    """The example host program (no device code of its own), linked against the library beside it."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-O2", "-std=c++17", "-Wall", "--offload-arch=gfx950", "-I", os.path.join(HERE, "..", "include"), CLIENT_SRC,
+           "-o", CLIENT, "-L", HERE, "-lqkvcard", "-Wl,-rpath,$ORIGIN"]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    return CLIENT
 
 
 if __name__ == "__main__":
