@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqkvcard.so")
-CLIENT_SRC = os.path.join(HERE, "..", "examples", "handoff_client.cpp")
+CLIENT_SRC = os.path.join(CSRC, "handoff_client.cpp")
 CLIENT = os.path.join(HERE, "handoff_client")          # a plain HIP host program that links the library
 SOURCES = ["api.hip", "classify.hip", "pack.hip", "unpack.hip", "assign.hip", "attend.hip", "controller.hip", "requant.hip", "probe.hip"]
 

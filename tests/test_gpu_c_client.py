@@ -1,4 +1,4 @@
-"""The boundary used without Python: a plain HIP host program (examples/handoff_client.cpp, built beside the
+"""The boundary used without Python: a plain HIP host program (paper_2605_03884_amd/csrc/handoff_client.cpp, built beside the
 library) takes seeded inputs from a file, runs one handoff through the C ABI with buffers from hipMalloc, and writes
 what it got; widths, card and dequantized cache are compared with the oracle byte for byte."""
 import os
