@@ -373,8 +373,9 @@ int qkv_requantize(const void* card_in_dev, uint64_t card_in_bytes, const qkv_de
  *     out[l][hq] = sum_t softmax(s)_t * V^[l][h][t],   lse[l][hq] = log sum_t exp(s_t)
  * where K^, V^ are the dequantized fp16 values, exactly those qkv_unpack_dequant would
  * write (raw 16-bit rows as they are).  Scores are accumulated in fp32 from fp16 products,
- * the softmax and the weighted sum run in fp32; the result agrees with the float64
- * definition to a few units in 1e-6 of max|V^| (summation order only).
+ * the softmax and the weighted sum run in fp32; against the float64 definition a score is off
+ * by at most 128 * 2^-24 * softmax_scale * sum_i |q_i K^_ti| (summation order only), which for
+ * caches of ordinary magnitude leaves out within a few units in 1e-6 of max|V^|.
  *   card_dev, card_bytes, expect, status_dev: as for qkv_unpack_dequant; head_dim must be 128.
  *   q_dev:    device, fp16 [layers][q_heads][128], 16-byte aligned.  q_heads is a multiple of
  *             kv_heads, at most 16 query heads per kv head.
