@@ -89,7 +89,7 @@ extern "C" {
 #define QKV_STATUS_BAD_BITS     0x1u  /* a bits[] value was not 2, 4, 8 or 16 (treated as 2)   */
 #define QKV_STATUS_BAD_COUNTS   0x2u  /* counts[] passed by the host differ from the histogram */
 #define QKV_STATUS_BAD_HEADER   0x4u  /* unpack: magic / version / shape / sizes do not match  */
-#define QKV_STATUS_BAD_ORDER    0x8u  /* unpack: an order[] entry was >= tokens (row skipped)  */
+#define QKV_STATUS_BAD_ORDER    0x8u  /* an order[] entry was >= tokens (row skipped / zeros)  */
 
 /* Problem description, host memory, caller-owned (paper Sec. 3.1 shape, Sec. 4.2.1 metadata). */
 typedef struct qkv_desc {
@@ -246,11 +246,40 @@ int qkv_quantize_pack(const qkv_desc_t* desc, const void* k_dev, const void* v_d
  *                  same desc and counts (it reads the card's order table, not bits_dev).
  * Arguments, alignment rules, error codes and status bits are those of qkv_quantize_pack;
  * plan followed by fill on one stream produces the same bytes.  Both are asynchronous.
+ * qkv_card_fill trusts nothing it reads from the card: an order[] entry that names no token
+ * (a card that was never planned, or was overwritten since) yields a row of zeros and sets
+ * QKV_STATUS_BAD_ORDER in the status word at byte 192 of the card; no access leaves K, V or
+ * the first qkv_card_bytes bytes of the card.
  */
 int qkv_card_plan(const qkv_desc_t* desc, const uint8_t* bits_dev, const int64_t counts[4],
                   void* card_dev, uint64_t card_capacity, void* stream);
 int qkv_card_fill(const qkv_desc_t* desc, const void* k_dev, const void* v_dev, const int64_t counts[4],
                   void* card_dev, uint64_t card_capacity, void* stream);
+
+/*
+ * Scores to a planned card in one launch (paper Sec. 3.3: the score decides the width under the
+ * budget; Sec. 4.2.1: the card's bit-width vector, sequence length, identifiers and average-bit
+ * statistic).  Does what qkv_assign_bits followed by qkv_card_plan does - same widths, same
+ * header, tables and pads, byte for byte - but in a single kernel: the workgroup that ranks the
+ * scores already holds every token's width, so slots, order[] and the header follow at once.
+ *   desc:       host.  tokens < 2^31.
+ *   scores_dev: device, float[T], 4-byte aligned (NaN is a precondition violation).
+ *   bits_dev:   device, uint8_t[T], written; may be NULL (the widths are in the card anyway).
+ *   counts_out: host, int64_t[4]: the budget's class counts (= qkv_budget_counts), filled before
+ *               return without a device sync; pass them on to qkv_card_fill.
+ *   card_dev:   device, 256-byte aligned, card_capacity >= qkv_card_bytes(desc, counts_out).
+ * qkv_card_fill on the same stream completes the card.  qkv_assign_quantize_pack is the two in
+ * one call: scores, budget and K/V in, widths and the whole card out (k_dev, v_dev as for
+ * qkv_quantize_pack).  Asynchronous on `stream`; allocate nothing.
+ * Errors: QKV_ERR_NULL, QKV_ERR_SHAPE, QKV_ERR_GROUP, QKV_ERR_BUDGET, QKV_ERR_ALIGN,
+ * QKV_ERR_CAPACITY, QKV_ERR_HIP.
+ */
+int qkv_assign_plan(const qkv_desc_t* desc, const float* scores_dev, double avg_bits_budget,
+                    uint8_t* bits_dev, int64_t counts_out[4], void* card_dev, uint64_t card_capacity,
+                    void* stream);
+int qkv_assign_quantize_pack(const qkv_desc_t* desc, const void* k_dev, const void* v_dev,
+                             const float* scores_dev, double avg_bits_budget, uint8_t* bits_dev,
+                             int64_t counts_out[4], void* card_dev, uint64_t card_capacity, void* stream);
 
 /*
  * Receiver-side injection (paper Sec. 4.2.2): unpack and dequantize a card into a
@@ -419,24 +448,6 @@ int qkv_card_peek(const void* card_dev, uint64_t card_bytes, qkv_desc_t* desc_ou
  * Errors: QKV_ERR_NULL, QKV_ERR_FORMAT, QKV_ERR_HIP.
  */
 int qkv_card_flags(const void* card_dev, uint64_t card_bytes, uint32_t* flags_out, void* stream);
-
-/*
- * Measurement aid, not part of the method: moves the memory traffic of a handoff without its
- * arithmetic, in the launch shape of the card kernels (one wave per unit, 128-bit accesses), so
- * that a benchmark can say what this memory system gives that traffic mix.  Unit u reads
- * reads_kib KiB at src + u * reads_kib KiB and writes writes_kib KiB at dst + u * writes_kib KiB;
- * every written word is the exclusive-or of the unit's 16-byte chunks that the writing lane read
- * (chunk k * 64 + lane, k = 0 .. reads_kib - 1, as four 32-bit words), plus the index of the write
- * (0 .. writes_kib - 1) in each word.
- *   reads_kib : writes_kib   8 : 2 (card creation at about 3 bits), 2 : 8 (injection), 8 : 8 (copy).
- *   nontemporal: bit 0 loads, bit 1 stores bypass the caches' keep policy.
- *   units_out:  host, may be NULL: the whole units that fit both buffers = units processed.
- * src_dev, dst_dev: device, 16-byte aligned, not overlapping.  Asynchronous on `stream`.
- * Errors: QKV_ERR_NULL, QKV_ERR_SHAPE (another mix or flag), QKV_ERR_ALIGN, QKV_ERR_OVERLAP, QKV_ERR_HIP.
- */
-int qkv_stream_probe(const void* src_dev, uint64_t src_bytes, void* dst_dev, uint64_t dst_bytes,
-                     int32_t reads_kib, int32_t writes_kib, int32_t nontemporal, uint64_t* units_out,
-                     void* stream);
 
 #ifdef __cplusplus
 }

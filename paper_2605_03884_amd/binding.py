@@ -100,6 +100,10 @@ def lib():
     L.qkv_budget_counts.argtypes = [ctypes.c_int64, ctypes.c_double, i64p]
     L.qkv_assign_bits.restype = ctypes.c_int
     L.qkv_assign_bits.argtypes = [vp, ctypes.c_int64, ctypes.c_double, vp, i64p, vp]
+    L.qkv_assign_plan.restype = ctypes.c_int
+    L.qkv_assign_plan.argtypes = [ctypes.POINTER(Desc), vp, ctypes.c_double, vp, i64p, vp, ctypes.c_uint64, vp]
+    L.qkv_assign_quantize_pack.restype = ctypes.c_int
+    L.qkv_assign_quantize_pack.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, ctypes.c_double, vp, i64p, vp, ctypes.c_uint64, vp]
     L.qkv_controller_scores.restype = ctypes.c_int
     L.qkv_controller_scores.argtypes = [vp, ctypes.c_int64, ctypes.POINTER(Controller), vp, vp]
     L.qkv_assign_bits_greedy.restype = ctypes.c_int
@@ -132,9 +136,6 @@ def lib():
                                 ctypes.POINTER(ctypes.c_uint32), vp]
     L.qkv_card_flags.restype = ctypes.c_int
     L.qkv_card_flags.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(ctypes.c_uint32), vp]
-    L.qkv_stream_probe.restype = ctypes.c_int
-    L.qkv_stream_probe.argtypes = [vp, ctypes.c_uint64, vp, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
-                                   ctypes.POINTER(ctypes.c_uint64), vp]
     _lib = L
     return L
 
@@ -194,6 +195,28 @@ def assign_bits(scores, avg_bits_budget, bits=None, stream=None):
     _check(lib().qkv_assign_bits(_dev_ptr(scores, torch.float32, "scores"), T, float(avg_bits_budget),
                                  _dev_ptr(bits, torch.uint8, "bits"), out, _stream(stream)), "qkv_assign_bits")
     return bits, list(out)
+
+
+def assign_plan(desc, scores, avg_bits_budget, card, bits=None, stream=None):
+    """scores: device float32[T]; card: device uint8 buffer (header, tables and pads are written); bits: device
+    uint8[T] or None.  Returns the class counts (list)."""
+    out = (ctypes.c_int64 * 4)()
+    bp = ctypes.c_void_p(0) if bits is None else _dev_ptr(bits, torch.uint8, "bits")
+    _check(lib().qkv_assign_plan(ctypes.byref(desc), _dev_ptr(scores, torch.float32, "scores"), float(avg_bits_budget), bp,
+                                 out, _dev_ptr(card, torch.uint8, "card"), card.numel(), _stream(stream)),
+           "qkv_assign_plan")
+    return list(out)
+
+
+def assign_quantize_pack(desc, k, v, scores, avg_bits_budget, card, bits=None, stream=None):
+    """Scores, budget and K/V in; widths (if bits is given) and the whole card out.  Returns the class counts."""
+    out = (ctypes.c_int64 * 4)()
+    bp = ctypes.c_void_p(0) if bits is None else _dev_ptr(bits, torch.uint8, "bits")
+    _check(lib().qkv_assign_quantize_pack(ctypes.byref(desc), _dev_ptr(k, torch.float16, "k"), _dev_ptr(v, torch.float16, "v"),
+                                          _dev_ptr(scores, torch.float32, "scores"), float(avg_bits_budget), bp, out,
+                                          _dev_ptr(card, torch.uint8, "card"), card.numel(), _stream(stream)),
+           "qkv_assign_quantize_pack")
+    return list(out)
 
 
 def controller_scores(features, params, scores=None, stream=None):
@@ -342,16 +365,6 @@ def card_attend(card, expect, q, softmax_scale, out, lse=None, workspace=None, s
                                  _dev_ptr(out, torch.float32, "out"), lp, _dev_ptr(workspace, torch.uint8, "workspace"),
                                  workspace.numel(), sp, _stream(stream)), "qkv_card_attend")
     return out, lse
-
-
-def stream_probe(src, dst, reads_kib, writes_kib, nontemporal=0, stream=None):
-    """Measurement aid: the traffic of a handoff without its arithmetic.  src, dst: device uint8 tensors.
-    Returns the number of units moved (reads_kib KiB read and writes_kib KiB written each)."""
-    units = ctypes.c_uint64(0)
-    _check(lib().qkv_stream_probe(_dev_ptr(src, torch.uint8, "src"), src.numel(), _dev_ptr(dst, torch.uint8, "dst"), dst.numel(),
-                                  int(reads_kib), int(writes_kib), int(nontemporal), ctypes.byref(units), _stream(stream)),
-           "qkv_stream_probe")
-    return units.value
 
 
 def card_flags(card, card_nbytes=None, stream=None):

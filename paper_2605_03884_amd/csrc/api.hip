@@ -237,8 +237,8 @@ int prepare_card(const qkv_desc_t* desc, const int64_t counts[4], const void* ca
   return QKV_OK;
 }
 
-int plan_card(const qkv_desc_t* desc, const uint8_t* bits_dev, const CardGeom& g, const uint64_t n[4], uint8_t* card,
-              hipStream_t s, uint32_t flags = 0) {
+// The header the host knows before the device has looked at anything (status 0).
+qkv_card_header_t make_header(const qkv_desc_t* desc, const CardGeom& g, const uint64_t n[4], uint32_t flags) {
   qkv_card_header_t h;
   std::memset(&h, 0, sizeof(h));
   static const uint8_t magic[8] = {'Q', 'K', 'V', 'C', 'A', 'R', 'D', 0};
@@ -262,7 +262,44 @@ int plan_card(const qkv_desc_t* desc, const uint8_t* bits_dev, const CardGeom& g
   h.avg_bits = (float)((double)code_bits / (double)h.tokens);   // achieved average bit width (Sec. 4.2.1)
   h.flags = flags;
   h.status = 0;
+  return h;
+}
+
+int plan_card(const qkv_desc_t* desc, const uint8_t* bits_dev, const CardGeom& g, const uint64_t n[4], uint8_t* card,
+              hipStream_t s, uint32_t flags = 0) {
+  const qkv_card_header_t h = make_header(desc, g, n, flags);
   return launch_classify(bits_dev, g, h, card, s) == hipSuccess ? QKV_OK : QKV_ERR_HIP;
+}
+
+// Scores and a budget to widths and a planned card, one launch.  `counts_out` gets the budget's class counts.
+int assign_and_plan(const qkv_desc_t* desc, const float* scores_dev, double avg_bits_budget, uint8_t* bits_dev,
+                    int64_t counts_out[4], void* card_dev, uint64_t card_capacity, CardGeom& g, hipStream_t s) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (desc->tokens >= (1ll << 31)) return QKV_ERR_SHAPE;
+  int64_t counts[4];
+  rc = counts_for_budget(desc->tokens, avg_bits_budget, counts);
+  if (rc) return rc;
+  if (reinterpret_cast<uintptr_t>(scores_dev) % 4 != 0) return QKV_ERR_ALIGN;
+  uint64_t n[4];
+  rc = prepare_card(desc, counts, card_dev, card_capacity, g, n);
+  if (rc) return rc;
+  const uint32_t cuts[3] = {(uint32_t)counts[3], (uint32_t)(counts[3] + counts[2]),
+                            (uint32_t)(counts[3] + counts[2] + counts[1])};
+  const qkv_card_header_t h = make_header(desc, g, n, 0u);
+  uint8_t* card = static_cast<uint8_t*>(card_dev);
+  if ((uint64_t)desc->tokens <= assign_plan_max_tokens()) {
+    if (launch_assign_plan(scores_dev, cuts, bits_dev, g, h, card, s) != hipSuccess) return QKV_ERR_HIP;
+  } else {
+    // Sequences beyond the one-launch kernel's reach: the allocator and the classification one after the
+    // other, same bytes.  Without a buffer from the caller the widths go straight to their place in the
+    // card, where the classification rewrites every byte with the value it read there.
+    uint8_t* widths = bits_dev ? bits_dev : card + g.off_bits;
+    if (launch_assign(scores_dev, (uint32_t)desc->tokens, cuts, widths, s) != hipSuccess) return QKV_ERR_HIP;
+    if (launch_classify(widths, g, h, card, s) != hipSuccess) return QKV_ERR_HIP;
+  }
+  std::memcpy(counts_out, counts, sizeof(counts));
+  return QKV_OK;
 }
 
 }  // namespace
@@ -275,6 +312,26 @@ int qkv_card_plan(const qkv_desc_t* desc, const uint8_t* bits_dev, const int64_t
   const int rc = prepare_card(desc, counts, card_dev, card_capacity, g, n);
   if (rc) return rc;
   return plan_card(desc, bits_dev, g, n, static_cast<uint8_t*>(card_dev), static_cast<hipStream_t>(stream));
+}
+
+int qkv_assign_plan(const qkv_desc_t* desc, const float* scores_dev, double avg_bits_budget, uint8_t* bits_dev,
+                    int64_t counts_out[4], void* card_dev, uint64_t card_capacity, void* stream) {
+  if (!desc || !scores_dev || !counts_out || !card_dev) return QKV_ERR_NULL;
+  CardGeom g;
+  return assign_and_plan(desc, scores_dev, avg_bits_budget, bits_dev, counts_out, card_dev, card_capacity, g,
+                         static_cast<hipStream_t>(stream));
+}
+
+int qkv_assign_quantize_pack(const qkv_desc_t* desc, const void* k_dev, const void* v_dev, const float* scores_dev,
+                             double avg_bits_budget, uint8_t* bits_dev, int64_t counts_out[4], void* card_dev,
+                             uint64_t card_capacity, void* stream) {
+  if (!desc || !k_dev || !v_dev || !scores_dev || !counts_out || !card_dev) return QKV_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(k_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(v_dev) % 16 != 0) return QKV_ERR_ALIGN;
+  CardGeom g;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int rc = assign_and_plan(desc, scores_dev, avg_bits_budget, bits_dev, counts_out, card_dev, card_capacity, g, s);
+  if (rc) return rc;
+  return launch_pack(g, k_dev, v_dev, static_cast<uint8_t*>(card_dev), false, s) == hipSuccess ? QKV_OK : QKV_ERR_HIP;
 }
 
 int qkv_card_fill(const qkv_desc_t* desc, const void* k_dev, const void* v_dev, const int64_t counts[4],
@@ -491,24 +548,6 @@ int qkv_card_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t*
                     static_cast<hipStream_t>(stream)) != hipSuccess)
     return QKV_ERR_HIP;
   return QKV_OK;
-}
-
-int qkv_stream_probe(const void* src_dev, uint64_t src_bytes, void* dst_dev, uint64_t dst_bytes, int32_t reads_kib,
-                     int32_t writes_kib, int32_t nontemporal, uint64_t* units_out, void* stream) {
-  if (!src_dev || !dst_dev) return QKV_ERR_NULL;
-  const bool known = (reads_kib == 8 && writes_kib == 2) || (reads_kib == 2 && writes_kib == 8) ||
-                     (reads_kib == 8 && writes_kib == 8);
-  if (!known || nontemporal < 0 || nontemporal > 3) return QKV_ERR_SHAPE;
-  if (reinterpret_cast<uintptr_t>(src_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(dst_dev) % 16 != 0) return QKV_ERR_ALIGN;
-  {
-    const uintptr_t s0 = reinterpret_cast<uintptr_t>(src_dev), d0 = reinterpret_cast<uintptr_t>(dst_dev);
-    if (s0 < d0 + dst_bytes && d0 < s0 + src_bytes) return QKV_ERR_OVERLAP;
-  }
-  const uint64_t units_r = src_bytes / ((uint64_t)reads_kib * 1024u), units_w = dst_bytes / ((uint64_t)writes_kib * 1024u);
-  const uint64_t units = units_r < units_w ? units_r : units_w;      // whole units that fit both buffers
-  if (units_out) *units_out = units;
-  return launch_stream_probe(src_dev, dst_dev, units, reads_kib, writes_kib, nontemporal, static_cast<hipStream_t>(stream)) ==
-                 hipSuccess ? QKV_OK : QKV_ERR_HIP;
 }
 
 namespace {

@@ -12,6 +12,7 @@
 // memory, which is why it is spread over several compute units instead of one.
 // Workgroup 0 also writes the header and zeroes the pad bytes of every section.
 #include "qkv_common.h"
+#include "qkv_plan.h"
 
 namespace qkv {
 namespace {
@@ -22,10 +23,6 @@ constexpr uint32_t kPerThread = 8;
 constexpr uint32_t kPerBlock = kThreads * kPerThread;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-// Class of a width: 4 -> 1, 8 -> 2, 16 -> 3, everything else 0 (2, and also invalid widths, which
-// are flagged in the header: order[] stays a permutation and every index stays in range).
-__device__ inline uint32_t class_of(uint32_t b) { return (b == 4) ? 1u : (b == 8) ? 2u : (b == 16) ? 3u : 0u; }
 
 // Number of bytes of w equal to the byte replicated in `pattern` (exact, no carries between bytes).
 __device__ inline uint32_t count_bytes_equal(uint64_t w, uint64_t pattern) {
@@ -66,8 +63,8 @@ __device__ inline void block_sums(uint32_t (&v)[N], uint32_t lane, uint32_t wave
 }
 
 __global__ __launch_bounds__(kThreads) void classify_kernel(const uint8_t* __restrict__ bits, CardGeom g,
-                                                           qkv_card_header_t header, uint8_t* __restrict__ card,
-                                                           bool aligned) {
+                                                           qkv_card_header_t header, PadTable pads,
+                                                           uint8_t* __restrict__ card, bool aligned) {
   __shared__ uint32_t sum_slots[7][kWaves];
   __shared__ uint32_t slots[kWaves];
   const uint32_t tid = threadIdx.x;
@@ -157,35 +154,10 @@ __global__ __launch_bounds__(kThreads) void classify_kernel(const uint8_t* __res
 
   if (blockIdx.x != 0) return;
 
-  // header: 64 dwords, the status word (dword 48) filled in from what the device saw
-  if (tid < 64) {
-    uint32_t status = (valid != T) ? QKV_STATUS_BAD_BITS : 0u;
-    if (tot0 != g.n[0] || tot1 != g.n[1] || tot2 != g.n[2] || tot3 != g.n[3]) status |= QKV_STATUS_BAD_COUNTS;
-    const uint32_t* h = reinterpret_cast<const uint32_t*>(&header);
-    uint32_t v = h[tid];
-    if (tid == 48) v = status;
-    reinterpret_cast<uint32_t*>(card)[tid] = v;
-  }
-
-  // pad bytes behind every section (each less than 256 bytes)
-  {
-    const uint64_t P = g.planes, D = g.head_dim, M = (uint64_t)(g.head_dim / g.group_size) * 4;
-    uint64_t start[10], used[10];
-    start[0] = g.off_bits;  used[0] = T;
-    start[1] = g.off_slot;  used[1] = 4ull * T;
-    start[2] = g.off_order; used[2] = 4ull * T;
-#pragma unroll
-    for (int c = 0; c < 3; ++c) {
-      start[3 + 2 * c] = g.off_codes[c]; used[3 + 2 * c] = P * g.n[c] * (D * width_of_class(c) / 8);
-      start[4 + 2 * c] = g.off_meta[c];  used[4 + 2 * c] = P * g.n[c] * M;
-    }
-    start[9] = g.off_fp16; used[9] = P * g.n[3] * D * 2;
-#pragma unroll
-    for (int s = 0; s < 10; ++s) {
-      const uint64_t pad = align256(used[s]) - used[s];
-      if (tid < pad) card[start[s] + used[s] + tid] = 0;
-    }
-  }
+  // header (the status word filled in from what the device saw) and the pad bytes behind every section
+  uint32_t status = (valid != T) ? QKV_STATUS_BAD_BITS : 0u;
+  if (tot0 != g.n[0] || tot1 != g.n[1] || tot2 != g.n[2] || tot3 != g.n[3]) status |= QKV_STATUS_BAD_COUNTS;
+  write_header_and_pads(card, header, pads, status, tid);
 }
 
 }  // namespace
@@ -194,7 +166,7 @@ hipError_t launch_classify(const uint8_t* bits, const CardGeom& geom, const qkv_
                            uint8_t* card, hipStream_t stream) {
   const bool aligned = reinterpret_cast<uintptr_t>(bits) % 8 == 0;
   const uint32_t blocks = (geom.tokens + kPerBlock - 1) / kPerBlock;
-  hipLaunchKernelGGL(classify_kernel, dim3(blocks), dim3(kThreads), 0, stream, bits, geom, header, card, aligned);
+  hipLaunchKernelGGL(classify_kernel, dim3(blocks), dim3(kThreads), 0, stream, bits, geom, header, make_pad_table(geom), card, aligned);
   return hipGetLastError();
 }
 

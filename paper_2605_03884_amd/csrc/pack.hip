@@ -42,9 +42,11 @@ __device__ inline uint32_t swizzle(uint32_t q) { return q ^ ((q >> 3) & 3u); }
 
 // ---- rows of a tile -------------------------------------------------------------------------
 
-// Address of the fp16 row that row `lane` of the tile is made from, 0 past the segment's end.
+// Address of the fp16 row that row `lane` of the tile is made from; 0 past the segment's end and
+// for an order[] entry that names no token (the row then reads as zeros and `bad` is raised): the
+// table lives in the caller's card buffer, so it is bounded like any other untrusted input.
 __device__ inline uint64_t tile_row_address(const PackArgs& a, int c, uint32_t r0, uint32_t n_rows, uint32_t lane,
-                                            uint32_t tile_rows) {
+                                            uint32_t tile_rows, uint32_t& bad) {
   const CardGeom& g = a.g;
   uint64_t addr = 0;
   const uint32_t r = r0 + lane;
@@ -56,8 +58,12 @@ __device__ inline uint64_t tile_row_address(const PackArgs& a, int c, uint32_t r
     const uint32_t lh = g.planes >> 1;
     const uint32_t row_bytes = g.head_dim * 2u;
     // V rows continue the plane numbering after K's; each address stays inside its own tensor
-    addr = (p < lh) ? reinterpret_cast<uint64_t>(a.k) + ((uint64_t)p * g.tokens + t) * row_bytes
-                    : reinterpret_cast<uint64_t>(a.v) + ((uint64_t)(p - lh) * g.tokens + t) * row_bytes;
+    if (t < g.tokens) {
+      addr = (p < lh) ? reinterpret_cast<uint64_t>(a.k) + ((uint64_t)p * g.tokens + t) * row_bytes
+                      : reinterpret_cast<uint64_t>(a.v) + ((uint64_t)(p - lh) * g.tokens + t) * row_bytes;
+    } else {
+      bad = 1;
+    }
   }
   return addr;
 }
@@ -79,14 +85,15 @@ __device__ inline void load_tile(uint64_t my_row_addr, uint32_t lane, uint32_t l
 // ---- one span of 32 values --------------------------------------------------------------------
 
 template <int W, int G, bool KEEP>
-__device__ inline void pack_tile(const PackArgs& a, int c, uint32_t r0, uint32_t n_rows, uint32_t lane, u32x4* lds) {
+__device__ inline void pack_tile(const PackArgs& a, int c, uint32_t r0, uint32_t n_rows, uint32_t lane, u32x4* lds,
+                                 uint32_t& bad) {
   constexpr int GS = G / 32;                     // spans (lanes) per group
   const CardGeom& g = a.g;
   const uint32_t lpr_shift = g.lpr_shift;
   const uint32_t tile_rows = kTileChunks >> lpr_shift;
   const uint32_t spr_shift = lpr_shift - 2;      // log2(spans per row)
 
-  const uint64_t my_row = tile_row_address(a, c, r0, n_rows, lane, tile_rows);
+  const uint64_t my_row = tile_row_address(a, c, r0, n_rows, lane, tile_rows, bad);
   u32x4 data[kTileIters];
   load_tile(my_row, lane, lpr_shift, data);
   const uint32_t wslot = swizzle(lane);
@@ -131,11 +138,11 @@ __device__ inline void pack_tile(const PackArgs& a, int c, uint32_t r0, uint32_t
 // whole blocks of 32 tokens.
 template <int W, bool KEEP>
 __device__ inline void pack_tile_kc(const PackArgs& a, int c, uint32_t r0, uint32_t n_rows, uint32_t key_rows,
-                                    uint32_t lane, u32x4* lds) {
+                                    uint32_t lane, u32x4* lds, uint32_t& bad) {
   const CardGeom& g = a.g;
   const uint32_t lpr_shift = g.lpr_shift;
   const uint32_t tile_rows = kTileChunks >> lpr_shift;
-  const uint64_t my_row = tile_row_address(a, c, r0, n_rows, lane, tile_rows);
+  const uint64_t my_row = tile_row_address(a, c, r0, n_rows, lane, tile_rows, bad);
   u32x4 data[kTileIters];
   load_tile(my_row, lane, lpr_shift, data);
   const uint32_t wslot = swizzle(lane);
@@ -175,12 +182,12 @@ __device__ inline void pack_tile_kc(const PackArgs& a, int c, uint32_t r0, uint3
 }
 
 template <bool KEEP>
-__device__ inline void copy_tile(const PackArgs& a, uint32_t r0, uint32_t n_rows, uint32_t lane) {
+__device__ inline void copy_tile(const PackArgs& a, uint32_t r0, uint32_t n_rows, uint32_t lane, uint32_t& bad) {
   const CardGeom& g = a.g;
   const uint32_t lpr_shift = g.lpr_shift;
   const uint32_t tile_rows = kTileChunks >> lpr_shift;
   const uint32_t row_bytes = g.head_dim * 2u;
-  const uint64_t my_row = tile_row_address(a, 3, r0, n_rows, lane, tile_rows);
+  const uint64_t my_row = tile_row_address(a, 3, r0, n_rows, lane, tile_rows, bad);
   u32x4 data[kTileIters];
   load_tile(my_row, lane, lpr_shift, data);
   uint8_t* dst = a.card + g.off_fp16 + (uint64_t)r0 * row_bytes;
@@ -205,6 +212,7 @@ __global__ __launch_bounds__(kBlockThreads) void pack_kernel(PackArgs a) {
   const uint32_t tile_rows = kTileChunks >> a.g.lpr_shift;
   u32x4* my_lds = lds[wave];
 
+  uint32_t bad = 0;   // an order[] entry past the last token was met
   uint32_t cum = 0;   // tiles of the classes already done, modulo n_waves
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
@@ -215,18 +223,20 @@ __global__ __launch_bounds__(kBlockThreads) void pack_kernel(PackArgs a) {
     for (uint32_t i = first; i < tiles; i += n_waves) {
       const uint32_t r0 = i * tile_rows;
       if (KC && c < 3 && r0 < (n_rows >> 1)) {                 // key rows: the host made sure no tile straddles the halves
-        if (c == 0) pack_tile_kc<2, KEEP>(a, 0, r0, n_rows, n_rows >> 1, lane, my_lds);
-        if (c == 1) pack_tile_kc<4, KEEP>(a, 1, r0, n_rows, n_rows >> 1, lane, my_lds);
-        if (c == 2) pack_tile_kc<8, KEEP>(a, 2, r0, n_rows, n_rows >> 1, lane, my_lds);
+        if (c == 0) pack_tile_kc<2, KEEP>(a, 0, r0, n_rows, n_rows >> 1, lane, my_lds, bad);
+        if (c == 1) pack_tile_kc<4, KEEP>(a, 1, r0, n_rows, n_rows >> 1, lane, my_lds, bad);
+        if (c == 2) pack_tile_kc<8, KEEP>(a, 2, r0, n_rows, n_rows >> 1, lane, my_lds, bad);
         continue;
       }
-      if (c == 0) pack_tile<2, G, KEEP>(a, 0, r0, n_rows, lane, my_lds);
-      if (c == 1) pack_tile<4, G, KEEP>(a, 1, r0, n_rows, lane, my_lds);
-      if (c == 2) pack_tile<8, G, KEEP>(a, 2, r0, n_rows, lane, my_lds);
-      if (c == 3) copy_tile<KEEP>(a, r0, n_rows, lane);
+      if (c == 0) pack_tile<2, G, KEEP>(a, 0, r0, n_rows, lane, my_lds, bad);
+      if (c == 1) pack_tile<4, G, KEEP>(a, 1, r0, n_rows, lane, my_lds, bad);
+      if (c == 2) pack_tile<8, G, KEEP>(a, 2, r0, n_rows, lane, my_lds, bad);
+      if (c == 3) copy_tile<KEEP>(a, r0, n_rows, lane, bad);
     }
     cum = (cum + tiles) % n_waves;
   }
+  // the header's status word (byte 192); the planning kernel wrote it earlier on the same stream
+  if (bad) atomicOr(reinterpret_cast<uint32_t*>(a.card + 192), QKV_STATUS_BAD_ORDER);
 }
 
 }  // namespace

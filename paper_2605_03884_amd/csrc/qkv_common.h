@@ -110,20 +110,32 @@ __device__ inline uint32_t wave_inclusive_scan(uint32_t v) {
 }
 
 // One wave finds the bucket that holds rank `left` in a 256-bucket histogram: the first d
-// whose cumulative count exceeds `left`.  Returns d and lowers `left` by the count before it.
-// The histogram's total must exceed `left`.
-__device__ inline uint32_t find_bucket(const uint32_t* hist, uint32_t lane, uint32_t& left) {
+// whose cumulative count exceeds `left`.  Returns d, lowers `left` by the count before it and
+// gives that bucket's own count in `in_bucket`.  The histogram's total must exceed `left`.
+__device__ inline uint32_t find_bucket(const uint32_t* hist, uint32_t lane, uint32_t& left, uint32_t& in_bucket) {
   const uint32_t h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
   const uint32_t inc = wave_inclusive_scan(h0 + h1 + h2 + h3);
   const uint64_t over = __builtin_amdgcn_ballot_w64(inc > left);
-  const uint32_t owner = (uint32_t)__builtin_ctzll(over | (1ull << 63));
-  const uint32_t before = __shfl(inc - (h0 + h1 + h2 + h3), owner, 64);
-  const uint32_t a0 = __shfl(h0, owner, 64), a1 = __shfl(h1, owner, 64), a2 = __shfl(h2, owner, 64);
+  const int owner = (int)__builtin_ctzll(over | (1ull << 63));        // the same in every lane: plain lane reads
+  const uint32_t before = (uint32_t)__builtin_amdgcn_readlane((int)(inc - (h0 + h1 + h2 + h3)), owner);
+  const uint32_t a0 = (uint32_t)__builtin_amdgcn_readlane((int)h0, owner), a1 = (uint32_t)__builtin_amdgcn_readlane((int)h1, owner),
+                 a2 = (uint32_t)__builtin_amdgcn_readlane((int)h2, owner), a3 = (uint32_t)__builtin_amdgcn_readlane((int)h3, owner);
   uint32_t rest = left - before;
-  uint32_t d = 4 * owner;
-  if (rest >= a0) { rest -= a0; ++d; if (rest >= a1) { rest -= a1; ++d; if (rest >= a2) { rest -= a2; ++d; } } }
+  uint32_t d = 4u * (uint32_t)owner;
+  in_bucket = a0;
+  if (rest >= a0) {
+    rest -= a0; ++d; in_bucket = a1;
+    if (rest >= a1) {
+      rest -= a1; ++d; in_bucket = a2;
+      if (rest >= a2) { rest -= a2; ++d; in_bucket = a3; }
+    }
+  }
   left = rest;
   return d;
+}
+__device__ inline uint32_t find_bucket(const uint32_t* hist, uint32_t lane, uint32_t& left) {
+  uint32_t in_bucket;
+  return find_bucket(hist, lane, left, in_bucket);
 }
 
 // Number of workgroups for a streaming kernel with `tiles` wave-tiles of work.
@@ -144,6 +156,9 @@ hipError_t launch_requant(const uint8_t* card_in, uint64_t card_in_bytes, const 
                           uint32_t* status, hipStream_t stream);
 hipError_t launch_assign(const float* scores, uint32_t tokens, const uint32_t cuts[3], uint8_t* bits,
                          hipStream_t stream);
+uint32_t assign_plan_max_tokens();      // longest sequence launch_assign_plan takes
+hipError_t launch_assign_plan(const float* scores, const uint32_t cuts[3], uint8_t* bits, const CardGeom& geom,
+                              const qkv_card_header_t& header, uint8_t* card, hipStream_t stream);
 void attend_plan(uint64_t tokens, uint32_t rep, uint64_t pairs, uint32_t* chunk, uint32_t* max_tasks);
 hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeom& expect, const void* q,
                          uint32_t q_heads, float softmax_scale, float* out, float* lse, float* workspace,
@@ -151,8 +166,6 @@ hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeo
 hipError_t launch_count(const uint8_t* bits, uint64_t tokens, unsigned long long* counts4, hipStream_t stream);
 hipError_t launch_controller(const float* features, uint32_t tokens, const qkv_controller_t& params, float* scores,
                              hipStream_t stream);
-hipError_t launch_stream_probe(const void* src, void* dst, uint64_t units, int reads_kib, int writes_kib, int nontemporal,
-                               hipStream_t stream);
 hipError_t launch_greedy(const float* scores, uint32_t tokens, uint32_t spare_units, uint8_t* bits,
                          unsigned long long* counts4, hipStream_t stream);
 

@@ -109,7 +109,9 @@ def test_argument_errors_are_reported_before_any_gpu_work():
     assert L.qkv_assign_bits(None, 64, 4.0, None, c, None) == -1
     assert L.qkv_count_bits(None, 64, c, None) == -1
     assert L.qkv_card_peek(None, 0, None, None, None, None, None) == -1
-    assert L.qkv_stream_probe(None, 0, None, 0, 8, 2, 0, None, None) == -1
+    assert L.qkv_assign_plan(ctypes.byref(d), None, 4.0, None, c, None, 0, None) == -1
+    assert L.qkv_assign_quantize_pack(ctypes.byref(d), None, None, None, 4.0, None, c, None, 0, None) == -1
+    assert not hasattr(L, "qkv_stream_probe")          # the measurement aid lives in its own library
     fl = ctypes.c_uint32(0)
     assert L.qkv_card_flags(None, 0, ctypes.byref(fl), None) == -1 and L.qkv_card_flags(None, 0, None, None) == -1
     assert L.qkv_card_attend(None, 0, ctypes.byref(d), None, 8, ctypes.c_float(1.0), None, None, None, 0, None, None) == -1

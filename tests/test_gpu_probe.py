@@ -1,4 +1,4 @@
-"""The stream probe (a measurement aid: a handoff's memory traffic without its arithmetic) moves exactly the bytes
+"""The stream probe (bench_probe/, a measurement aid for bench.py outside the product library: a handoff's memory traffic without its arithmetic) moves exactly the bytes
 it says: every written word against the exclusive-or definition in numpy, ragged buffer sizes, nothing written
 past the last whole unit, host-side refusals."""
 import ctypes
@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 import torch
 
-import paper_2605_03884_amd as qkv
+import bench_probe
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -30,7 +30,7 @@ def test_probe_moves_what_it_says(reads, writes, nontemporal):
     dst_bytes = units * writes * 1024 + writes * 1024 + 112              # room for one more unit than the source has
     canary = 0xA5
     dst = torch.full((dst_bytes,), canary, dtype=torch.uint8, device=DEV)
-    got_units = qkv.stream_probe(torch.from_numpy(src).to(DEV), dst, reads, writes, nontemporal)
+    got_units = bench_probe.stream_probe(torch.from_numpy(src).to(DEV), dst, reads, writes, nontemporal)
     torch.cuda.synchronize()
     assert got_units == units
     out = dst.cpu().numpy()
@@ -41,15 +41,15 @@ def test_probe_moves_what_it_says(reads, writes, nontemporal):
 def test_probe_limited_by_the_destination_and_empty():
     src = torch.zeros(64 * 8 * 1024, dtype=torch.uint8, device=DEV)
     dst = torch.full((5 * 2 * 1024 + 100,), 7, dtype=torch.uint8, device=DEV)
-    assert qkv.stream_probe(src, dst, 8, 2) == 5
+    assert bench_probe.stream_probe(src, dst, 8, 2) == 5
     torch.cuda.synchronize()
     out = dst.cpu().numpy()
     assert np.array_equal(out[:5 * 2048], expected(np.zeros(5 * 8192, dtype=np.uint8), 5, 8, 2)) and np.all(out[5 * 2048:] == 7)
-    assert qkv.stream_probe(src[:100], dst, 8, 2) == 0                     # not one whole unit: nothing launched
+    assert bench_probe.stream_probe(src[:100], dst, 8, 2) == 0                     # not one whole unit: nothing launched
 
 
 def test_probe_host_errors():
-    L = qkv.lib()
+    L = bench_probe.lib()
     buf = torch.zeros(1 << 16, dtype=torch.uint8, device=DEV)
     other = torch.zeros(1 << 16, dtype=torch.uint8, device=DEV)
     n = ctypes.c_uint64(0)
