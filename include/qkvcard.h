@@ -429,6 +429,27 @@ int qkv_card_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t*
                     uint32_t* status_dev, void* stream);
 
 /*
+ * qkv_card_attend for callers that cannot allocate device memory - code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc: the same kernels, the same results bit for
+ * bit, with the partials kept in a fixed array inside the library instead of a caller's workspace.
+ * Arguments as for qkv_card_attend, without the workspace.  The call allocates and frees nothing.
+ *   - The array holds QKV_ATTEND_STATIC_SCRATCH_BYTES per GPU the library runs on, from the first
+ *     call on that GPU until the process ends.  A shape whose qkv_card_attend_workspace() exceeds it
+ *     is refused with QKV_ERR_CAPACITY (the Llama-3.1-8B shape at 8192 tokens with 32 query heads
+ *     needs 13.3 MB; at 32768 tokens use qkv_card_attend with a workspace).
+ *   - All calls on one GPU share the array: two calls that overlap in time on the same GPU (on
+ *     different streams, or from different threads) race and give wrong results.  Calls on one
+ *     stream are ordered by the stream.  Nothing in the array needs clearing between calls: every
+ *     partial a call reads it has written itself.
+ *   - The first call on a GPU looks the array's device address up with the runtime; make that
+ *     first call outside a graph capture.
+ */
+#define QKV_ATTEND_STATIC_SCRATCH_BYTES (16u << 20)
+int qkv_card_attend_static(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect,
+                           const void* q_dev, int32_t q_heads, float softmax_scale,
+                           float* out_dev, float* lse_dev, uint32_t* status_dev, void* stream);
+
+/*
  * Read a card's header back to the host and validate it (magic, version, shape
  * domain, counts summing to tokens, section offsets equal to the closed form,
  * total_bytes <= card_bytes).  Any out pointer may be NULL.  SYNCHRONISES `stream`.

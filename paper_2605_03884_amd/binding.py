@@ -131,6 +131,9 @@ def lib():
     L.qkv_card_attend.restype = ctypes.c_int
     L.qkv_card_attend.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, ctypes.c_int32, ctypes.c_float, vp, vp,
                                   vp, ctypes.c_uint64, vp, vp]
+    L.qkv_card_attend_static.restype = ctypes.c_int
+    L.qkv_card_attend_static.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, ctypes.c_int32, ctypes.c_float, vp, vp,
+                                         vp, vp]
     L.qkv_card_peek.restype = ctypes.c_int
     L.qkv_card_peek.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), i64p, ctypes.POINTER(ctypes.c_float),
                                 ctypes.POINTER(ctypes.c_uint32), vp]
@@ -364,6 +367,17 @@ def card_attend(card, expect, q, softmax_scale, out, lse=None, workspace=None, s
                                  _dev_ptr(q, torch.float16, "q"), int(q_heads), float(softmax_scale),
                                  _dev_ptr(out, torch.float32, "out"), lp, _dev_ptr(workspace, torch.uint8, "workspace"),
                                  workspace.numel(), sp, _stream(stream)), "qkv_card_attend")
+    return out, lse
+
+
+def card_attend_static(card, expect, q, softmax_scale, out, lse=None, status=None, card_nbytes=None, stream=None):
+    """card_attend without a workspace: the partials live in the library's fixed scratch array (no allocation)."""
+    n = card.numel() if card_nbytes is None else int(card_nbytes)
+    lp = ctypes.c_void_p(0) if lse is None else _dev_ptr(lse, torch.float32, "lse")
+    sp = ctypes.c_void_p(0) if status is None else _dev_ptr(status, None, "status")
+    _check(lib().qkv_card_attend_static(_dev_ptr(card, torch.uint8, "card"), n, ctypes.byref(expect),
+                                        _dev_ptr(q, torch.float16, "q"), int(q.shape[1]), float(softmax_scale),
+                                        _dev_ptr(out, torch.float32, "out"), lp, sp, _stream(stream)), "qkv_card_attend_static")
     return out, lse
 
 

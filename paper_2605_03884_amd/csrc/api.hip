@@ -224,7 +224,7 @@ int qkv_count_bits(const uint8_t* bits_dev, int64_t tokens, int64_t counts_out[4
 namespace {
 
 // Checks shared by the card-building calls; fills the geometry.
-int prepare_card(const qkv_desc_t* desc, const int64_t counts[4], const void* card_dev, uint64_t card_capacity,
+static int prepare_card(const qkv_desc_t* desc, const int64_t counts[4], const void* card_dev, uint64_t card_capacity,
                  CardGeom& g, uint64_t n[4]) {
   int rc = check_desc(desc);
   if (rc) return rc;
@@ -238,7 +238,7 @@ int prepare_card(const qkv_desc_t* desc, const int64_t counts[4], const void* ca
 }
 
 // The header the host knows before the device has looked at anything (status 0).
-qkv_card_header_t make_header(const qkv_desc_t* desc, const CardGeom& g, const uint64_t n[4], uint32_t flags) {
+static qkv_card_header_t make_header(const qkv_desc_t* desc, const CardGeom& g, const uint64_t n[4], uint32_t flags) {
   qkv_card_header_t h;
   std::memset(&h, 0, sizeof(h));
   static const uint8_t magic[8] = {'Q', 'K', 'V', 'C', 'A', 'R', 'D', 0};
@@ -265,14 +265,14 @@ qkv_card_header_t make_header(const qkv_desc_t* desc, const CardGeom& g, const u
   return h;
 }
 
-int plan_card(const qkv_desc_t* desc, const uint8_t* bits_dev, const CardGeom& g, const uint64_t n[4], uint8_t* card,
+static int plan_card(const qkv_desc_t* desc, const uint8_t* bits_dev, const CardGeom& g, const uint64_t n[4], uint8_t* card,
               hipStream_t s, uint32_t flags = 0) {
   const qkv_card_header_t h = make_header(desc, g, n, flags);
   return launch_classify(bits_dev, g, h, card, s) == hipSuccess ? QKV_OK : QKV_ERR_HIP;
 }
 
 // Scores and a budget to widths and a planned card, one launch.  `counts_out` gets the budget's class counts.
-int assign_and_plan(const qkv_desc_t* desc, const float* scores_dev, double avg_bits_budget, uint8_t* bits_dev,
+static int assign_and_plan(const qkv_desc_t* desc, const float* scores_dev, double avg_bits_budget, uint8_t* bits_dev,
                     int64_t counts_out[4], void* card_dev, uint64_t card_capacity, CardGeom& g, hipStream_t s) {
   int rc = check_desc(desc);
   if (rc) return rc;
@@ -388,7 +388,7 @@ int qkv_requantize(const void* card_in_dev, uint64_t card_in_bytes, const qkv_de
 
 namespace {
 // Shapes the per-channel key tiles are written for.
-int check_keys_per_channel(const qkv_desc_t* d) {
+static int check_keys_per_channel(const qkv_desc_t* d) {
   if (d->group_size != 32 || (d->head_dim != 64 && d->head_dim != 128)) return QKV_ERR_SHAPE;
   if (d->tokens % (d->head_dim == 64 ? 64 : 32) != 0) return QKV_ERR_SHAPE;
   return QKV_OK;
@@ -415,7 +415,7 @@ int qkv_quantize_pack_kc(const qkv_desc_t* desc, const void* k_dev, const void* 
 }
 
 namespace {
-int unpack_any(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, void* k_out_dev, void* v_out_dev,
+static int unpack_any(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, void* k_out_dev, void* v_out_dev,
                uint32_t* status_dev, bool keys_per_channel, void* stream) {
   if (!card_dev || !expect || !k_out_dev || !v_out_dev) return QKV_ERR_NULL;
   int rc = check_desc(expect);
@@ -504,7 +504,7 @@ int qkv_inject_layers(const void* card_dev, uint64_t card_bytes, const qkv_desc_
 
 namespace {
 // Shape rules of the fused attention path and the floats of workspace it needs.
-int attend_workspace_floats(const qkv_desc_t* expect, int32_t q_heads, uint64_t* floats) {
+static int attend_workspace_floats(const qkv_desc_t* expect, int32_t q_heads, uint64_t* floats) {
   const int rc = check_desc(expect);
   if (rc) return rc;
   if (expect->head_dim != 128) return QKV_ERR_SHAPE;
@@ -527,22 +527,37 @@ int qkv_card_attend_workspace(const qkv_desc_t* expect, int32_t q_heads, uint64_
   return QKV_OK;
 }
 
-int qkv_card_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, const void* q_dev,
-                    int32_t q_heads, float softmax_scale, float* out_dev, float* lse_dev, void* workspace_dev,
-                    uint64_t workspace_bytes, uint32_t* status_dev, void* stream) {
-  if (!card_dev || !expect || !q_dev || !out_dev || !workspace_dev) return QKV_ERR_NULL;
-  uint64_t floats = 0;
+namespace {
+// Checks of both attention entry points; fills the geometry the kernels validate the header against and
+// the floats of scratch the launch needs.
+static int prepare_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, const void* q_dev, int32_t q_heads,
+                   float softmax_scale, const float* out_dev, const float* lse_dev, const uint32_t* status_dev, CardGeom& g,
+                   uint64_t& floats) {
+  if (!card_dev || !expect || !q_dev || !out_dev) return QKV_ERR_NULL;
   const int rc = attend_workspace_floats(expect, q_heads, &floats);
   if (rc) return rc;
   if (!std::isfinite(softmax_scale)) return QKV_ERR_SHAPE;
-  if (card_bytes < QKV_CARD_HEADER_BYTES || workspace_bytes < floats * sizeof(float)) return QKV_ERR_CAPACITY;
+  if (card_bytes < QKV_CARD_HEADER_BYTES) return QKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(card_dev) % QKV_CARD_ALIGN != 0 || reinterpret_cast<uintptr_t>(q_dev) % 16 != 0 ||
       reinterpret_cast<uintptr_t>(out_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(lse_dev) % 4 != 0 ||
-      reinterpret_cast<uintptr_t>(workspace_dev) % 16 != 0 || reinterpret_cast<uintptr_t>(status_dev) % 4 != 0)
+      reinterpret_cast<uintptr_t>(status_dev) % 4 != 0)
     return QKV_ERR_ALIGN;
   const uint64_t zero[4] = {0, 0, 0, (uint64_t)expect->tokens};
-  CardGeom g;
   build_geom(g, expect->layers, expect->kv_heads, expect->head_dim, expect->group_size, expect->tokens, zero);
+  return QKV_OK;
+}
+}  // namespace
+
+int qkv_card_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, const void* q_dev,
+                    int32_t q_heads, float softmax_scale, float* out_dev, float* lse_dev, void* workspace_dev,
+                    uint64_t workspace_bytes, uint32_t* status_dev, void* stream) {
+  if (!workspace_dev) return QKV_ERR_NULL;
+  CardGeom g;
+  uint64_t floats = 0;
+  const int rc = prepare_attend(card_dev, card_bytes, expect, q_dev, q_heads, softmax_scale, out_dev, lse_dev, status_dev, g, floats);
+  if (rc) return rc;
+  if (workspace_bytes < floats * sizeof(float)) return QKV_ERR_CAPACITY;
+  if (reinterpret_cast<uintptr_t>(workspace_dev) % 16 != 0) return QKV_ERR_ALIGN;
   if (launch_attend(static_cast<const uint8_t*>(card_dev), card_bytes, g, q_dev, (uint32_t)q_heads, softmax_scale,
                     out_dev, lse_dev, static_cast<float*>(workspace_dev), status_dev,
                     static_cast<hipStream_t>(stream)) != hipSuccess)
@@ -550,9 +565,25 @@ int qkv_card_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t*
   return QKV_OK;
 }
 
+int qkv_card_attend_static(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, const void* q_dev,
+                           int32_t q_heads, float softmax_scale, float* out_dev, float* lse_dev, uint32_t* status_dev,
+                           void* stream) {
+  CardGeom g;
+  uint64_t floats = 0;
+  const int rc = prepare_attend(card_dev, card_bytes, expect, q_dev, q_heads, softmax_scale, out_dev, lse_dev, status_dev, g, floats);
+  if (rc) return rc;
+  if (floats * sizeof(float) > (uint64_t)QKV_ATTEND_STATIC_SCRATCH_BYTES) return QKV_ERR_CAPACITY;   // shape beyond the fixed scratch
+  float* scratch_at = nullptr;
+  if (attend_static_scratch(&scratch_at) != hipSuccess) return QKV_ERR_HIP;
+  if (launch_attend(static_cast<const uint8_t*>(card_dev), card_bytes, g, q_dev, (uint32_t)q_heads, softmax_scale,
+                    out_dev, lse_dev, scratch_at, status_dev, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return QKV_ERR_HIP;
+  return QKV_OK;
+}
+
 namespace {
 // Copies a card's header to the host (synchronising the stream) and validates it.
-int fetch_header(const void* card_dev, uint64_t card_bytes, void* stream, qkv_card_header_t& h) {
+static int fetch_header(const void* card_dev, uint64_t card_bytes, void* stream, qkv_card_header_t& h) {
   if (!card_dev) return QKV_ERR_NULL;
   if (card_bytes < QKV_CARD_HEADER_BYTES) return QKV_ERR_FORMAT;
   hipStream_t s = static_cast<hipStream_t>(stream);

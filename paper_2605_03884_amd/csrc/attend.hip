@@ -28,6 +28,8 @@
 // 1 (at 2 / 4 / 8 / 16 bits) without a branch in between; rounds past a task's end see zeros and
 // count as -inf.  114 registers and 10 KiB of LDS per wave: four waves per SIMD.
 
+#include <atomic>
+
 #include "qkv_common.h"
 #include "qkv_decode.h"
 
@@ -566,6 +568,37 @@ void attend_plan(uint64_t tokens, uint32_t rep, uint64_t pairs, uint32_t* chunk,
   while (c > 192u && pairs * ((tokens + c - 1) / c + 2u) < slots) c -= 192u;
   *chunk = c;
   *max_tasks = (uint32_t)((tokens + *chunk - 1) / *chunk) + 3u;   // every class may end with a partly filled task
+}
+
+// ---- scratch for callers that cannot allocate -------------------------------------------------
+//
+// qkv_card_attend_static keeps the partials in this array instead of a caller's workspace.  Every
+// GPU the library runs on holds its own copy, at its own address, until the process ends.  In host
+// code the array's name is only a handle for the runtime: the device address comes from
+// hipGetSymbolAddress, once per device, and that address is what kernels and copies are given.
+namespace {
+constexpr uint64_t kStaticScratchBytes = QKV_ATTEND_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) float scratch[kStaticScratchBytes / sizeof(float)];
+std::atomic<float*> g_scratch_at[64];        // per device ordinal, null = not looked up yet
+}  // namespace
+
+// The current device's copy of the scratch array.  Looks the address up on the first call per device.
+hipError_t attend_static_scratch(float** ptr) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  float* p = g_scratch_at[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    void* at = nullptr;
+    e = hipGetSymbolAddress(&at, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (at == nullptr) return hipErrorInvalidSymbol;
+    p = static_cast<float*>(at);
+    g_scratch_at[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  return hipSuccess;
 }
 
 hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeom& expect, const void* q,
