@@ -582,14 +582,21 @@ static void unpack_per_token(const uint8_t* card, const Layout& lay, const RefDe
   }
 }
 
-// Checks the bits / slot tables of a parsed card before they are used as indices.
+// Checks the three tables of a parsed card before they are used as indices: every width valid, slot[t] the
+// rank of t among the tokens of its width, the class counts those of the header, and order[] the inverse of
+// slot[] (entry base_c + slot[t] names t).  A card whose tables disagree anywhere is refused as a whole.
 static int validate_tables(const uint8_t* card, const Layout& lay, const RefDesc& d, const int64_t counts[4]) {
   const uint8_t* bits = card + lay.off_bits;
+  int64_t base[4];
+  base[0] = 0;
+  for (int c = 1; c < 4; ++c) base[c] = base[c - 1] + counts[c - 1];
   int64_t seen[4] = {0, 0, 0, 0};
   for (int64_t t = 0; t < d.tokens; ++t) {
     const int c = class_of_width(bits[t]);
     if (c < 0) return kErrFormat;
     if ((int64_t)get_u32(card + lay.off_slot + 4 * (uint64_t)t) != seen[c]) return kErrFormat;
+    if (seen[c] >= counts[c]) return kErrFormat;
+    if ((int64_t)get_u32(card + lay.off_order + 4 * (uint64_t)(base[c] + seen[c])) != t) return kErrFormat;
     seen[c] += 1;
   }
   for (int c = 0; c < 4; ++c) if (seen[c] != counts[c]) return kErrFormat;

@@ -60,6 +60,16 @@ typedef __attribute__((address_space(1))) u32x4 global_u32x4;
 // LDS position (in 16-byte units) of output chunk q of a tile.
 __device__ inline uint32_t swizzle(uint32_t q) { return q ^ ((q >> 3) & 3u); }
 
+// The card's three tables must tell one story: entry j of class c's part of order[] names token t only if
+// bits[t] is that class's width and slot[t] is j.  Then no token is named twice, so every output row is
+// written exactly once; an entry that fails is skipped and reported like one that names no token at all.
+// (t < tokens has been checked; the two look-ups hit tables of a few KiB that stay in cache.)
+__device__ inline bool tables_agree(const uint8_t* card, const CardGeom& g, int c, uint32_t j, uint32_t t) {
+  const uint32_t width = card[g.off_bits + t];
+  const uint32_t slot = reinterpret_cast<const uint32_t*>(card + g.off_slot)[t];
+  return width == width_of_class(c) && slot == j;
+}
+
 // Address of the output row that row `lane` of the tile starting at segment row r0 goes to;
 // 0 for rows past the segment's end and for corrupt order[] entries.
 __device__ inline uint64_t tile_row_address(const UnpackArgs& a, const CardGeom& g, int c, uint32_t r0, uint32_t n_rows,
@@ -73,7 +83,7 @@ __device__ inline uint64_t tile_row_address(const UnpackArgs& a, const CardGeom&
     const uint32_t t = reinterpret_cast<const uint32_t*>(a.card + g.off_order)[g.base[c] + j];
     const uint32_t lh = g.planes >> 1;
     const uint32_t row_bytes = g.head_dim * 2u;
-    if (t < g.tokens) {
+    if (t < g.tokens && tables_agree(a.card, g, c, j, t)) {
       addr = (p < lh) ? reinterpret_cast<uint64_t>(a.k_out) + ((uint64_t)p * g.tokens + t) * row_bytes
                       : reinterpret_cast<uint64_t>(a.v_out) + ((uint64_t)(p - lh) * g.tokens + t) * row_bytes;
     } else {
@@ -339,7 +349,7 @@ __device__ inline uint64_t inject_row_address(const InjectArgs& a, const CardGeo
     const uint32_t layer = pl / a.kv_heads;
     const uint32_t head = pl - layer * a.kv_heads;
     const uint32_t li = min(layer - a.layer_begin, a.layer_count - 1u);
-    if (t < g.tokens) {
+    if (t < g.tokens && tables_agree(a.card, g, c, j, t)) {
       addr = (kv ? a.v_layer[li] : a.k_layer[li]) + head * a.head_stride + t * a.token_stride;
     } else {
       bad = 1;

@@ -407,6 +407,47 @@ def test_plan_then_fill_equals_quantize_pack():
     assert e.value.code == -5
 
 
+def test_cards_beyond_the_cache_take_the_streaming_kernels_small_shapes():
+    """Cards larger than 512 MB are unpacked by other kernel instances (card loads that bypass the memory-side cache).
+    The benchmark-size tests reach them at 32K tokens; here small cards sit at the front of a 513 MB buffer whose
+    size is what the call is told, so that every head dimension, group size and ragged shape goes through them."""
+    big = torch.zeros((513 << 20,), dtype=torch.uint8, device=DEV)
+    rng = np.random.default_rng(77)
+    shapes = [(1, 1, 1, 64, 32), (1, 2, 37, 128, 32), (2, 3, 1500, 128, 64), (1, 1, 9000, 256, 128), (3, 2, 2049, 64, 64),
+              (1, 40, 1111, 128, 128), (2, 2, 40000, 64, 32)]
+    for L, H, T, D, G in shapes:
+        say("streamed unpack L=%d H=%d T=%d D=%d G=%d" % (L, H, T, D, G))
+        desc, K, V = make_problem(L, H, T, D, G, seed=300 + T)
+        mixes = [rng.choice(np.array([2, 4, 8, 16], dtype=np.uint8), size=T, p=[0.4, 0.3, 0.2, 0.1]),
+                 np.full(T, 2, dtype=np.uint8), np.full(T, 16, dtype=np.uint8)]
+        for bits in mixes:
+            counts = [int((bits == w).sum()) for w in (2, 4, 8, 16)]
+            rd = ref_desc(desc)
+            want = ref.quantize_pack(rd, K, V, bits, counts)
+            wk, wv = ref.unpack_dequant(want, rd)
+            big[:want.size].copy_(torch.from_numpy(want))
+            k, v, st = gpu_unpack(big, desc, nbytes=big.numel())
+            assert st == 0
+            assert first_diff(k.ravel(), wk.ravel()) is None and first_diff(v.ravel(), wv.ravel()) is None
+    # a corrupt order[] entry is skipped and reported there too; a foreign header is refused
+    L, H, T, D, G = 1, 2, 150, 128, 32
+    desc, K, V = make_problem(L, H, T, D, G, seed=61)
+    bits = qkv_synth.make_bits_uniform_choice(T, 62).numpy()
+    counts = [int((bits == w).sum()) for w in (2, 4, 8, 16)]
+    card = ref.quantize_pack(ref_desc(desc), K, V, bits, counts)
+    off_order = int.from_bytes(card[96:104].tobytes(), "little")
+    bad = card.copy()
+    bad[off_order + 28:off_order + 32] = np.frombuffer((T + 1000).to_bytes(4, "little"), dtype=np.uint8)
+    big[:bad.size].copy_(torch.from_numpy(bad))
+    k, v, st = gpu_unpack(big, desc, nbytes=big.numel())
+    assert st == qkv.STATUS_BAD_ORDER
+    tok = int.from_bytes(card[off_order + 28:off_order + 32].tobytes(), "little")
+    assert np.all(k[:, :, tok, :] == 0x7E00)
+    big[0] = ord("X")
+    k, v, st = gpu_unpack(big, desc, nbytes=big.numel())
+    assert st == qkv.STATUS_BAD_HEADER and np.all(k == 0x7E00) and np.all(v == 0x7E00)
+
+
 def test_pack_is_deterministic():
     L, H, T, D, G = 2, 2, 900, 128, 32
     desc, K, V = make_problem(L, H, T, D, G, seed=41)
@@ -528,6 +569,26 @@ def test_unpack_rejects_foreign_headers_and_bounds_order():
     keep = np.ones(T, dtype=bool)
     keep[tok] = False
     assert np.array_equal(k[:, :, keep, :], good_k[:, :, keep, :]) and np.all(k[:, :, tok, :] == nan)
+    say("order entry that names a token twice, and two entries of different classes swapped")
+    entry = lambda i: card[off_order + 4 * i:off_order + 4 * i + 4].tobytes()
+    lost = int.from_bytes(entry(7), "little")
+    k, v, st = gpu_unpack(corrupted(off_order + 4 * 7, entry(8)), desc)           # entry 7 now names entry 8's token
+    assert st == qkv.STATUS_BAD_ORDER
+    keep = np.ones(T, dtype=bool)
+    keep[lost] = False
+    assert np.array_equal(k[:, :, keep, :], good_k[:, :, keep, :]) and np.all(k[:, :, lost, :] == nan)
+    assert np.array_equal(v[:, :, keep, :], good_v[:, :, keep, :]) and np.all(v[:, :, lost, :] == nan)
+    with pytest.raises(ref.OracleError):                                           # the oracle refuses the same card as a whole
+        ref.unpack_dequant(corrupted(off_order + 4 * 7, entry(8)).cpu().numpy(), ref_desc(desc))
+    swapped = card.copy()
+    a_tok, b_tok = entry(0), entry(T - 1)                                          # first 2-bit token, last 16-bit token
+    swapped[off_order:off_order + 4] = np.frombuffer(b_tok, dtype=np.uint8)
+    swapped[off_order + 4 * (T - 1):off_order + 4 * T] = np.frombuffer(a_tok, dtype=np.uint8)
+    k, v, st = gpu_unpack(torch.from_numpy(swapped).to(DEV), desc)
+    assert st == qkv.STATUS_BAD_ORDER
+    keep = np.ones(T, dtype=bool)
+    keep[[int.from_bytes(a_tok, "little"), int.from_bytes(b_tok, "little")]] = False
+    assert np.array_equal(k[:, :, keep, :], good_k[:, :, keep, :]) and np.all(k[:, :, ~keep, :] == nan)
     say("status pointer omitted")
     k = torch.zeros((L, H, T, D), dtype=torch.float16, device=DEV)
     v = torch.zeros_like(k)

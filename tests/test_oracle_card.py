@@ -351,6 +351,36 @@ def test_pack_and_unpack_reject_bad_input():
     assert cc.tolist() == counts.tolist() and status == 0
 
 
+def test_unpack_refuses_a_card_whose_tables_disagree():
+    """bits, slot and order must tell one story (order the inverse of slot, slot the stable rank); the oracle
+    refuses the whole card when any of them is touched, and accepts it again when the damage is undone."""
+    d, K, V, bits = tiny_problem()
+    counts = ref.count_bits(bits)
+    card = ref.quantize_pack(d, K, V, bits, counts)
+    off = ref.card_offsets(d, counts)
+    T = d.tokens
+
+    def entry(table, i):
+        return slice(off[table] + 4 * i, off[table] + 4 * i + 4)
+
+    def refused(c):
+        with pytest.raises(ref.OracleError) as e:
+            ref.unpack_dequant(c, d)
+        return e.value.code == -9
+
+    order = card[off["order"]:off["order"] + 4 * T].view(np.uint32)
+    assert sorted(order.tolist()) == list(range(T))
+    dup = card.copy(); dup[entry("order", 5)] = card[entry("order", 6)]                      # a token named twice
+    far = card.copy(); far[entry("order", 5)] = np.frombuffer((T + 7).to_bytes(4, "little"), dtype=np.uint8)
+    swap = card.copy(); swap[entry("order", 0)] = card[entry("order", T - 1)]; swap[entry("order", T - 1)] = card[entry("order", 0)]
+    slot = card.copy(); slot[entry("slot", 9)] = np.frombuffer((3).to_bytes(4, "little"), dtype=np.uint8) if \
+        int.from_bytes(card[entry("slot", 9)].tobytes(), "little") != 3 else np.frombuffer((4).to_bytes(4, "little"), dtype=np.uint8)
+    width = card.copy(); width[off["bits"] + 2] = 2 if bits[2] != 2 else 4                     # a token moved to another class
+    for broken in (dup, far, swap, slot, width):
+        assert refused(broken)
+    ref.unpack_dequant(card, d)                                                                 # the untouched card still unpacks
+
+
 def test_generator_is_reproducible_and_device_free():
     a = qkv_synth.make_kv(1, 2, 64, 128, 1001, "tiny")
     b = qkv_synth.make_kv(1, 2, 64, 128, 1001, "tiny")
