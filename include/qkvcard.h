@@ -50,7 +50,11 @@
  *     been written and no GPU work has been enqueued.
  *   - "device" pointers are HIP device memory of the current device; "host"
  *     pointers are ordinary process memory.  The caller owns every buffer; the
- *     library keeps no pointer after a call returns and no state between calls.
+ *     library keeps no pointer to caller memory after a call returns and reads no
+ *     environment variable.  Its only state between calls is the fixed scratch
+ *     array of qkv_card_attend_static (one per GPU, its address looked up once).
+ *   - No call allocates device memory except qkv_count_bits (32 bytes, freed before
+ *     it returns).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  GPU
  *     work is enqueued there and the call returns without waiting, except where
  *     a function says it synchronises.
@@ -130,7 +134,8 @@ typedef struct qkv_card_header {
   uint8_t  reserved[60];    /* 196  zero                                        */
 } qkv_card_header_t;
 
-/* Library version as major*10000 + minor*100 + patch.  Host only. */
+/* Library version as major*10000 + minor*100 + patch.  Host only.  (A utility of the boundary; no passage of the
+ * paper stands behind it.  The same holds for qkv_error_string.) */
 int qkv_version(void);
 
 /* Static, NUL-terminated text for a return code.  Host only; never NULL. */
@@ -167,7 +172,9 @@ int qkv_assign_bits(const float* scores_dev, int64_t tokens, double avg_bits_bud
                     uint8_t* bits_dev, int64_t counts_out[4], void* stream);
 
 /*
- * Histogram of a caller-made bits vector (uniform cards, explicit mixes).
+ * Histogram of a caller-made bits vector (uniform cards as in the paper's latency experiment, Sec. 5.3, or any
+ * explicit mix): a utility that yields the class counts the card-building calls need; it restates no formula of
+ * the paper.
  *   bits_dev: device, uint8_t[T].  counts_out: host, int64_t[4] for widths 2,4,8,16.
  * Values other than 2/4/8/16 are not counted (the sum then falls short of T).
  * Allocates and frees a small device scratch buffer and SYNCHRONISES `stream`.
@@ -450,7 +457,8 @@ int qkv_card_attend_static(const void* card_dev, uint64_t card_bytes, const qkv_
                            float* out_dev, float* lse_dev, uint32_t* status_dev, void* stream);
 
 /*
- * Read a card's header back to the host and validate it (magic, version, shape
+ * Read a card's header back to the host (paper Sec. 4.2.1: the card is self-describing - sequence length, identifiers,
+ * position offset, achieved average bit width) and validate it (magic, version, shape
  * domain, counts summing to tokens, section offsets equal to the closed form,
  * total_bytes <= card_bytes).  Any out pointer may be NULL.  SYNCHRONISES `stream`.
  * Returns QKV_ERR_FORMAT for an invalid header (out values are then not written).

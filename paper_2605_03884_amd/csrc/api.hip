@@ -1,7 +1,6 @@
 // api.hip — the C ABI of the CacheCard library: argument checks, card geometry, launch
 // planning.  Every operation's arithmetic runs in the HIP kernels of this directory; there
 // is no host fallback.
-#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -10,35 +9,10 @@
 
 namespace qkv {
 
-namespace {
-std::atomic<int> g_cu_count[64];   // compute units per device ordinal, 0 = not asked yet
-
-int compute_units() {
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-  int n = g_cu_count[dev].load(std::memory_order_relaxed);
-  if (n == 0) {
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-    g_cu_count[dev].store(n, std::memory_order_relaxed);
-  }
-  return n;
-}
-}  // namespace
-
-// Grid size for the streaming kernels: one wave per tile (measured faster than a persistent
-// grid: 216 vs 226 us packing, 191 vs 206 us unpacking at 8K tokens).  QKV_BLOCKS_PER_CU = n
-// caps the grid at n workgroups per compute unit, whose waves then stride over the tiles.
+// Grid size for the streaming kernels: one wave per tile, four waves per workgroup (measured faster than a
+// persistent grid whose waves stride over the tiles: 216 vs 226 us packing, 191 vs 206 us unpacking at 8K tokens).
 int grid_blocks(uint64_t tiles) {
-  static const int per_cu = [] {
-    const char* e = std::getenv("QKV_BLOCKS_PER_CU");
-    const int v = e ? std::atoi(e) : 0;
-    return (v >= 1 && v <= 4096) ? v : 0;
-  }();
   uint64_t n = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-  if (per_cu > 0) {
-    const uint64_t cap = (uint64_t)compute_units() * (uint64_t)per_cu;
-    if (n > cap) n = cap;
-  }
   if (n > 0x7FFFFFFFull) n = 0x7FFFFFFFull;
   return n < 1 ? 1 : (int)n;
 }
