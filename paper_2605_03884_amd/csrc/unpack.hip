@@ -322,10 +322,51 @@ __global__ __launch_bounds__(kBlockThreads) void unpack_kernel(UnpackArgs a) {
   const uint32_t n_waves = gridDim.x * kWavesPerBlock;
   u32x4* my_lds = lds[wave];
 
+  uint32_t bad = 0;
+  if (!KC) {
+    // Plane by plane, from the last plane to the first; inside a plane the raw rows' tiles first, the 2-bit rows'
+    // last, each width from its last tile down - the card is still walked from its end, which is what the memory-
+    // side cache holds of a card a little larger than itself (a 302 MB card: 212 us this way, 264 us front to back).
+    // A tile never straddles planes; each (plane, width) ends in a partial tile.  Width by width over the whole
+    // card, as the card itself is laid out, a plane's rows of the rarer widths were written into DRAM pages that
+    // nobody else touched at that time; plane by plane, all rows of one stretch of a plane (2 MiB at 8K tokens, some
+    // twenty planes in flight) leave within microseconds of each other.  32K tokens, four hops at budgets 6 / 4 / 3 / 2:
+    // 1163 / 1031 / 963 / 851 us width by width, 1060 / 996 / 950 / 860 us plane by plane.  (The packing kernel keeps
+    // the card's own order: there the scattered side is the smaller one and plane by plane cost 3 %.)
+    const uint32_t tile_rows = kTileChunks >> g.lpr_shift;
+    const uint32_t tp0 = (g.n[0] + tile_rows - 1) / tile_rows, tp1 = (g.n[1] + tile_rows - 1) / tile_rows,
+                   tp2 = (g.n[2] + tile_rows - 1) / tile_rows, tp3 = (g.n[3] + tile_rows - 1) / tile_rows;
+    const uint32_t per_plane = tp0 + tp1 + tp2 + tp3;
+    const uint32_t s = (uint32_t)__builtin_amdgcn_readfirstlane((int)gw);
+    const uint32_t pr = s / per_plane;
+    if (pr >= g.planes) return;
+    const uint32_t p = g.planes - 1u - pr;
+    uint32_t k = s - pr * per_plane;
+    const RopeLane no_rope = {};
+    if (k < tp3) {
+      const uint32_t r0 = p * g.n[3] + (tp3 - 1u - k) * tile_rows, end = (p + 1u) * g.n[3];
+      const uint64_t my_row = tile_row_address(a, g, 3, r0, end, lane, tile_rows, bad);
+      copy_tile<KEEP, false>(a.card, g, r0, end, my_row, lane, no_rope);
+    } else if ((k -= tp3) < tp2) {
+      const uint32_t r0 = p * g.n[2] + (tp2 - 1u - k) * tile_rows, end = (p + 1u) * g.n[2];
+      const uint64_t my_row = tile_row_address(a, g, 2, r0, end, lane, tile_rows, bad);
+      unpack_tile<8, G, KEEP, false>(a.card, g, 2, r0, end, my_row, lane, my_lds, no_rope);
+    } else if ((k -= tp2) < tp1) {
+      const uint32_t r0 = p * g.n[1] + (tp1 - 1u - k) * tile_rows, end = (p + 1u) * g.n[1];
+      const uint64_t my_row = tile_row_address(a, g, 1, r0, end, lane, tile_rows, bad);
+      unpack_tile<4, G, KEEP, false>(a.card, g, 1, r0, end, my_row, lane, my_lds, no_rope);
+    } else {
+      k -= tp1;
+      const uint32_t r0 = p * g.n[0] + (tp0 - 1u - k) * tile_rows, end = (p + 1u) * g.n[0];
+      const uint64_t my_row = tile_row_address(a, g, 0, r0, end, lane, tile_rows, bad);
+      unpack_tile<2, G, KEEP, false>(a.card, g, 0, r0, end, my_row, lane, my_lds, no_rope);
+    }
+    if (bad && a.status) atomicOr(a.status, QKV_STATUS_BAD_ORDER);
+    return;
+  }
   // The card is walked from its end to its start: right after packing, its tail is what the
   // 256 MB memory-side cache still holds (a card of 302 MB unpacks in 212 us this way, 264 us
   // front to back; cards that fit, or that are several times larger, are indifferent).
-  uint32_t bad = 0;
   uint32_t cum = 0;
   unpack_class<3, G, KEEP, KC>(a, g, gw, n_waves, lane, my_lds, cum, bad);
   unpack_class<2, G, KEEP, KC>(a, g, gw, n_waves, lane, my_lds, cum, bad);
@@ -450,7 +491,8 @@ hipError_t launch_unpack(const uint8_t* card, uint64_t card_bytes, const CardGeo
   // the class counts are only known on the device: size the grid for the worst split
   const uint32_t tile_rows = kTileChunks >> expect.lpr_shift;
   const uint64_t rows = (uint64_t)expect.planes * expect.tokens;
-  const uint64_t tiles = (rows + tile_rows - 1) / tile_rows + 3;
+  const uint64_t tiles = keys_per_channel ? (rows + tile_rows - 1) / tile_rows + 3
+                                          : (uint64_t)expect.planes * ((expect.tokens + tile_rows - 1) / tile_rows + 3);
   const dim3 grid(grid_blocks(tiles)), block(kBlockThreads);
   const bool keep = card_bytes <= kCacheResidentCardBytes;
   if (keys_per_channel) {                        // group size 32 only (checked by the caller)
