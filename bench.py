@@ -33,7 +33,7 @@ MALL_BYTES = 256 << 20    # memory-side cache: a working set below this is serve
 # taken: `sources` is a digest of the kernel sources at that time, and the figures are reported only while
 # the sources still have that digest (else `traffic` is null and says why).
 MEASURED_TRAFFIC = {
-    "llama8b_8k_b3": {"pack": 1341465395, "unpack": 1342183220, "sources": "",
+    "llama8b_8k_b3": {"pack": 1341416735, "unpack": 1346870188, "sources": "bf0ee3e3439722cd",
                       "profile": "profiles/pack_unpack_llama8b_8k_b3_hbm_traffic.txt"},
 }
 KERNEL_SOURCES = ["pack.hip", "unpack.hip", "qkv_encode.h", "qkv_decode.h", "qkv_common.h"]
