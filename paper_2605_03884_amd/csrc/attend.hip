@@ -75,17 +75,6 @@ struct AttendArgs {
   uint32_t* valid;         // one word of the workspace: 1 when the header was accepted
 };
 
-__device__ inline float wave_max(float v) {
-#pragma unroll
-  for (int d = 1; d < kWaveSize; d <<= 1) v = fmaxf(v, __shfl_xor(v, d, kWaveSize));
-  return v;
-}
-__device__ inline float wave_sum(float v) {
-#pragma unroll
-  for (int d = 1; d < kWaveSize; d <<= 1) v += __shfl_xor(v, d, kWaveSize);
-  return v;
-}
-
 template <int W, int G>
 struct SpanData {
   uint32_t cw[W == 16 ? 16 : W];
@@ -154,7 +143,7 @@ __device__ inline void decode_fetched(const SpanData<W, G>& d, uint32_t (&out)[1
 }
 
 template <int G>
-__device__ inline void decode_fetched_select(const SpanData<2, G>& d, const u32x2* table, uint32_t (&out)[16]) {
+__device__ inline void decode_fetched_select(const SpanData<2, G>& d, const uint8_t* table, uint32_t (&out)[16]) {
   decode_span2_select(d.cw, half_bits_to_float(d.pair & 0xFFFFu), half_bits_to_float(d.pair >> 16), table, out);
 }
 
@@ -207,14 +196,65 @@ __device__ inline uint32_t decode_two_tokens(float c0, float s0, float z0, float
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
 }
 
+// ---- cross-lane helpers ------------------------------------------------------------------------
+
+template <int CTRL>
+__device__ inline float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+// maximum / sum over the 16 lanes of a row, left in every lane of the row (row_ror: 8, 4, 2, 1)
+__device__ inline float row_max16(float v) {
+  v = fmaxf(v, dpp_move<0x128>(v));
+  v = fmaxf(v, dpp_move<0x124>(v));
+  v = fmaxf(v, dpp_move<0x122>(v));
+  return fmaxf(v, dpp_move<0x121>(v));
+}
+__device__ inline float row_sum16(float v) {
+  v += dpp_move<0x128>(v);
+  v += dpp_move<0x124>(v);
+  v += dpp_move<0x122>(v);
+  return v + dpp_move<0x121>(v);
+}
+
+// Lane (n, kq) holds four partial sums a_r, one per head r, each to be added up over the four
+// lanes (n, 0 .. 3); returns in lane (n, kq) the total of head kq.  v_permlane32_swap hands the
+// lower half of the wave its partner's first operand and the upper half its partner's second
+// one; v_permlane16_swap does the same between neighbouring rows of 16.
+__device__ inline float sum_over_quarters(float a0, float a1, float a2, float a3) {
+  const auto s02 = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, a0), __builtin_bit_cast(uint32_t, a2), false, false);
+  const uint32_t s02x = s02[0], s02y = s02[1];
+  const float u0 = __builtin_bit_cast(float, s02x) + __builtin_bit_cast(float, s02y);      // heads 0 | 2
+  const auto s13 = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, a1), __builtin_bit_cast(uint32_t, a3), false, false);
+  const uint32_t s13x = s13[0], s13y = s13[1];
+  const float u1 = __builtin_bit_cast(float, s13x) + __builtin_bit_cast(float, s13y);      // heads 1 | 3
+  const auto sr = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(uint32_t, u0), __builtin_bit_cast(uint32_t, u1), false, false);
+  const uint32_t srx = sr[0], sry = sr[1];
+  return __builtin_bit_cast(float, srx) + __builtin_bit_cast(float, sry);
+}
+
 // One task: rows [j0, j1) of class c for the pair (layer, kv head) = pair.
 // lds: scores / weights as [head][chunk] floats (R4 * chunk <= kLdsFloatsPerWave);
-// tile: the round's packed rows (16 tokens x up to 256 bytes) followed by 16 x 4 pairs.
-template <int W, int G>
+// tile: the round's packed rows (16 tokens x up to 256 bytes) followed by the rows' pairs.
+//
+// NARROW (at most 4 query heads per kv head, the grouped-query case): the contractions run on
+// v_mfma_f32_4x4x4_16b_f16, sixteen independent 4 x 4 x 4 products per instruction, at half the
+// cycles of the 16 x 16 x 16 form, whose rows 4 .. 15 would be idle.  Block b = lanes 4 b .. 4 b + 3;
+// a lane gives row (lane % 4) of A and column (lane % 4) of B, and gets column (lane % 4) of the
+// block's product, one row per register.
+//   scores   A = q[head n % 4][4 dimensions], B = K^[token n][the same 4 dimensions]: the lane gets
+//            the scores of its token n against the four heads, summed over its quarter kq of the
+//            head dimension only; sum_over_quarters finishes the sum and leaves lane (n, kq)
+//            with head kq, which it stores.
+//   values   A = weights[head a % 4][tokens 4 kt .. + 3], B = V^[those tokens][dimension 8 a + e]:
+//            the lane accumulates, over its own four tokens of every round, out[4 heads][8 a + e];
+//            the four kt are added up once, at the end of the task.
+// Otherwise (5 .. 16 query heads per kv head) the 16 x 16 x 16 form is used with the tokens as rows
+// of the score product, so that a lane ends up with four consecutive tokens of one head.
+template <int W, int G, bool NARROW>
 __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c, uint32_t pair, uint32_t j0, uint32_t j1,
-                                   uint32_t lane, float* lds, uint8_t* tile, const u32x2* table, uint64_t part) {
-  const uint32_t n = lane & 15u, kq = lane >> 4;          // also (a, kt) of the value pass and (m, k group) of the MFMAs
-  const uint32_t R = a.rep, R4 = (R + 3u) & ~3u;
+                                   uint32_t lane, float* lds, uint8_t* tile, const uint8_t* table, uint64_t part) {
+  const uint32_t n = lane & 15u, kq = lane >> 4;          // also (a, kt) of the value pass
+  const uint32_t R = a.rep, R4 = NARROW ? 4u : ((R + 3u) & ~3u);
   const uint32_t chunk = a.chunk % 192u == 0u ? a.chunk : 96u;      // LDS pitch of a head's scores: the task size, padded
   const uint32_t lh = g.planes >> 1;
   const uint32_t n_c = g.n[c];
@@ -226,16 +266,17 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   const LanePtrs kp = lane_pointers<W, G>(a.card, g, c, k_row0 + j0, n, kq);
   const LanePtrs vp = lane_pointers<W, G>(a.card, g, c, v_row0 + j0, n, kq);
 
-  // ---- q as MFMA A operands: row m = lane % 16 is query head m of this kv head, the lane holds
-  // q[m][32 kq .. 32 kq + 31]; operand j is q[m][32 kq + 4 j .. + 3]
+  // ---- q as MFMA operands: the lane holds q[head][32 kq .. 32 kq + 31] of head n (head n % 4 when
+  // NARROW); operand j is q[head][32 kq + 4 j .. + 3]
   f16x4 qa[8];
   {
     u32x4 raw[4];
 #pragma unroll
     for (int h = 0; h < 4; ++h) raw[h] = (u32x4)(0u);
-    if (n < R) {
+    const uint32_t head = NARROW ? (n & 3u) : n;
+    if (head < R) {
       const uint32_t l = pair / g.kv_heads, hh = pair - l * g.kv_heads;
-      const u32x4* src = reinterpret_cast<const u32x4*>(a.q + ((uint64_t)(l * a.q_heads + hh * R + n) * 128u + 32u * kq));
+      const u32x4* src = reinterpret_cast<const u32x4*>(a.q + ((uint64_t)(l * a.q_heads + hh * R + head) * 128u + 32u * kq));
 #pragma unroll
       for (int h = 0; h < 4; ++h) raw[h] = src[h];
     }
@@ -266,49 +307,70 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
           const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
           buf[u] = fetch_span<W, G>(kp, rd + kPrefetch, tn < cnt);
           f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+          if constexpr (NARROW) {
 #pragma unroll
-          for (int j = 0; j < 8; ++j)
-            acc = __builtin_amdgcn_mfma_f32_16x16x16f16(qa[j], __builtin_bit_cast(f16x4, (u32x2){kb[2 * j], kb[2 * j + 1]}),
-                                                        acc, 0, 0, 0);
-          // the lane holds heads 4 kq .. 4 kq + 3 of token n
-          const uint32_t t = rd * kRoundTokens + n;
-          if (4u * kq < R4) {
-            const bool live = t < cnt;
-            float* dst = lds + (4u * kq) * chunk + t;
-            dst[0] = live ? acc.x * a.scale_log2 : -INFINITY;
-            dst[chunk] = live ? acc.y * a.scale_log2 : -INFINITY;
-            dst[2 * chunk] = live ? acc.z * a.scale_log2 : -INFINITY;
-            dst[3 * chunk] = live ? acc.w * a.scale_log2 : -INFINITY;
+            for (int j = 0; j < 8; ++j)
+              acc = __builtin_amdgcn_mfma_f32_4x4x4f16(qa[j], __builtin_bit_cast(f16x4, (u32x2){kb[2 * j], kb[2 * j + 1]}),
+                                                       acc, 0, 0, 0);
+            // head kq of token n
+            const float sc = sum_over_quarters(acc.x, acc.y, acc.z, acc.w);
+            const uint32_t t = rd * kRoundTokens + n;
+            lds[kq * chunk + t] = (t < cnt) ? sc * a.scale_log2 : -INFINITY;
+          } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+              acc = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, (u32x2){kb[2 * j], kb[2 * j + 1]}), qa[j],
+                                                          acc, 0, 0, 0);
+            // tokens 4 kq .. 4 kq + 3 of head n
+            const uint32_t t = rd * kRoundTokens + 4u * kq;
+            if (n < R4) {
+              f32x4 sc;
+              sc.x = (t < cnt) ? acc.x * a.scale_log2 : -INFINITY;
+              sc.y = (t + 1u < cnt) ? acc.y * a.scale_log2 : -INFINITY;
+              sc.z = (t + 2u < cnt) ? acc.z * a.scale_log2 : -INFINITY;
+              sc.w = (t + 3u < cnt) ? acc.w * a.scale_log2 : -INFINITY;
+              *reinterpret_cast<f32x4*>(lds + n * chunk + t) = sc;
+            }
           }
         }
       }
     }
   }
 
-  // ---- softmax over the task's tokens, head by head (the wave's own LDS accesses are in order)
-  // whole groups of kPrefetch rounds are processed; the task size is a multiple of such a group,
-  // so the padded rounds stay inside the task's share of LDS
+  // ---- softmax over the task's tokens, four heads at a time: row kq of the wave takes head
+  // 4 hg + kq, its lane n the tokens 64 i + 4 n .. + 3 (the wave's own LDS accesses are in order).
+  // Whole groups of kPrefetch rounds are processed; the task size is a multiple of such a group,
+  // so the padded rounds stay inside the task's share of LDS.
   const uint32_t slots = (rounds + kPrefetch - 1) / kPrefetch * kPrefetch * kRoundTokens;
-  for (uint32_t r = 0; r < R4; ++r) {
+  for (uint32_t hg = 0; hg < R4; hg += 4u) {
+    const uint32_t r = hg + kq;
     float* row = lds + r * chunk;
     float m = -INFINITY;
-    for (uint32_t t = lane; t < slots; t += kWaveSize) m = fmaxf(m, row[t]);
-    m = wave_max(m);
-    float l = 0.f;
-    for (uint32_t t = lane; t < slots; t += kWaveSize) {
-      const float p = __builtin_amdgcn_exp2f(row[t] - m);
-      l += p;
-      // what the value pass feeds the MFMA: p * 2^14 as an fp16 high part plus the fp16 remainder (both go
-      // into the same accumulator; the remainder is a normal number for any p that matters), packed into
-      // the score's slot
-      const float ps = p * 16384.0f;
-      const _Float16 hi = (_Float16)ps;
-      const _Float16 lo = (_Float16)(ps - (float)hi);
-      row[t] = __builtin_bit_cast(float, (uint32_t)__builtin_bit_cast(uint16_t, hi) |
-                                             ((uint32_t)__builtin_bit_cast(uint16_t, lo) << 16));
+    for (uint32_t t = 4u * n; t < slots; t += 64u) {
+      const f32x4 sv = *reinterpret_cast<const f32x4*>(row + t);
+      m = fmaxf(fmaxf(m, fmaxf(sv.x, sv.y)), fmaxf(sv.z, sv.w));
     }
-    l = wave_sum(l);
-    if (lane == 0 && r < R) {
+    m = row_max16(m);
+    float l = 0.f;
+    for (uint32_t t = 4u * n; t < slots; t += 64u) {
+      const f32x4 sv = *reinterpret_cast<const f32x4*>(row + t);
+      u32x4 packed;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float p = __builtin_amdgcn_exp2f(sv[i] - m);
+        l += p;
+        // what the value pass feeds the MFMA: p * 2^14 as an fp16 high part plus the fp16 remainder (both go
+        // into the same accumulator; the remainder is a normal number for any p that matters), packed into
+        // the score's slot
+        const float ps = p * 16384.0f;
+        const _Float16 hi = (_Float16)ps;
+        const _Float16 lo = (_Float16)(ps - (float)hi);
+        packed[i] = (uint32_t)__builtin_bit_cast(uint16_t, hi) | ((uint32_t)__builtin_bit_cast(uint16_t, lo) << 16);
+      }
+      *reinterpret_cast<u32x4*>(row + t) = packed;
+    }
+    l = row_sum16(l);
+    if (n == 0 && r < R) {
       a.part_ml[(part * R + r) * 2] = m;
       a.part_ml[(part * R + r) * 2 + 1] = l;
     }
@@ -318,8 +380,9 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   // one token's packed row in the LDS tile; rows of 32 / 64 bytes get a pitch of 40 / 80 so that
   // the four rows a read instruction touches (4 apart) fall on different banks
   constexpr uint32_t kRowBytes = (W == 2) ? 40u : (W == 4) ? 80u : 16u * W;
-  // behind the rows: the 16 x 4 pairs (2-bit rows: 16 x 4 four-value tables), and for 2-bit rows the selector table
+  // behind the rows, as [quarter of the head dimension][token]: the 4 x 16 pairs (2-bit rows: 4 x 16 four-value tables)
   uint32_t* pairs_lds = reinterpret_cast<uint32_t*>(tile + ((W == 16) ? 0u : 16u * kRowBytes));
+  const uint32_t w_head = NARROW ? (n & 3u) : n;            // the head whose weights this lane feeds the MFMA
   f32x4 acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -349,9 +412,9 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
               // the span's four decoded values instead of its (scale, zero): x_k = fp16(fma(k, scale, zero))
               const float s = half_bits_to_float(buf[u].pair & 0xFFFFu);
               const float z = half_bits_to_float(buf[u].pair >> 16);
-              reinterpret_cast<u32x2*>(pairs_lds)[n * 4u + kq] = (u32x2){decode_pair(0.0f, 1.0f, s, z), decode_pair(2.0f, 3.0f, s, z)};
+              reinterpret_cast<u32x2*>(pairs_lds)[kq * 16u + n] = (u32x2){decode_pair(0.0f, 1.0f, s, z), decode_pair(2.0f, 3.0f, s, z)};
             } else if constexpr (W != 16) {
-              pairs_lds[n * 4u + kq] = buf[u].pair;
+              pairs_lds[kq * 16u + n] = buf[u].pair;
             }
           }
           const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
@@ -364,15 +427,18 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
             // by selection: the piece's two code bytes index the selector table, the selectors pick the
             // values out of the token's four; then pairs of dimensions are turned into pairs of tokens
             uint32_t tv[4][4];                     // token i, dimension pair m: {V^[8a+2m], V^[8a+2m+1]}
+            const u32x4* xs = reinterpret_cast<const u32x4*>(pairs_lds) + ((n >> 2) * 16u + 4u * kq) / 2u;
+            const u32x4 x01 = xs[0], x23 = xs[1];  // the four-value tables of tokens 4 kt .. 4 kt + 3 for this lane's dimensions
+            const uint32_t xl[4] = {x01.x, x01.z, x23.x, x23.z}, xh[4] = {x01.y, x01.w, x23.y, x23.w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               const uint32_t piece = *reinterpret_cast<const uint16_t*>(tile + (4u * kq + i) * kRowBytes + n * 2u);
-              const u32x2 x = reinterpret_cast<const u32x2*>(pairs_lds)[(4u * kq + i) * 4u + (n >> 2)];
-              const u32x2 s0 = table[piece & 0xFFu], s1 = table[piece >> 8];
-              tv[i][0] = __builtin_amdgcn_perm(x.y, x.x, s0.x);
-              tv[i][1] = __builtin_amdgcn_perm(x.y, x.x, s0.y);
-              tv[i][2] = __builtin_amdgcn_perm(x.y, x.x, s1.x);
-              tv[i][3] = __builtin_amdgcn_perm(x.y, x.x, s1.y);
+              const u32x2 s0 = *reinterpret_cast<const u32x2*>(table + byte_times8<0>(piece));
+              const u32x2 s1 = *reinterpret_cast<const u32x2*>(table + byte_times8<1>(piece));
+              tv[i][0] = __builtin_amdgcn_perm(xh[i], xl[i], s0.x);
+              tv[i][1] = __builtin_amdgcn_perm(xh[i], xl[i], s0.y);
+              tv[i][2] = __builtin_amdgcn_perm(xh[i], xl[i], s1.x);
+              tv[i][3] = __builtin_amdgcn_perm(xh[i], xl[i], s1.y);
             }
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -382,7 +448,7 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
             }
           } else {
           Piece<W> pc[4];
-          uint32_t pr[4];
+          uint32_t pr[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const uint8_t* src = tile + (4u * kq + i) * kRowBytes + n * W;
@@ -390,7 +456,10 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
             else if constexpr (W == 4) pc[i].w[0] = *reinterpret_cast<const uint32_t*>(src);
             else if constexpr (W == 8) { const u32x2 t = *reinterpret_cast<const u32x2*>(src); pc[i].w[0] = t.x; pc[i].w[1] = t.y; }
             else { const u32x4 t = *reinterpret_cast<const u32x4*>(src); pc[i].w[0] = t.x; pc[i].w[1] = t.y; pc[i].w[2] = t.z; pc[i].w[3] = t.w; }
-            pr[i] = (W != 16) ? pairs_lds[(4u * kq + i) * 4u + (n >> 2)] : 0u;
+          }
+          if constexpr (W != 16) {
+            const u32x4 t = *reinterpret_cast<const u32x4*>(pairs_lds + (n >> 2) * 16u + 4u * kq);
+            pr[0] = t.x; pr[1] = t.y; pr[2] = t.z; pr[3] = t.w;
           }
           if constexpr (W == 16) {
 #pragma unroll
@@ -414,9 +483,9 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
             }
           }
           }
-          // A operands: the weights of head m = n for tokens 4 kt .. 4 kt + 3, high parts and low parts
+          // A operands: the weights of head w_head for tokens 4 kt .. 4 kt + 3, high parts and low parts
           u32x4 pw = (u32x4)(0u);
-          if (n < R4) pw = *reinterpret_cast<const u32x4*>(lds + n * chunk + rd * kRoundTokens + 4u * kq);
+          if (w_head < R4) pw = *reinterpret_cast<const u32x4*>(lds + w_head * chunk + rd * kRoundTokens + 4u * kq);
           const f16x4 a_hi = __builtin_bit_cast(f16x4, (u32x2){__builtin_amdgcn_perm(pw.y, pw.x, 0x05040100u),
                                                                __builtin_amdgcn_perm(pw.w, pw.z, 0x05040100u)});
           const f16x4 a_lo = __builtin_bit_cast(f16x4, (u32x2){__builtin_amdgcn_perm(pw.y, pw.x, 0x07060302u),
@@ -424,29 +493,48 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
             const f16x4 be = __builtin_bit_cast(f16x4, b[e]);
-            acc[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(a_hi, be, acc[e], 0, 0, 0);
-            acc[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(a_lo, be, acc[e], 0, 0, 0);
+            if constexpr (NARROW) {
+              acc[e] = __builtin_amdgcn_mfma_f32_4x4x4f16(a_hi, be, acc[e], 0, 0, 0);
+              acc[e] = __builtin_amdgcn_mfma_f32_4x4x4f16(a_lo, be, acc[e], 0, 0, 0);
+            } else {
+              acc[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(a_hi, be, acc[e], 0, 0, 0);
+              acc[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(a_lo, be, acc[e], 0, 0, 0);
+            }
           }
         }
       }
     }
   }
-  // the lane holds out[heads 4 kq .. 4 kq + 3][dimensions 8 n .. 8 n + 7]
+  if constexpr (NARROW) {
+    // the lane holds, for its own tokens only, out[heads 0 .. 3][dimensions 8 n .. 8 n + 7]: add up the four kt;
+    // lane (n, kq) is left with head kq
+    // (every lane takes part in the sums; only the stores are conditional)
+    float o[8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t r = 4u * kq + i;
-    if (r < R) {
-      float o[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] = acc[e][i] * (1.0f / 16384.0f);
-      f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + r) * 128u + 8u * n);
+    for (int e = 0; e < 8; ++e) o[e] = sum_over_quarters(acc[e].x, acc[e].y, acc[e].z, acc[e].w) * (1.0f / 16384.0f);
+    if (kq < R) {
+      f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + kq) * 128u + 8u * n);
       dst[0] = (f32x4){o[0], o[1], o[2], o[3]};
       dst[1] = (f32x4){o[4], o[5], o[6], o[7]};
+    }
+  } else {
+    // the lane holds out[heads 4 kq .. 4 kq + 3][dimensions 8 n .. 8 n + 7]
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t r = 4u * kq + i;
+      if (r < R) {
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = acc[e][i] * (1.0f / 16384.0f);
+        f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + r) * 128u + 8u * n);
+        dst[0] = (f32x4){o[0], o[1], o[2], o[3]};
+        dst[1] = (f32x4){o[4], o[5], o[6], o[7]};
+      }
     }
   }
 }
 
-template <int G>
+template <int G, bool NARROW>
 __global__ __launch_bounds__(kAttendWaves * kWaveSize) __attribute__((amdgpu_waves_per_eu(2)))
 void attend_kernel(AttendArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[kAttendWaves][kLdsFloatsPerWave];
@@ -463,7 +551,7 @@ void attend_kernel(AttendArgs a) {
   }
   if (!ok) return;                            // uniform over the grid
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t wave = threadIdx.x >> 6;
+  const uint32_t wave = (kAttendWaves == 1) ? 0u : threadIdx.x >> 6;     // a constant keeps every LDS address an immediate
   const uint32_t gw = blockIdx.x * kAttendWaves + wave;
   const uint32_t pairs = g.planes >> 1;
   const uint32_t pair = gw / a.max_tasks;
@@ -496,14 +584,14 @@ void attend_kernel(AttendArgs a) {
   }
   float* my_lds = lds[wave];
   uint8_t* my_tile = tiles[wave];
-  u32x2* my_table = reinterpret_cast<u32x2*>(my_tile + 16 * 40 + 512);
+  uint8_t* my_table = my_tile + 16 * 40 + 512;
   if (cls == 0) {
-    build_select_table(my_table, lane);
-    attend_task<2, G>(a, g, 0, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+    build_select_table(reinterpret_cast<u32x2*>(my_table), lane);
+    attend_task<2, G, NARROW>(a, g, 0, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
   }
-  if (cls == 1) attend_task<4, G>(a, g, 1, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
-  if (cls == 2) attend_task<8, G>(a, g, 2, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
-  if (cls == 3) attend_task<16, G>(a, g, 3, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+  if (cls == 1) attend_task<4, G, NARROW>(a, g, 1, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+  if (cls == 2) attend_task<8, G, NARROW>(a, g, 2, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+  if (cls == 3) attend_task<16, G, NARROW>(a, g, 3, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
 }
 
 // Merges the partials of one (layer, query head): thread d owns output dimension d.  The
@@ -623,10 +711,20 @@ hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeo
   a.status = status;
   const uint64_t waves = pairs * a.max_tasks;
   const dim3 grid((uint32_t)((waves + kAttendWaves - 1) / kAttendWaves)), block(kAttendWaves * kWaveSize);
+  const bool narrow = a.rep <= 4u;             // grouped-query shapes: the 4 x 4 x 4 contraction
   switch (expect.group_size) {
-    case 32: hipLaunchKernelGGL(attend_kernel<32>, grid, block, 0, stream, a); break;
-    case 64: hipLaunchKernelGGL(attend_kernel<64>, grid, block, 0, stream, a); break;
-    default: hipLaunchKernelGGL(attend_kernel<128>, grid, block, 0, stream, a); break;
+    case 32:
+      if (narrow) hipLaunchKernelGGL((attend_kernel<32, true>), grid, block, 0, stream, a);
+      else hipLaunchKernelGGL((attend_kernel<32, false>), grid, block, 0, stream, a);
+      break;
+    case 64:
+      if (narrow) hipLaunchKernelGGL((attend_kernel<64, true>), grid, block, 0, stream, a);
+      else hipLaunchKernelGGL((attend_kernel<64, false>), grid, block, 0, stream, a);
+      break;
+    default:
+      if (narrow) hipLaunchKernelGGL((attend_kernel<128, true>), grid, block, 0, stream, a);
+      else hipLaunchKernelGGL((attend_kernel<128, false>), grid, block, 0, stream, a);
+      break;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

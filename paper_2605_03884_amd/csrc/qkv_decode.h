@@ -121,19 +121,38 @@ __device__ inline void build_select_table(u32x2* table, uint32_t lane) {
   }
 }
 
-// The 32 values of a 2-bit span through the selector table: same values as decode_span<2>.
-__device__ inline void decode_span2_select(const uint32_t (&cw)[2], float s, float z, const u32x2* table,
+// 8 * (byte J of w), the offset of a byte's entry in the selector table: one instruction (a shift whose
+// operand is picked out of the register by sub-dword addressing) instead of an extraction and a shift.
+template <int J>
+__device__ inline uint32_t byte_times8(uint32_t w) {
+  uint32_t r;
+  const uint32_t three = 3u;
+  if (J == 0) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(three), "v"(w));
+  if (J == 1) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(three), "v"(w));
+  if (J == 2) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(three), "v"(w));
+  if (J == 3) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(three), "v"(w));
+  return r;
+}
+
+// The 32 values of a 2-bit span through the selector table (given as its first byte): same values as decode_span<2>.
+__device__ inline void decode_span2_select(const uint32_t (&cw)[2], float s, float z, const uint8_t* table,
                                            uint32_t (&out)[16]) {
   const uint32_t x01 = decode_pair(0.0f, 1.0f, s, z);
   const uint32_t x23 = decode_pair(2.0f, 3.0f, s, z);
 #pragma unroll
   for (int w = 0; w < 2; ++w) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const u32x2 sel = table[(cw[w] >> (8 * j)) & 0xFFu];
-      out[8 * w + 2 * j] = __builtin_amdgcn_perm(x23, x01, sel.x);
-      out[8 * w + 2 * j + 1] = __builtin_amdgcn_perm(x23, x01, sel.y);
-    }
+    const u32x2 sel0 = *reinterpret_cast<const u32x2*>(table + byte_times8<0>(cw[w]));
+    const u32x2 sel1 = *reinterpret_cast<const u32x2*>(table + byte_times8<1>(cw[w]));
+    const u32x2 sel2 = *reinterpret_cast<const u32x2*>(table + byte_times8<2>(cw[w]));
+    const u32x2 sel3 = *reinterpret_cast<const u32x2*>(table + byte_times8<3>(cw[w]));
+    out[8 * w + 0] = __builtin_amdgcn_perm(x23, x01, sel0.x);
+    out[8 * w + 1] = __builtin_amdgcn_perm(x23, x01, sel0.y);
+    out[8 * w + 2] = __builtin_amdgcn_perm(x23, x01, sel1.x);
+    out[8 * w + 3] = __builtin_amdgcn_perm(x23, x01, sel1.y);
+    out[8 * w + 4] = __builtin_amdgcn_perm(x23, x01, sel2.x);
+    out[8 * w + 5] = __builtin_amdgcn_perm(x23, x01, sel2.y);
+    out[8 * w + 6] = __builtin_amdgcn_perm(x23, x01, sel3.x);
+    out[8 * w + 7] = __builtin_amdgcn_perm(x23, x01, sel3.y);
   }
 }
 

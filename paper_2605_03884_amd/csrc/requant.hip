@@ -80,7 +80,7 @@ __device__ __forceinline__ void decode_old_class(const uint8_t* card, const Card
         cw[4 * h] = v.x; cw[4 * h + 1] = v.y; cw[4 * h + 2] = v.z; cw[4 * h + 3] = v.w;
       }
     }
-    if constexpr (W == 2) decode_span2_select(cw, s, z, table, w);      // most spans at low budgets: by selection
+    if constexpr (W == 2) decode_span2_select(cw, s, z, reinterpret_cast<const uint8_t*>(table), w);      // most spans at low budgets: by selection
     else decode_span<W>(cw, s, z, w);
   }
 }
