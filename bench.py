@@ -38,10 +38,24 @@ MEASURED_TRAFFIC = {
 }
 KERNEL_SOURCES = ["pack.hip", "unpack.hip", "qkv_encode.h", "qkv_decode.h", "qkv_common.h"]
 
+# The attention kernel is bound by instruction issue, not by memory: its roofline block is priced against the
+# vector pipes.  One compute unit has 4 SIMDs, each of which starts one vector instruction (64 lanes wide, 16
+# lanes a cycle) every 4 cycles: 256 CUs x 4 x 2.4 GHz = 614.4 G vector instructions/s, or 39.3 T lane
+# operations/s (the published 157.3 TFLOP/s of fp32 is this figure times 2 flops of an FMA times 2 values of a
+# packed instruction).  The kernel's vector instructions per launch come from the SQ_INSTS_VALU counter
+# (matrix instructions included), with the digest of the sources they were counted for.
+VECTOR_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+MEASURED_ATTEND = {
+    "llama8b_8k_b3": {"valu_instructions": 24134913, "mfma_instructions": 3182592, "lds_instructions": 2981888,
+                      "lds_active_cycles": 18725549, "lds_bank_conflict_cycles": 10719405, "sources": "56067185fbf40cc9",
+                      "profile": "profiles/card_attend_llama8b_8k_b3.txt"},
+}
+ATTEND_SOURCES = ["attend.hip", "qkv_decode.h", "qkv_common.h"]
 
-def kernel_sources_digest():
+
+def kernel_sources_digest(names=KERNEL_SOURCES):
     h = hashlib.sha256()
-    for name in KERNEL_SOURCES:
+    for name in names:
         with open(os.path.join(ROOT, "paper_2605_03884_amd", "csrc", name), "rb") as f:
             h.update(f.read())
     return h.hexdigest()[:16]
@@ -523,6 +537,19 @@ def main():
                   "algorithmic_bytes": att_bytes, "achieved_gbs": round(att_bytes / (att_ms * 1e-3) / 1e9, 1),
                   "frac_hbm_peak": round(att_bytes / (att_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                   "dense_cache_gbs_equivalent": round(kv_bytes / (att_ms * 1e-3) / 1e9, 1)}
+        # what bounds it: the vector pipes (the whole call is timed, merging kernel included)
+        meas, att_digest = MEASURED_ATTEND.get(args.workload), kernel_sources_digest(ATTEND_SOURCES)
+        if meas is not None and meas["sources"] == att_digest:
+            tlane = meas["valu_instructions"] * 64 / (att_ms * 1e-3) / 1e12
+            attend["roofline"] = {"bound": "alu", "achieved": round(tlane, 2), "peak": round(VECTOR_PEAK_TLANEOPS, 1),
+                                  "unit": "T lane-op/s", "frac": round(tlane / VECTOR_PEAK_TLANEOPS, 4),
+                                  "vector_instructions_per_launch": meas["valu_instructions"],
+                                  "of_which_matrix": meas["mfma_instructions"], "profile": meas["profile"],
+                                  "kernel_sources_digest": att_digest}
+        else:
+            attend["roofline"] = {"bound": "alu", "achieved": None, "peak": round(VECTOR_PEAK_TLANEOPS, 1), "unit": "T lane-op/s",
+                                  "frac": None, "kernel_sources_digest": att_digest,
+                                  "note": "no instruction count on file for this workload and these sources"}
 
     # injection into per-layer caches (one key and one value tensor per layer, room for a prefix), with and
     # without realigning the keys, in one call and layer by layer

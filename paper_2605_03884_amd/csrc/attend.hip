@@ -342,6 +342,13 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   // Whole groups of kPrefetch rounds are processed; the task size is a multiple of such a group,
   // so the padded rounds stay inside the task's share of LDS.
   const uint32_t slots = (rounds + kPrefetch - 1) / kPrefetch * kPrefetch * kRoundTokens;
+  // the first value rows are requested now, so that they arrive while the softmax runs
+  SpanData<W, G> vbuf[kPrefetch];
+#pragma unroll
+  for (int u = 0; u < kPrefetch; ++u) {
+    const uint32_t t = u * kRoundTokens + n;
+    vbuf[u] = fetch_span<W, G>(vp, u, t < cnt);
+  }
   for (uint32_t hg = 0; hg < R4; hg += 4u) {
     const uint32_t r = hg + kq;
     float* row = lds + r * chunk;
@@ -387,12 +394,7 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
   {
-    SpanData<W, G> buf[kPrefetch];
-#pragma unroll
-    for (int u = 0; u < kPrefetch; ++u) {
-      const uint32_t t = u * kRoundTokens + n;
-      buf[u] = fetch_span<W, G>(vp, u, t < cnt);
-    }
+    SpanData<W, G> (&buf)[kPrefetch] = vbuf;
     for (uint32_t rd0 = 0; rd0 < rounds; rd0 += kPrefetch) {
 #pragma unroll
       for (int u = 0; u < kPrefetch; ++u) {

@@ -2,6 +2,8 @@
 // and the decoder of one span of 32 values.  Internal to the GPU library.
 #pragma once
 
+#include <cstddef>
+
 #include "qkv_common.h"
 
 namespace qkv {
@@ -24,32 +26,47 @@ __device__ inline V card_load(const V* p) {
 
 // True when the header describes a layout-v1 card of the expected shape and grouping (flags word) that
 // fits in card_bytes; fills `g` from the header's class counts.  Uniform over the grid.
+//
+// Every wave of every kernel that reads a card starts here, so the latency of this function is
+// on the critical path of the first waves: the header's first 192 bytes are fetched as one batch
+// of loads from a uniform address (the field offsets are those of qkv_card_header_t), and the
+// checks are plain and-ed comparisons with a single branch, instead of a chain of short-circuit
+// tests that would each wait for its own load.
 __device__ inline bool card_geometry_from_header(const uint8_t* card, uint64_t card_bytes, uint32_t layers,
                                                  uint32_t kv_heads, uint32_t head_dim, uint32_t group_size,
                                                  uint64_t tokens, CardGeom& g, uint32_t want_flags = 0u) {
-  const qkv_card_header_t* h = reinterpret_cast<const qkv_card_header_t*>(card);
+  static_assert(offsetof(qkv_card_header_t, version) == 8 && offsetof(qkv_card_header_t, tokens) == 32 &&
+                offsetof(qkv_card_header_t, count) == 40 && offsetof(qkv_card_header_t, total_bytes) == 72 &&
+                offsetof(qkv_card_header_t, off_bits) == 80 && offsetof(qkv_card_header_t, off_codes) == 104 &&
+                offsetof(qkv_card_header_t, off_meta) == 128 && offsetof(qkv_card_header_t, off_fp16) == 152 &&
+                offsetof(qkv_card_header_t, flags) == 188, "word indices below follow the header's layout");
   const uint32_t* w = reinterpret_cast<const uint32_t*>(card);
-  bool ok = w[0] == 0x43564B51u && w[1] == 0x00445241u;          // "QKVC" "ARD\0"
-  ok = ok && h->version == QKV_CARD_VERSION && h->header_bytes == QKV_CARD_HEADER_BYTES && h->flags == want_flags;
-  ok = ok && h->layers == layers && h->kv_heads == kv_heads && h->head_dim == head_dim &&
-       h->group_size == group_size && h->tokens == tokens;
+  uint32_t hw[48];
+#pragma unroll
+  for (int i = 0; i < 48; ++i) hw[i] = w[i];
+  const auto u64_at = [&hw](int word) { return (uint64_t)hw[word] | ((uint64_t)hw[word + 1] << 32); };
+  uint32_t ok = (uint32_t)(hw[0] == 0x43564B51u) & (uint32_t)(hw[1] == 0x00445241u);          // "QKVC" "ARD\0"
+  ok &= (uint32_t)(hw[2] == QKV_CARD_VERSION) & (uint32_t)(hw[3] == QKV_CARD_HEADER_BYTES) & (uint32_t)(hw[47] == want_flags);
+  ok &= (uint32_t)(hw[4] == layers) & (uint32_t)(hw[5] == kv_heads) & (uint32_t)(hw[6] == head_dim) &
+        (uint32_t)(hw[7] == group_size) & (uint32_t)(u64_at(8) == tokens);
   uint64_t counts[4];
   uint64_t sum = 0;
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
-    counts[c] = h->count[c];
-    ok = ok && counts[c] <= tokens;
-    sum += ok ? counts[c] : 0;
+    counts[c] = u64_at(10 + 2 * c);
+    ok &= (uint32_t)(counts[c] <= tokens);       // with every count bounded the sum cannot wrap
+    sum += counts[c];
   }
-  ok = ok && sum == tokens;
+  ok &= (uint32_t)(sum == tokens);
   if (!ok) return false;
   build_geom(g, layers, kv_heads, head_dim, group_size, tokens, counts);
-  ok = g.total <= card_bytes && h->total_bytes == g.total;
-  ok = ok && h->off_bits == g.off_bits && h->off_slot == g.off_slot && h->off_order == g.off_order &&
-       h->off_fp16 == g.off_fp16;
+  ok = (uint32_t)(g.total <= card_bytes) & (uint32_t)(u64_at(18) == g.total);
+  ok &= (uint32_t)(u64_at(20) == g.off_bits) & (uint32_t)(u64_at(22) == g.off_slot) & (uint32_t)(u64_at(24) == g.off_order) &
+        (uint32_t)(u64_at(38) == g.off_fp16);
 #pragma unroll
-  for (int c = 0; c < 3; ++c) ok = ok && h->off_codes[c] == g.off_codes[c] && h->off_meta[c] == g.off_meta[c];
-  return ok;
+  for (int c = 0; c < 3; ++c)
+    ok &= (uint32_t)(u64_at(26 + 2 * c) == g.off_codes[c]) & (uint32_t)(u64_at(32 + 2 * c) == g.off_meta[c]);
+  return ok != 0u;
 }
 
 // decode = fp16( fma(code, scale, zero) ): an fp32 fma rounded to fp32, then rounded to
