@@ -410,12 +410,14 @@ int qkv_requantize(const void* card_in_dev, uint64_t card_in_bytes, const qkv_de
  * where K^, V^ are the dequantized fp16 values, exactly those qkv_unpack_dequant would
  * write (raw 16-bit rows as they are).  Scores are accumulated in fp32 from fp16 products,
  * the softmax and the weighted sum run in fp32; against the float64 definition a score is off
- * by at most 128 * 2^-24 * softmax_scale * sum_i |q_i K^_ti| (summation order only), which for
- * caches of ordinary magnitude leaves out within a few units in 1e-6 of max|V^|.
- *   card_dev, card_bytes, expect, status_dev: as for qkv_unpack_dequant; head_dim must be 128.
- *   q_dev:    device, fp16 [layers][q_heads][128], 16-byte aligned.  q_heads is a multiple of
- *             kv_heads, at most 16 query heads per kv head.
- *   out_dev:  device, float [layers][q_heads][128], 16-byte aligned, written in full.
+ * by at most head_dim * 2^-24 * softmax_scale * sum_i |q_i K^_ti| (summation order only), which
+ * for caches of ordinary magnitude leaves out within a few units in 1e-6 of max|V^|.
+ *   card_dev, card_bytes, expect, status_dev: as for qkv_unpack_dequant; head_dim 64, 128 or 256
+ *             (the kernel is laid out for 128: at 64 half of its lanes idle, at 256 it takes the
+ *             head dimension in two halves), keys grouped per token.
+ *   q_dev:    device, fp16 [layers][q_heads][head_dim], 16-byte aligned.  q_heads is a multiple
+ *             of kv_heads, at most 16 query heads per kv head.
+ *   out_dev:  device, float [layers][q_heads][head_dim], 16-byte aligned, written in full.
  *   lse_dev:  device, float [layers][q_heads], may be NULL.  With (out, lse) the caller can
  *             merge this result with attention over its own tokens.
  *   workspace_dev: device scratch of at least qkv_card_attend_workspace() bytes, 16-byte
@@ -426,7 +428,7 @@ int qkv_requantize(const void* card_in_dev, uint64_t card_in_bytes, const qkv_de
  * Several new tokens at once (a speculative window, a short suffix): every card token precedes
  * all of them, so no mask is needed and a "query head" may just as well be a (token, head) pair.
  * With S tokens and R = query heads per kv head, S * R <= 16, lay q out as
- * [layers][kv_heads][S][R][128] and pass q_heads = kv_heads * S * R; out and lse come back in
+ * [layers][kv_heads][S][R][head_dim] and pass q_heads = kv_heads * S * R; out and lse come back in
  * the same order.  The card is then read once for all S tokens.
  */
 int qkv_card_attend_workspace(const qkv_desc_t* expect, int32_t q_heads, uint64_t* bytes_out);

@@ -356,7 +356,7 @@ def card_attend_workspace(expect, q_heads):
 
 def card_attend(card, expect, q, softmax_scale, out, lse=None, workspace=None, status=None, card_nbytes=None,
                 stream=None):
-    """card: device uint8; q: device float16 [L, Hq, 128]; out: device float32 [L, Hq, 128]; lse: float32 [L, Hq]."""
+    """card: device uint8; q: device float16 [L, Hq, D]; out: device float32 [L, Hq, D]; lse: float32 [L, Hq]; D = 64, 128 or 256."""
     n = card.numel() if card_nbytes is None else int(card_nbytes)
     q_heads = q.shape[1]
     if workspace is None:

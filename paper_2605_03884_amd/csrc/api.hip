@@ -481,13 +481,12 @@ namespace {
 static int attend_workspace_floats(const qkv_desc_t* expect, int32_t q_heads, uint64_t* floats) {
   const int rc = check_desc(expect);
   if (rc) return rc;
-  if (expect->head_dim != 128) return QKV_ERR_SHAPE;
   if (q_heads < expect->kv_heads || q_heads % expect->kv_heads != 0 || q_heads / expect->kv_heads > 16)
     return QKV_ERR_SHAPE;
   const uint32_t rep = (uint32_t)(q_heads / expect->kv_heads);
   uint32_t chunk = 0, max_tasks = 0;
   attend_plan((uint64_t)expect->tokens, rep, (uint64_t)expect->layers * (uint64_t)expect->kv_heads, &chunk, &max_tasks);
-  *floats = (uint64_t)expect->layers * (uint64_t)expect->kv_heads * max_tasks * rep * (128u + 2u) + 4u;   // + verdict word
+  *floats = (uint64_t)expect->layers * (uint64_t)expect->kv_heads * max_tasks * rep * ((uint32_t)expect->head_dim + 2u) + 4u;   // + verdict word
   return QKV_OK;
 }
 }  // namespace

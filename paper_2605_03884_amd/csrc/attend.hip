@@ -87,11 +87,12 @@ struct LanePtrs {
   const uint8_t* pair;     // the group's (scale, zero)
 };
 
-template <int W, int G>
+// DS = spans of 32 values per token (head_dim / 32); sq = which of them, 0 .. DS - 1.
+template <int W, int G, int DS>
 __device__ inline LanePtrs lane_pointers(const uint8_t* card, const CardGeom& g, int c, uint64_t row0, uint32_t n,
-                                         uint32_t kq) {
+                                         uint32_t sq) {
   constexpr int GS = G / 32;
-  const uint64_t gsp = (row0 + n) * 4 + kq;
+  const uint64_t gsp = (row0 + n) * DS + sq;
   LanePtrs p;
   if (W == 16) {
     p.codes = card + g.off_fp16 + gsp * 64u;
@@ -104,7 +105,7 @@ __device__ inline LanePtrs lane_pointers(const uint8_t* card, const CardGeom& g,
 }
 
 // Issues the loads of the lane's span in round rd; nothing is decoded yet.  Zeros when !valid.
-template <int W, int G>
+template <int W, int G, int DS>
 __device__ inline SpanData<W, G> fetch_span(const LanePtrs& p, uint32_t rd, bool valid) {
   constexpr int GS = G / 32;
   constexpr int NW = (W == 16) ? 16 : W;
@@ -113,7 +114,7 @@ __device__ inline SpanData<W, G> fetch_span(const LanePtrs& p, uint32_t rd, bool
   for (int i = 0; i < NW; ++i) d.cw[i] = 0;
   d.pair = 0;
   if (valid) {
-    const uint8_t* src = p.codes + (uint64_t)rd * (kRoundTokens * 16u * W);       // 16 rows of 16 W bytes
+    const uint8_t* src = p.codes + (uint64_t)rd * (kRoundTokens * DS * 4u * W);    // 16 rows of DS spans of 4 W bytes
     if (W == 2) {
       const u32x2 t = *reinterpret_cast<const u32x2*>(src);
       d.cw[0] = t.x; d.cw[1] = t.y;
@@ -124,7 +125,7 @@ __device__ inline SpanData<W, G> fetch_span(const LanePtrs& p, uint32_t rd, bool
         d.cw[4 * h] = t.x; d.cw[4 * h + 1] = t.y; d.cw[4 * h + 2] = t.z; d.cw[4 * h + 3] = t.w;
       }
     }
-    if (W != 16) d.pair = *reinterpret_cast<const uint32_t*>(p.pair + (uint64_t)rd * (kRoundTokens * 16u / GS));
+    if (W != 16) d.pair = *reinterpret_cast<const uint32_t*>(p.pair + (uint64_t)rd * (kRoundTokens * DS * 4u / GS));
   }
   return d;
 }
@@ -250,7 +251,11 @@ __device__ inline float sum_over_quarters(float a0, float a1, float a2, float a3
 //            the four kt are added up once, at the end of the task.
 // Otherwise (5 .. 16 query heads per kv head) the 16 x 16 x 16 form is used with the tokens as rows
 // of the score product, so that a lane ends up with four consecutive tokens of one head.
-template <int W, int G, bool NARROW>
+//
+// DS = head_dim / 32 spans per token.  The lane mapping covers a slab of 128 dimensions (4 spans);
+// head_dim 256 is two slabs (the score of a round adds both up before it is stored, the value
+// pass sweeps the task once per slab), head_dim 64 half a slab (quarters 2 and 3 see zeros).
+template <int W, int G, bool NARROW, int DS>
 __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c, uint32_t pair, uint32_t j0, uint32_t j1,
                                    uint32_t lane, float* lds, uint8_t* tile, const uint8_t* table, uint64_t part) {
   const uint32_t n = lane & 15u, kq = lane >> 4;          // also (a, kt) of the value pass
@@ -262,65 +267,72 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   const uint64_t v_row0 = (uint64_t)(lh + pair) * n_c;
   const uint32_t cnt = j1 - j0;
   const uint32_t rounds = (cnt + kRoundTokens - 1) / kRoundTokens;
-  constexpr int kPrefetch = Prefetch<W>::kRounds;
-  const LanePtrs kp = lane_pointers<W, G>(a.card, g, c, k_row0 + j0, n, kq);
-  const LanePtrs vp = lane_pointers<W, G>(a.card, g, c, v_row0 + j0, n, kq);
+  constexpr int kPrefetch = (DS > 4 && W >= 8) ? 1 : Prefetch<W>::kRounds;     // two slabs in flight cost twice the registers
+  constexpr int S = (DS + 3) / 4;                          // slabs of 128 dimensions
+  constexpr uint32_t D = 32u * DS;
+  const bool lane_has_span = DS >= 4 || kq < (uint32_t)DS; // head_dim 64: quarters 2 and 3 hold nothing
+  LanePtrs kp[S];
+#pragma unroll
+  for (int sl = 0; sl < S; ++sl) kp[sl] = lane_pointers<W, G, DS>(a.card, g, c, k_row0 + j0, n, lane_has_span ? 4u * sl + kq : 0u);
 
-  // ---- q as MFMA operands: the lane holds q[head][32 kq .. 32 kq + 31] of head n (head n % 4 when
-  // NARROW); operand j is q[head][32 kq + 4 j .. + 3]
-  f16x4 qa[8];
-  {
+  // ---- q as MFMA operands: the lane holds q[head][128 sl + 32 kq .. + 31] of head n (head n % 4 when
+  // NARROW); operand j of slab sl is q[head][128 sl + 32 kq + 4 j .. + 3]
+  f16x4 qa[S][8];
+#pragma unroll
+  for (int sl = 0; sl < S; ++sl) {
     u32x4 raw[4];
 #pragma unroll
     for (int h = 0; h < 4; ++h) raw[h] = (u32x4)(0u);
     const uint32_t head = NARROW ? (n & 3u) : n;
-    if (head < R) {
+    if (head < R && lane_has_span) {
       const uint32_t l = pair / g.kv_heads, hh = pair - l * g.kv_heads;
-      const u32x4* src = reinterpret_cast<const u32x4*>(a.q + ((uint64_t)(l * a.q_heads + hh * R + head) * 128u + 32u * kq));
+      const u32x4* src = reinterpret_cast<const u32x4*>(a.q + ((uint64_t)(l * a.q_heads + hh * R + head) * D + 128u * sl + 32u * kq));
 #pragma unroll
       for (int h = 0; h < 4; ++h) raw[h] = src[h];
     }
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
-      qa[2 * h] = __builtin_bit_cast(f16x4, (u32x2){raw[h].x, raw[h].y});
-      qa[2 * h + 1] = __builtin_bit_cast(f16x4, (u32x2){raw[h].z, raw[h].w});
+      qa[sl][2 * h] = __builtin_bit_cast(f16x4, (u32x2){raw[h].x, raw[h].y});
+      qa[sl][2 * h + 1] = __builtin_bit_cast(f16x4, (u32x2){raw[h].z, raw[h].w});
     }
   }
 
   // ---- scores: lds[head * chunk + token] in log2 units, -inf for tokens past the task's end.
   // The loads of the next kPrefetch rounds are always in flight.
   {
-    SpanData<W, G> buf[kPrefetch];
+    SpanData<W, G> buf[kPrefetch][S];
 #pragma unroll
     for (int u = 0; u < kPrefetch; ++u) {
       const uint32_t t = u * kRoundTokens + n;
-      buf[u] = fetch_span<W, G>(kp, u, t < cnt);
+#pragma unroll
+      for (int sl = 0; sl < S; ++sl) buf[u][sl] = fetch_span<W, G, DS>(kp[sl], u, t < cnt && lane_has_span);
     }
     for (uint32_t rd0 = 0; rd0 < rounds; rd0 += kPrefetch) {
 #pragma unroll
       for (int u = 0; u < kPrefetch; ++u) {
         const uint32_t rd = rd0 + u;
         {                                          // rounds past the task's end see zeros and store -inf
-          uint32_t kb[16];
-          if constexpr (W == 2) decode_fetched_select<G>(buf[u], table, kb);
-          else decode_fetched<W, G>(buf[u], kb);
-          const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
-          buf[u] = fetch_span<W, G>(kp, rd + kPrefetch, tn < cnt);
           f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-          if constexpr (NARROW) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-              acc = __builtin_amdgcn_mfma_f32_4x4x4f16(qa[j], __builtin_bit_cast(f16x4, (u32x2){kb[2 * j], kb[2 * j + 1]}),
-                                                       acc, 0, 0, 0);
+          for (int sl = 0; sl < S; ++sl) {
+            uint32_t kb[16];
+            if constexpr (W == 2) decode_fetched_select<G>(buf[u][sl], table, kb);
+            else decode_fetched<W, G>(buf[u][sl], kb);
+            const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
+            buf[u][sl] = fetch_span<W, G, DS>(kp[sl], rd + kPrefetch, tn < cnt && lane_has_span);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              const f16x4 kj = __builtin_bit_cast(f16x4, (u32x2){kb[2 * j], kb[2 * j + 1]});
+              if constexpr (NARROW) acc = __builtin_amdgcn_mfma_f32_4x4x4f16(qa[sl][j], kj, acc, 0, 0, 0);
+              else acc = __builtin_amdgcn_mfma_f32_16x16x16f16(kj, qa[sl][j], acc, 0, 0, 0);
+            }
+          }
+          if constexpr (NARROW) {
             // head kq of token n
             const float sc = sum_over_quarters(acc.x, acc.y, acc.z, acc.w);
             const uint32_t t = rd * kRoundTokens + n;
             lds[kq * chunk + t] = (t < cnt) ? sc * a.scale_log2 : -INFINITY;
           } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-              acc = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, (u32x2){kb[2 * j], kb[2 * j + 1]}), qa[j],
-                                                          acc, 0, 0, 0);
             // tokens 4 kq .. 4 kq + 3 of head n
             const uint32_t t = rd * kRoundTokens + 4u * kq;
             if (n < R4) {
@@ -343,11 +355,12 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   // so the padded rounds stay inside the task's share of LDS.
   const uint32_t slots = (rounds + kPrefetch - 1) / kPrefetch * kPrefetch * kRoundTokens;
   // the first value rows are requested now, so that they arrive while the softmax runs
+  LanePtrs vp = lane_pointers<W, G, DS>(a.card, g, c, v_row0 + j0, n, lane_has_span ? kq : 0u);
   SpanData<W, G> vbuf[kPrefetch];
 #pragma unroll
   for (int u = 0; u < kPrefetch; ++u) {
     const uint32_t t = u * kRoundTokens + n;
-    vbuf[u] = fetch_span<W, G>(vp, u, t < cnt);
+    vbuf[u] = fetch_span<W, G, DS>(vp, u, t < cnt && lane_has_span);
   }
   for (uint32_t hg = 0; hg < R4; hg += 4u) {
     const uint32_t r = hg + kq;
@@ -390,6 +403,17 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   // behind the rows, as [quarter of the head dimension][token]: the 4 x 16 pairs (2-bit rows: 4 x 16 four-value tables)
   uint32_t* pairs_lds = reinterpret_cast<uint32_t*>(tile + ((W == 16) ? 0u : 16u * kRowBytes));
   const uint32_t w_head = NARROW ? (n & 3u) : n;            // the head whose weights this lane feeds the MFMA
+  // one sweep over the task's rows per slab of 128 output dimensions (the weights stay in LDS)
+#pragma unroll 1
+  for (int sl = 0; sl < S; ++sl) {
+  if (sl > 0) {
+    vp = lane_pointers<W, G, DS>(a.card, g, c, v_row0 + j0, n, 4u * sl + kq);
+#pragma unroll
+    for (int u = 0; u < kPrefetch; ++u) {
+      const uint32_t t = u * kRoundTokens + n;
+      vbuf[u] = fetch_span<W, G, DS>(vp, u, t < cnt);
+    }
+  }
   f32x4 acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -420,7 +444,7 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
             }
           }
           const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
-          buf[u] = fetch_span<W, G>(vp, rd + kPrefetch, tn < cnt);
+          buf[u] = fetch_span<W, G, DS>(vp, rd + kPrefetch, tn < cnt && lane_has_span);
 
           // pieces of lane (a, kt) = (n, kq): tokens 4 kt + i, dimensions 8 a .. 8 a + 7
           // B operands: b[e] = {V^[4kt][8a+e], V^[4kt+1][8a+e], V^[4kt+2][8a+e], V^[4kt+3][8a+e]}
@@ -514,8 +538,8 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
     float o[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = sum_over_quarters(acc[e].x, acc[e].y, acc[e].z, acc[e].w) * (1.0f / 16384.0f);
-    if (kq < R) {
-      f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + kq) * 128u + 8u * n);
+    if (kq < R && (DS >= 4 || n < 8u)) {          // head_dim 64: lanes n >= 8 stand for dimensions that do not exist
+      f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + kq) * D + 128u * sl + 8u * n);
       dst[0] = (f32x4){o[0], o[1], o[2], o[3]};
       dst[1] = (f32x4){o[4], o[5], o[6], o[7]};
     }
@@ -524,19 +548,20 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const uint32_t r = 4u * kq + i;
-      if (r < R) {
+      if (r < R && (DS >= 4 || n < 8u)) {
         float o[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = acc[e][i] * (1.0f / 16384.0f);
-        f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + r) * 128u + 8u * n);
+        f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + r) * D + 128u * sl + 8u * n);
         dst[0] = (f32x4){o[0], o[1], o[2], o[3]};
         dst[1] = (f32x4){o[4], o[5], o[6], o[7]};
       }
     }
   }
+  }   // slabs
 }
 
-template <int G, bool NARROW>
+template <int G, bool NARROW, int DS>
 __global__ __launch_bounds__(kAttendWaves * kWaveSize) __attribute__((amdgpu_waves_per_eu(2)))
 void attend_kernel(AttendArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[kAttendWaves][kLdsFloatsPerWave];
@@ -589,11 +614,11 @@ void attend_kernel(AttendArgs a) {
   uint8_t* my_table = my_tile + 16 * 40 + 512;
   if (cls == 0) {
     build_select_table(reinterpret_cast<u32x2*>(my_table), lane);
-    attend_task<2, G, NARROW>(a, g, 0, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+    attend_task<2, G, NARROW, DS>(a, g, 0, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
   }
-  if (cls == 1) attend_task<4, G, NARROW>(a, g, 1, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
-  if (cls == 2) attend_task<8, G, NARROW>(a, g, 2, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
-  if (cls == 3) attend_task<16, G, NARROW>(a, g, 3, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+  if (cls == 1) attend_task<4, G, NARROW, DS>(a, g, 1, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+  if (cls == 2) attend_task<8, G, NARROW, DS>(a, g, 2, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+  if (cls == 3) attend_task<16, G, NARROW, DS>(a, g, 3, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
 }
 
 // Merges the partials of one (layer, query head): thread d owns output dimension d.  The
@@ -601,10 +626,10 @@ void attend_kernel(AttendArgs a) {
 // weights cost no chain of dependent global loads.
 constexpr int kMergeBatch = 256;             // tasks whose (m, l) are held in LDS at a time
 
-__global__ __launch_bounds__(128) void attend_merge_kernel(AttendArgs a) {
+__global__ __launch_bounds__(256) void attend_merge_kernel(AttendArgs a) {
   __shared__ float ml_m[kMergeBatch], ml_l[kMergeBatch];
   if (*a.valid == 0) return;                           // header refused: outputs stay untouched
-  const uint32_t d = threadIdx.x;
+  const uint32_t d = threadIdx.x, D = a.head_dim;      // one thread per output dimension
   const uint32_t lq = blockIdx.x;                      // l * Hq + hq
   const uint32_t l = lq / a.q_heads, hq = lq - l * a.q_heads;
   const uint32_t h = hq / a.rep, r = hq - h * a.rep;
@@ -613,7 +638,7 @@ __global__ __launch_bounds__(128) void attend_merge_kernel(AttendArgs a) {
   for (uint32_t t0 = 0; t0 < a.max_tasks; t0 += kMergeBatch) {
     const uint32_t nb = min((uint32_t)kMergeBatch, a.max_tasks - t0);
     __syncthreads();
-    for (uint32_t t = d; t < nb; t += 128) {
+    for (uint32_t t = d; t < nb; t += D) {
       const float* ml = a.part_ml + ((part0 + t0 + t) * a.rep + r) * 2;
       ml_m[t] = ml[0];
       ml_l[t] = ml[1];
@@ -629,14 +654,14 @@ __global__ __launch_bounds__(128) void attend_merge_kernel(AttendArgs a) {
     // loads first, unconditionally (an empty task's slot holds anything: it is read but not used)
 #pragma unroll 8
     for (uint32_t t = 0; t < nb; ++t) {
-      const float v = a.part_o[((part0 + t0 + t) * a.rep + r) * 128u + d];
+      const float v = a.part_o[((part0 + t0 + t) * a.rep + r) * D + d];
       const float lt = ml_l[t];
       const float w = __builtin_amdgcn_exp2f(ml_m[t] - M);
       den += (lt > 0.f) ? w * lt : 0.f;
       num += (lt > 0.f) ? w * v : 0.f;
     }
   }
-  a.out[(uint64_t)lq * 128u + d] = num / den;
+  a.out[(uint64_t)lq * D + d] = num / den;
   if (d == 0 && a.lse) a.lse[lq] = (M + __builtin_log2f(den)) * 0.69314718055994530942f;
 }
 
@@ -705,32 +730,33 @@ hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeo
   a.scale_log2 = softmax_scale * 1.44269504088896340736f;
   attend_plan(expect.tokens, a.rep, (uint64_t)expect.layers * expect.kv_heads, &a.chunk, &a.max_tasks);
   const uint64_t pairs = (uint64_t)expect.layers * expect.kv_heads;
+  const uint32_t D = expect.head_dim;
   a.part_o = workspace;
-  a.part_ml = workspace + pairs * a.max_tasks * a.rep * 128u;
-  a.valid = reinterpret_cast<uint32_t*>(workspace + pairs * a.max_tasks * a.rep * 130u);
+  a.part_ml = workspace + pairs * a.max_tasks * a.rep * D;
+  a.valid = reinterpret_cast<uint32_t*>(workspace + pairs * a.max_tasks * a.rep * (D + 2u));
   a.out = out;
   a.lse = lse;
   a.status = status;
   const uint64_t waves = pairs * a.max_tasks;
   const dim3 grid((uint32_t)((waves + kAttendWaves - 1) / kAttendWaves)), block(kAttendWaves * kWaveSize);
   const bool narrow = a.rep <= 4u;             // grouped-query shapes: the 4 x 4 x 4 contraction
-  switch (expect.group_size) {
-    case 32:
-      if (narrow) hipLaunchKernelGGL((attend_kernel<32, true>), grid, block, 0, stream, a);
-      else hipLaunchKernelGGL((attend_kernel<32, false>), grid, block, 0, stream, a);
-      break;
-    case 64:
-      if (narrow) hipLaunchKernelGGL((attend_kernel<64, true>), grid, block, 0, stream, a);
-      else hipLaunchKernelGGL((attend_kernel<64, false>), grid, block, 0, stream, a);
-      break;
-    default:
-      if (narrow) hipLaunchKernelGGL((attend_kernel<128, true>), grid, block, 0, stream, a);
-      else hipLaunchKernelGGL((attend_kernel<128, false>), grid, block, 0, stream, a);
-      break;
+  const uint32_t G = expect.group_size;
+#define QKV_LAUNCH_ATTEND(GG, DSS)                                                                     \
+  do {                                                                                                 \
+    if (narrow) hipLaunchKernelGGL((attend_kernel<GG, true, DSS>), grid, block, 0, stream, a);         \
+    else hipLaunchKernelGGL((attend_kernel<GG, false, DSS>), grid, block, 0, stream, a);               \
+  } while (0)
+  if (D == 64u) {
+    if (G == 32u) QKV_LAUNCH_ATTEND(32, 2); else QKV_LAUNCH_ATTEND(64, 2);
+  } else if (D == 128u) {
+    if (G == 32u) QKV_LAUNCH_ATTEND(32, 4); else if (G == 64u) QKV_LAUNCH_ATTEND(64, 4); else QKV_LAUNCH_ATTEND(128, 4);
+  } else {
+    if (G == 32u) QKV_LAUNCH_ATTEND(32, 8); else if (G == 64u) QKV_LAUNCH_ATTEND(64, 8); else QKV_LAUNCH_ATTEND(128, 8);
   }
+#undef QKV_LAUNCH_ATTEND
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attend_merge_kernel, dim3(expect.layers * q_heads), dim3(128), 0, stream, a);
+  hipLaunchKernelGGL(attend_merge_kernel, dim3(expect.layers * q_heads), dim3(D), 0, stream, a);
   return hipGetLastError();
 }
 

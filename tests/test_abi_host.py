@@ -119,7 +119,11 @@ def test_argument_errors_are_reported_before_any_gpu_work():
     assert L.qkv_card_attend_workspace(ctypes.byref(d), 8, ctypes.byref(ws)) == 0 and ws.value > 0
     assert L.qkv_card_attend_workspace(ctypes.byref(d), 3, ctypes.byref(ws)) == -2      # not a multiple of kv_heads
     assert L.qkv_card_attend_workspace(ctypes.byref(d), 2 * 17, ctypes.byref(ws)) == -2  # more than 16 query heads per kv head
-    assert L.qkv_card_attend_workspace(ctypes.byref(qkv.Desc.make(2, 2, 64, 64, 32)), 8, ctypes.byref(ws)) == -2
+    ws64, ws256 = ctypes.c_uint64(0), ctypes.c_uint64(0)                                 # every supported head_dim
+    assert L.qkv_card_attend_workspace(ctypes.byref(qkv.Desc.make(2, 2, 64, 64, 32)), 8, ctypes.byref(ws64)) == 0
+    assert L.qkv_card_attend_workspace(ctypes.byref(qkv.Desc.make(2, 2, 64, 256, 32)), 8, ctypes.byref(ws256)) == 0
+    assert 0 < ws64.value < ws256.value
+    assert L.qkv_card_attend_workspace(ctypes.byref(qkv.Desc.make(2, 2, 64, 96, 32)), 8, ctypes.byref(ws)) == -2
 
 
 def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):

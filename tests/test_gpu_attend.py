@@ -58,15 +58,14 @@ def bounds(card, rd, q, scale):
     for l in range(rd.layers):
         for hq in range(q.shape[1]):
             ds = max(ds, float((Kf[l, hq // rep] @ np.abs(q[l, hq].astype(np.float64))).max()))
-    ds *= 128 * 2.0 ** -24 * scale
+    ds *= rd.head_dim * 2.0 ** -24 * scale
     vmax = float(np.abs(vq.view(np.float16).astype(np.float64)).max())
     base = (rd.tokens + 8) * 2.0 ** -24 + 2.0 ** -21
     return min((2 * ds + base) * vmax, 1e-5 * max(1.0, vmax)), min(ds + base, 1e-4)
 
 
-def check(L, H, rep, T, G, bits, seed, label, scale=None, kind="llama"):
+def check(L, H, rep, T, G, bits, seed, label, scale=None, kind="llama", D=128):
     say(label)
-    D = 128
     scale = D ** -0.5 if scale is None else scale
     rd, card = build_card(L, H, T, D, G, bits, seed, kind)
     q = np.random.default_rng(seed + 1).standard_normal((L, H * rep, D)).astype(np.float16)
@@ -100,6 +99,23 @@ def test_query_heads_per_kv_head(rep):
     T = 900
     bits = qkv_synth.make_bits_uniform_choice(T, 60 + rep).numpy()
     check(2, 2, rep, T, 32, bits, 600 + rep, "attend rep=%d" % rep)
+
+
+@pytest.mark.parametrize("D,G", [(64, 32), (64, 64), (256, 32), (256, 64), (256, 128)])
+@pytest.mark.parametrize("rep", [1, 4, 7])
+def test_other_head_dims(D, G, rep):
+    """head_dim 64 (half of the kernel's lanes idle) and 256 (two halves of 128), mixed widths, both MFMA forms."""
+    T = 600
+    bits = qkv_synth.make_bits_uniform_choice(T, 90 + D + rep).numpy()
+    check(2, 2, rep, T, G, bits, 900 + D + G + rep, "attend head_dim=%d G=%d rep=%d" % (D, G, rep), D=D)
+
+
+@pytest.mark.parametrize("D", [64, 256])
+@pytest.mark.parametrize("width", [2, 4, 8, 16])
+def test_other_head_dims_uniform_widths_and_ragged_tasks(D, width):
+    for T in (1, 17, 385, 1000):
+        check(1, 2, 4, T, 32, np.full(T, width, dtype=np.uint8), 950 + D + width + T,
+              "attend head_dim=%d uniform %d-bit T=%d" % (D, width, T), D=D)
 
 
 def test_skewed_mixes_empty_classes_and_scales():
@@ -177,9 +193,13 @@ def test_bad_header_leaves_outputs_untouched_and_errors_are_reported():
     with pytest.raises(qkv.QkvError) as e:       # 17 query heads per kv head
         qkv.card_attend_workspace(desc, 34)
     assert e.value.code == -2
-    with pytest.raises(qkv.QkvError) as e:       # head_dim other than 128
-        qkv.card_attend_workspace(qkv.Desc.make(L, H, T, 64, 32), 8)
+    with pytest.raises(qkv.QkvError) as e:       # a head_dim no card can have
+        qkv.card_attend_workspace(qkv.Desc.make(L, H, T, 96, 32), 8)
     assert e.value.code == -2
+    # a card of another head_dim than the caller expects is refused on the device, like any foreign header
+    q256 = np.zeros((L, H * rep, 256), dtype=np.float16)
+    out, lse, st = run_gpu(card, L, H, T, 256, G, q256, 1.0)
+    assert st == qkv.STATUS_BAD_HEADER and np.isnan(out).all() and np.isnan(lse).all()
 
 
 def test_benchmark_shape_8k():
