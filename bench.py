@@ -33,7 +33,7 @@ MALL_BYTES = 256 << 20    # memory-side cache: a working set below this is serve
 # taken: `sources` is a digest of the kernel sources at that time, and the figures are reported only while
 # the sources still have that digest (else `traffic` is null and says why).
 MEASURED_TRAFFIC = {
-    "llama8b_8k_b3": {"pack": 1341416735, "unpack": 1346870188, "sources": "bf0ee3e3439722cd",
+    "llama8b_8k_b3": {"pack": 1341414175, "unpack": 1346903980, "sources": "b7796b44ceff80e5",
                       "profile": "profiles/pack_unpack_llama8b_8k_b3_hbm_traffic.txt"},
 }
 KERNEL_SOURCES = ["pack.hip", "unpack.hip", "qkv_encode.h", "qkv_decode.h", "qkv_common.h"]
@@ -46,8 +46,8 @@ KERNEL_SOURCES = ["pack.hip", "unpack.hip", "qkv_encode.h", "qkv_decode.h", "qkv
 # (matrix instructions included), with the digest of the sources they were counted for.
 VECTOR_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 MEASURED_ATTEND = {
-    "llama8b_8k_b3": {"valu_instructions": 24134913, "mfma_instructions": 3182592, "lds_instructions": 2981888,
-                      "lds_active_cycles": 18725549, "lds_bank_conflict_cycles": 10719405, "sources": "56067185fbf40cc9",
+    "llama8b_8k_b3": {"valu_instructions": 24413697, "mfma_instructions": 3182592, "lds_instructions": 2981888,
+                      "lds_active_cycles": 18725549, "lds_bank_conflict_cycles": 10719405, "sources": "b082105f8e527c33",
                       "profile": "profiles/card_attend_llama8b_8k_b3.txt"},
 }
 ATTEND_SOURCES = ["attend.hip", "qkv_decode.h", "qkv_common.h"]

@@ -11,14 +11,15 @@
 // selection; thread i owns the consecutive tokens [i * per, (i + 1) * per).
 //
 // What this kernel costs is set by two things, neither of them memory: it runs once per launch,
-// so every line of its code is fetched cold (a fully unrolled version of 20 KB spent most of its
-// time waiting for instructions), and its sixteen waves share the issue slots of one compute
-// unit.  Hence: keys live in LDS and every sweep over them is a short rolled loop (T <= 8192;
-// longer sequences re-read the scores, which stay in cache); the first pass's histogram is kept
-// in 16 copies against same-word atomics (real scores share sign and exponent); later passes
-// test a key against all three cut prefixes and skip the counting code for waves that hold no
-// match; cuts whose prefixes still coincide share one histogram; a wave without ties needs three
-// comparisons per key for the widths.
+// so every line of its code is fetched cold, and its sixteen waves share the issue slots of one
+// compute unit.  Hence: a thread keeps its keys in registers, and the kernel is instantiated per
+// number of keys per thread (1, 2, 4, ... 32, chosen from the token count), so that a launch
+// touches only the code of its own size; the passes after the first are one rolled loop; the
+// first pass's histogram is kept in 16 copies against same-word atomics (real scores share sign
+// and exponent); later passes test a key against all three cut prefixes and skip the counting
+// code for waves that hold no match; cuts whose prefixes still coincide share one histogram; a
+// wave without ties needs three comparisons per key for the widths.  Beyond 32768 tokens an
+// older form takes over that re-reads the scores (they stay in cache) instead of holding keys.
 //
 // Planning variant (PLAN): once the cut keys are known every thread knows the widths of its own
 // tokens, so a block-wide prefix count of the classes gives the stable slots, order[] and the

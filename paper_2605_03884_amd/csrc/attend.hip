@@ -12,21 +12,24 @@
 // segment for one (layer, kv head), for all R query heads, and leaves an unnormalised
 // partial (running maximum m, sum l, sum of p.V^) in a workspace; a second kernel merges the
 // partials of each (layer, query head).  Inside a task, in rounds of 16 tokens:
-//   scores   lane (n, kq) = (token n of the round, quarter kq of the head dimension) reads its
-//            span of 32 codes and its pair, decodes it to 8 MFMA B operands, and eight
-//            v_mfma_f32_16x16x16_f16 accumulate q.K^ for 16 tokens x up to 16 query heads
-//            (the k index of the MFMA is a fixed permutation of the head dimension, applied to
-//            q and K^ alike).  Scores go to LDS.
+//   scores   lane (n, kq) = (token n of the round, quarter kq of a slab of 128 dimensions) reads
+//            its span of 32 codes and its pair, decodes it to 8 MFMA operands of 4 dimensions,
+//            and eight MFMAs accumulate q.K^ for the round's tokens and the kv head's query
+//            heads (the k index of the MFMA is a fixed permutation of the head dimension,
+//            applied to q and K^ alike).  Scores go to LDS.
 //   softmax  one maximum per head over the task's tokens, p = exp2(s - m) back into LDS.
 //   values   the round's packed V rows are regrouped through LDS (still packed) so that a lane
-//            holds 4 consecutive tokens x 8 dimensions, decodes them into 8 MFMA B operands,
+//            holds 4 consecutive tokens x 8 dimensions, decodes them into 8 MFMA operands,
 //            and 2 x 8 MFMAs (softmax weights as an fp16 high part and the fp16 remainder, into
-//            the same accumulators) add p.V^ for 16 tokens x up to 16 query heads.
+//            the same accumulators) add p.V^.
+// Which MFMA: v_mfma_f32_4x4x4_16b_f16 for up to 4 query heads per kv head, the 16 x 16 x 16
+// form for 5 .. 16 (see attend_task).  head_dim 256 is two slabs, head_dim 64 half a one.
 // 2-bit spans, most of a card at low budgets, are not decoded by arithmetic: a group has only
-// four decoded values, which are computed once, and a selector table in LDS indexed by a byte
-// of four codes drives v_perm_b32 to pick them.  Rounds are taken in whole groups of 4 / 3 / 2 /
+// four decoded values, which are computed once, and a selector table in LDS indexed by a byte of
+// four codes drives v_perm_b32 to pick them.  Rounds are taken in whole groups of 4 / 3 / 2 /
 // 1 (at 2 / 4 / 8 / 16 bits) without a branch in between; rounds past a task's end see zeros and
-// count as -inf.  114 registers and 10 KiB of LDS per wave: four waves per SIMD.
+// count as -inf.  About 106 registers (head_dim 256: up to 128) and 10 KiB of LDS per wave: four
+// waves per SIMD.
 
 #include <atomic>
 
