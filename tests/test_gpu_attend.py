@@ -102,7 +102,7 @@ def test_query_heads_per_kv_head(rep):
 
 
 @pytest.mark.parametrize("D,G", [(64, 32), (64, 64), (256, 32), (256, 64), (256, 128)])
-@pytest.mark.parametrize("rep", [1, 4, 7])
+@pytest.mark.parametrize("rep", [1, 4, 7, 16])
 def test_other_head_dims(D, G, rep):
     """head_dim 64 (half of the kernel's lanes idle) and 256 (two halves of 128), mixed widths, both MFMA forms."""
     T = 600
