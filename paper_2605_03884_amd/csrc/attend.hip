@@ -409,159 +409,159 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   // one sweep over the task's rows per slab of 128 output dimensions (the weights stay in LDS)
 #pragma unroll 1
   for (int sl = 0; sl < S; ++sl) {
-  if (sl > 0) {
-    vp = lane_pointers<W, G, DS>(a.card, g, c, v_row0 + j0, n, 4u * sl + kq);
-#pragma unroll
-    for (int u = 0; u < kPrefetch; ++u) {
-      const uint32_t t = u * kRoundTokens + n;
-      vbuf[u] = fetch_span<W, G, DS>(vp, u, t < cnt);
-    }
-  }
-  f32x4 acc[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) acc[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  {
-    SpanData<W, G> (&buf)[kPrefetch] = vbuf;
-    for (uint32_t rd0 = 0; rd0 < rounds; rd0 += kPrefetch) {
+    if (sl > 0) {
+      vp = lane_pointers<W, G, DS>(a.card, g, c, v_row0 + j0, n, 4u * sl + kq);
 #pragma unroll
       for (int u = 0; u < kPrefetch; ++u) {
-        const uint32_t rd = rd0 + u;
-        {                                          // rounds past the task's end add zero weights times zeros
-          // rows into LDS as they were loaded: token n, quarter kq
-          {
-            uint8_t* dst = tile + n * kRowBytes + kq * (4u * W);
-            if constexpr (W == 2) {
-              *reinterpret_cast<u32x2*>(dst) = (u32x2){buf[u].cw[0], buf[u].cw[1]};
-            } else {
+        const uint32_t t = u * kRoundTokens + n;
+        vbuf[u] = fetch_span<W, G, DS>(vp, u, t < cnt);
+      }
+    }
+    f32x4 acc[8];
 #pragma unroll
-              for (int h = 0; h < (W == 16 ? 16 : W) / 4; ++h)
-                reinterpret_cast<u32x4*>(dst)[h] = (u32x4){buf[u].cw[4 * h], buf[u].cw[4 * h + 1], buf[u].cw[4 * h + 2], buf[u].cw[4 * h + 3]};
+    for (int e = 0; e < 8; ++e) acc[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    {
+      SpanData<W, G> (&buf)[kPrefetch] = vbuf;
+      for (uint32_t rd0 = 0; rd0 < rounds; rd0 += kPrefetch) {
+#pragma unroll
+        for (int u = 0; u < kPrefetch; ++u) {
+          const uint32_t rd = rd0 + u;
+          {                                          // rounds past the task's end add zero weights times zeros
+            // rows into LDS as they were loaded: token n, quarter kq
+            {
+              uint8_t* dst = tile + n * kRowBytes + kq * (4u * W);
+              if constexpr (W == 2) {
+                *reinterpret_cast<u32x2*>(dst) = (u32x2){buf[u].cw[0], buf[u].cw[1]};
+              } else {
+#pragma unroll
+                for (int h = 0; h < (W == 16 ? 16 : W) / 4; ++h)
+                  reinterpret_cast<u32x4*>(dst)[h] = (u32x4){buf[u].cw[4 * h], buf[u].cw[4 * h + 1], buf[u].cw[4 * h + 2], buf[u].cw[4 * h + 3]};
+              }
+              if constexpr (W == 2 && kSelectV) {
+                // the span's four decoded values instead of its (scale, zero): x_k = fp16(fma(k, scale, zero))
+                const float s = half_bits_to_float(buf[u].pair & 0xFFFFu);
+                const float z = half_bits_to_float(buf[u].pair >> 16);
+                reinterpret_cast<u32x2*>(pairs_lds)[kq * 16u + n] = (u32x2){decode_pair(0.0f, 1.0f, s, z), decode_pair(2.0f, 3.0f, s, z)};
+              } else if constexpr (W != 16) {
+                pairs_lds[kq * 16u + n] = buf[u].pair;
+              }
             }
-            if constexpr (W == 2 && kSelectV) {
-              // the span's four decoded values instead of its (scale, zero): x_k = fp16(fma(k, scale, zero))
-              const float s = half_bits_to_float(buf[u].pair & 0xFFFFu);
-              const float z = half_bits_to_float(buf[u].pair >> 16);
-              reinterpret_cast<u32x2*>(pairs_lds)[kq * 16u + n] = (u32x2){decode_pair(0.0f, 1.0f, s, z), decode_pair(2.0f, 3.0f, s, z)};
-            } else if constexpr (W != 16) {
-              pairs_lds[kq * 16u + n] = buf[u].pair;
-            }
-          }
-          const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
-          buf[u] = fetch_span<W, G, DS>(vp, rd + kPrefetch, tn < cnt && lane_has_span);
+            const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
+            buf[u] = fetch_span<W, G, DS>(vp, rd + kPrefetch, tn < cnt && lane_has_span);
 
-          // pieces of lane (a, kt) = (n, kq): tokens 4 kt + i, dimensions 8 a .. 8 a + 7
-          // B operands: b[e] = {V^[4kt][8a+e], V^[4kt+1][8a+e], V^[4kt+2][8a+e], V^[4kt+3][8a+e]}
-          u32x2 b[8];
-          if constexpr (W == 2 && kSelectV) {
-            // by selection: the piece's two code bytes index the selector table, the selectors pick the
-            // values out of the token's four; then pairs of dimensions are turned into pairs of tokens
-            uint32_t tv[4][4];                     // token i, dimension pair m: {V^[8a+2m], V^[8a+2m+1]}
-            const u32x4* xs = reinterpret_cast<const u32x4*>(pairs_lds) + ((n >> 2) * 16u + 4u * kq) / 2u;
-            const u32x4 x01 = xs[0], x23 = xs[1];  // the four-value tables of tokens 4 kt .. 4 kt + 3 for this lane's dimensions
-            const uint32_t xl[4] = {x01.x, x01.z, x23.x, x23.z}, xh[4] = {x01.y, x01.w, x23.y, x23.w};
+            // pieces of lane (a, kt) = (n, kq): tokens 4 kt + i, dimensions 8 a .. 8 a + 7
+            // B operands: b[e] = {V^[4kt][8a+e], V^[4kt+1][8a+e], V^[4kt+2][8a+e], V^[4kt+3][8a+e]}
+            u32x2 b[8];
+            if constexpr (W == 2 && kSelectV) {
+              // by selection: the piece's two code bytes index the selector table, the selectors pick the
+              // values out of the token's four; then pairs of dimensions are turned into pairs of tokens
+              uint32_t tv[4][4];                     // token i, dimension pair m: {V^[8a+2m], V^[8a+2m+1]}
+              const u32x4* xs = reinterpret_cast<const u32x4*>(pairs_lds) + ((n >> 2) * 16u + 4u * kq) / 2u;
+              const u32x4 x01 = xs[0], x23 = xs[1];  // the four-value tables of tokens 4 kt .. 4 kt + 3 for this lane's dimensions
+              const uint32_t xl[4] = {x01.x, x01.z, x23.x, x23.z}, xh[4] = {x01.y, x01.w, x23.y, x23.w};
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const uint32_t piece = *reinterpret_cast<const uint16_t*>(tile + (4u * kq + i) * kRowBytes + n * 2u);
+                const u32x2 s0 = *reinterpret_cast<const u32x2*>(table + byte_times8<0>(piece));
+                const u32x2 s1 = *reinterpret_cast<const u32x2*>(table + byte_times8<1>(piece));
+                tv[i][0] = __builtin_amdgcn_perm(xh[i], xl[i], s0.x);
+                tv[i][1] = __builtin_amdgcn_perm(xh[i], xl[i], s0.y);
+                tv[i][2] = __builtin_amdgcn_perm(xh[i], xl[i], s1.x);
+                tv[i][3] = __builtin_amdgcn_perm(xh[i], xl[i], s1.y);
+              }
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;      // high or low halves of two words
+                b[e].x = __builtin_amdgcn_perm(tv[1][e >> 1], tv[0][e >> 1], sel);
+                b[e].y = __builtin_amdgcn_perm(tv[3][e >> 1], tv[2][e >> 1], sel);
+              }
+            } else {
+            Piece<W> pc[4];
+            uint32_t pr[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              const uint32_t piece = *reinterpret_cast<const uint16_t*>(tile + (4u * kq + i) * kRowBytes + n * 2u);
-              const u32x2 s0 = *reinterpret_cast<const u32x2*>(table + byte_times8<0>(piece));
-              const u32x2 s1 = *reinterpret_cast<const u32x2*>(table + byte_times8<1>(piece));
-              tv[i][0] = __builtin_amdgcn_perm(xh[i], xl[i], s0.x);
-              tv[i][1] = __builtin_amdgcn_perm(xh[i], xl[i], s0.y);
-              tv[i][2] = __builtin_amdgcn_perm(xh[i], xl[i], s1.x);
-              tv[i][3] = __builtin_amdgcn_perm(xh[i], xl[i], s1.y);
+              const uint8_t* src = tile + (4u * kq + i) * kRowBytes + n * W;
+              if constexpr (W == 2) pc[i].w[0] = *reinterpret_cast<const uint16_t*>(src);
+              else if constexpr (W == 4) pc[i].w[0] = *reinterpret_cast<const uint32_t*>(src);
+              else if constexpr (W == 8) { const u32x2 t = *reinterpret_cast<const u32x2*>(src); pc[i].w[0] = t.x; pc[i].w[1] = t.y; }
+              else { const u32x4 t = *reinterpret_cast<const u32x4*>(src); pc[i].w[0] = t.x; pc[i].w[1] = t.y; pc[i].w[2] = t.z; pc[i].w[3] = t.w; }
             }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-              const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;      // high or low halves of two words
-              b[e].x = __builtin_amdgcn_perm(tv[1][e >> 1], tv[0][e >> 1], sel);
-              b[e].y = __builtin_amdgcn_perm(tv[3][e >> 1], tv[2][e >> 1], sel);
+            if constexpr (W != 16) {
+              const u32x4 t = *reinterpret_cast<const u32x4*>(pairs_lds + (n >> 2) * 16u + 4u * kq);
+              pr[0] = t.x; pr[1] = t.y; pr[2] = t.z; pr[3] = t.w;
             }
-          } else {
-          Piece<W> pc[4];
-          uint32_t pr[4] = {0u, 0u, 0u, 0u};
+            if constexpr (W == 16) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const uint8_t* src = tile + (4u * kq + i) * kRowBytes + n * W;
-            if constexpr (W == 2) pc[i].w[0] = *reinterpret_cast<const uint16_t*>(src);
-            else if constexpr (W == 4) pc[i].w[0] = *reinterpret_cast<const uint32_t*>(src);
-            else if constexpr (W == 8) { const u32x2 t = *reinterpret_cast<const u32x2*>(src); pc[i].w[0] = t.x; pc[i].w[1] = t.y; }
-            else { const u32x4 t = *reinterpret_cast<const u32x4*>(src); pc[i].w[0] = t.x; pc[i].w[1] = t.y; pc[i].w[2] = t.z; pc[i].w[3] = t.w; }
-          }
-          if constexpr (W != 16) {
-            const u32x4 t = *reinterpret_cast<const u32x4*>(pairs_lds + (n >> 2) * 16u + 4u * kq);
-            pr[0] = t.x; pr[1] = t.y; pr[2] = t.z; pr[3] = t.w;
-          }
-          if constexpr (W == 16) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-              const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;      // high or low halves of two words
-              b[e].x = __builtin_amdgcn_perm(pc[1].w[e >> 1], pc[0].w[e >> 1], sel);
-              b[e].y = __builtin_amdgcn_perm(pc[3].w[e >> 1], pc[2].w[e >> 1], sel);
-            }
-          } else {
-            float c0[8], c1[8], c2[8], c3[8];
-            piece_codes<W>(pc[0], pc[1], c0, c1);
-            piece_codes<W>(pc[2], pc[3], c2, c3);
-            const float s0 = half_bits_to_float(pr[0] & 0xFFFFu), z0 = half_bits_to_float(pr[0] >> 16);
-            const float s1 = half_bits_to_float(pr[1] & 0xFFFFu), z1 = half_bits_to_float(pr[1] >> 16);
-            const float s2 = half_bits_to_float(pr[2] & 0xFFFFu), z2 = half_bits_to_float(pr[2] >> 16);
-            const float s3 = half_bits_to_float(pr[3] & 0xFFFFu), z3 = half_bits_to_float(pr[3] >> 16);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-              b[e].x = decode_two_tokens(c0[e], s0, z0, c1[e], s1, z1);
-              b[e].y = decode_two_tokens(c2[e], s2, z2, c3[e], s3, z3);
-            }
-          }
-          }
-          // A operands: the weights of head w_head for tokens 4 kt .. 4 kt + 3, high parts and low parts
-          u32x4 pw = (u32x4)(0u);
-          if (w_head < R4) pw = *reinterpret_cast<const u32x4*>(lds + w_head * chunk + rd * kRoundTokens + 4u * kq);
-          const f16x4 a_hi = __builtin_bit_cast(f16x4, (u32x2){__builtin_amdgcn_perm(pw.y, pw.x, 0x05040100u),
-                                                               __builtin_amdgcn_perm(pw.w, pw.z, 0x05040100u)});
-          const f16x4 a_lo = __builtin_bit_cast(f16x4, (u32x2){__builtin_amdgcn_perm(pw.y, pw.x, 0x07060302u),
-                                                               __builtin_amdgcn_perm(pw.w, pw.z, 0x07060302u)});
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const f16x4 be = __builtin_bit_cast(f16x4, b[e]);
-            if constexpr (NARROW) {
-              acc[e] = __builtin_amdgcn_mfma_f32_4x4x4f16(a_hi, be, acc[e], 0, 0, 0);
-              acc[e] = __builtin_amdgcn_mfma_f32_4x4x4f16(a_lo, be, acc[e], 0, 0, 0);
+              for (int e = 0; e < 8; ++e) {
+                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;      // high or low halves of two words
+                b[e].x = __builtin_amdgcn_perm(pc[1].w[e >> 1], pc[0].w[e >> 1], sel);
+                b[e].y = __builtin_amdgcn_perm(pc[3].w[e >> 1], pc[2].w[e >> 1], sel);
+              }
             } else {
-              acc[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(a_hi, be, acc[e], 0, 0, 0);
-              acc[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(a_lo, be, acc[e], 0, 0, 0);
+              float c0[8], c1[8], c2[8], c3[8];
+              piece_codes<W>(pc[0], pc[1], c0, c1);
+              piece_codes<W>(pc[2], pc[3], c2, c3);
+              const float s0 = half_bits_to_float(pr[0] & 0xFFFFu), z0 = half_bits_to_float(pr[0] >> 16);
+              const float s1 = half_bits_to_float(pr[1] & 0xFFFFu), z1 = half_bits_to_float(pr[1] >> 16);
+              const float s2 = half_bits_to_float(pr[2] & 0xFFFFu), z2 = half_bits_to_float(pr[2] >> 16);
+              const float s3 = half_bits_to_float(pr[3] & 0xFFFFu), z3 = half_bits_to_float(pr[3] >> 16);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                b[e].x = decode_two_tokens(c0[e], s0, z0, c1[e], s1, z1);
+                b[e].y = decode_two_tokens(c2[e], s2, z2, c3[e], s3, z3);
+              }
+            }
+            }
+            // A operands: the weights of head w_head for tokens 4 kt .. 4 kt + 3, high parts and low parts
+            u32x4 pw = (u32x4)(0u);
+            if (w_head < R4) pw = *reinterpret_cast<const u32x4*>(lds + w_head * chunk + rd * kRoundTokens + 4u * kq);
+            const f16x4 a_hi = __builtin_bit_cast(f16x4, (u32x2){__builtin_amdgcn_perm(pw.y, pw.x, 0x05040100u),
+                                                                 __builtin_amdgcn_perm(pw.w, pw.z, 0x05040100u)});
+            const f16x4 a_lo = __builtin_bit_cast(f16x4, (u32x2){__builtin_amdgcn_perm(pw.y, pw.x, 0x07060302u),
+                                                                 __builtin_amdgcn_perm(pw.w, pw.z, 0x07060302u)});
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const f16x4 be = __builtin_bit_cast(f16x4, b[e]);
+              if constexpr (NARROW) {
+                acc[e] = __builtin_amdgcn_mfma_f32_4x4x4f16(a_hi, be, acc[e], 0, 0, 0);
+                acc[e] = __builtin_amdgcn_mfma_f32_4x4x4f16(a_lo, be, acc[e], 0, 0, 0);
+              } else {
+                acc[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(a_hi, be, acc[e], 0, 0, 0);
+                acc[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(a_lo, be, acc[e], 0, 0, 0);
+              }
             }
           }
         }
       }
     }
-  }
-  if constexpr (NARROW) {
-    // the lane holds, for its own tokens only, out[heads 0 .. 3][dimensions 8 n .. 8 n + 7]: add up the four kt;
-    // lane (n, kq) is left with head kq
-    // (every lane takes part in the sums; only the stores are conditional)
-    float o[8];
+    if constexpr (NARROW) {
+      // the lane holds, for its own tokens only, out[heads 0 .. 3][dimensions 8 n .. 8 n + 7]: add up the four kt;
+      // lane (n, kq) is left with head kq
+      // (every lane takes part in the sums; only the stores are conditional)
+      float o[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = sum_over_quarters(acc[e].x, acc[e].y, acc[e].z, acc[e].w) * (1.0f / 16384.0f);
-    if (kq < R && (DS >= 4 || n < 8u)) {          // head_dim 64: lanes n >= 8 stand for dimensions that do not exist
-      f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + kq) * D + 128u * sl + 8u * n);
-      dst[0] = (f32x4){o[0], o[1], o[2], o[3]};
-      dst[1] = (f32x4){o[4], o[5], o[6], o[7]};
-    }
-  } else {
-    // the lane holds out[heads 4 kq .. 4 kq + 3][dimensions 8 n .. 8 n + 7]
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t r = 4u * kq + i;
-      if (r < R && (DS >= 4 || n < 8u)) {
-        float o[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = acc[e][i] * (1.0f / 16384.0f);
-        f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + r) * D + 128u * sl + 8u * n);
+      for (int e = 0; e < 8; ++e) o[e] = sum_over_quarters(acc[e].x, acc[e].y, acc[e].z, acc[e].w) * (1.0f / 16384.0f);
+      if (kq < R && (DS >= 4 || n < 8u)) {          // head_dim 64: lanes n >= 8 stand for dimensions that do not exist
+        f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + kq) * D + 128u * sl + 8u * n);
         dst[0] = (f32x4){o[0], o[1], o[2], o[3]};
         dst[1] = (f32x4){o[4], o[5], o[6], o[7]};
       }
+    } else {
+      // the lane holds out[heads 4 kq .. 4 kq + 3][dimensions 8 n .. 8 n + 7]
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t r = 4u * kq + i;
+        if (r < R && (DS >= 4 || n < 8u)) {
+          float o[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = acc[e][i] * (1.0f / 16384.0f);
+          f32x4* dst = reinterpret_cast<f32x4*>(a.part_o + (part * R + r) * D + 128u * sl + 8u * n);
+          dst[0] = (f32x4){o[0], o[1], o[2], o[3]};
+          dst[1] = (f32x4){o[4], o[5], o[6], o[7]};
+        }
+      }
     }
   }
-  }   // slabs
 }
 
 template <int G, bool NARROW, int DS>
