@@ -523,17 +523,18 @@ def main():
     # beyond the handoff itself: one decode step's attention taken directly over the card
     # (32 query heads on 8 kv heads as in Llama-3.1-8B), timed on its own
     attend = None
-    if D == 128 and not h.kc and not args.handoff_only:
+    if D == 128 and not args.handoff_only:
         rep = 4
         qv = qkv_synth.normal(h.cfg["data_seed"] + 17, 9, 0, L * H * rep * D, dev).view(L, H * rep, D).to(torch.float16)
         a_out = torch.empty((L, H * rep, D), dtype=torch.float32, device=dev)
         a_lse = torch.empty((L, H * rep), dtype=torch.float32, device=dev)
         ws = torch.empty(qkv.card_attend_workspace(desc, H * rep), dtype=torch.uint8, device=dev)
         n_att = max(10, args.steps // 4)
-        att_ms = timed_calls(lambda: qkv.card_attend(card, desc, qv, D ** -0.5, a_out, lse=a_lse, workspace=ws), n_att,
+        attend_call = qkv.card_attend_kc if h.kc else qkv.card_attend      # by the grouping of the card's keys
+        att_ms = timed_calls(lambda: attend_call(card, desc, qv, D ** -0.5, a_out, lse=a_lse, workspace=ws), n_att,
                              warm=max(3, args.warmup // 4))
         att_bytes = card_bytes + qv.numel() * 2 + a_out.numel() * 4 + a_lse.numel() * 4
-        attend = {"call": "qkv_card_attend", "q_heads": H * rep, "avg_ms": round(att_ms, 4), "calls": n_att,
+        attend = {"call": "qkv_card_attend_kc" if h.kc else "qkv_card_attend", "q_heads": H * rep, "avg_ms": round(att_ms, 4), "calls": n_att,
                   "algorithmic_bytes": att_bytes, "achieved_gbs": round(att_bytes / (att_ms * 1e-3) / 1e9, 1),
                   "frac_hbm_peak": round(att_bytes / (att_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                   "dense_cache_gbs_equivalent": round(kv_bytes / (att_ms * 1e-3) / 1e9, 1)}

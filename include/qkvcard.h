@@ -321,7 +321,7 @@ int qkv_unpack_dequant(const void* card_dev, uint64_t card_bytes, const qkv_desc
  * (QKV_ERR_COUNTS) counts naming exactly one of the widths 2, 4, 8 for all tokens.  A card of
  * one grouping handed to the other grouping's call is refused on the device (QKV_STATUS_BAD_HEADER,
  * nothing written); qkv_inject_layers takes either grouping (its keys_per_channel field says
- * which), qkv_card_attend reads per-token groups only.
+ * which), and qkv_card_attend_kc is qkv_card_attend for this grouping.
  */
 int qkv_quantize_pack_kc(const qkv_desc_t* desc, const void* k_dev, const void* v_dev, const uint8_t* bits_dev,
                          const int64_t counts[4], void* card_dev, uint64_t card_capacity, void* stream);
@@ -436,6 +436,20 @@ int qkv_card_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t*
                     const void* q_dev, int32_t q_heads, float softmax_scale,
                     float* out_dev, float* lse_dev, void* workspace_dev, uint64_t workspace_bytes,
                     uint32_t* status_dev, void* stream);
+
+/*
+ * qkv_card_attend for cards whose keys are grouped per channel (those of qkv_quantize_pack_kc; paper
+ * Sec. 2 names the scheme, Sec. 4.3 the goal).  Same arguments, same results to the same bound, under
+ * the shape rules of qkv_quantize_pack_kc (group_size 32: QKV_ERR_GROUP otherwise; head_dim 64 or 128,
+ * tokens a multiple of 32, of 64 at head_dim 64: QKV_ERR_SHAPE otherwise).  There a key group holds 32
+ * tokens of one channel, so the scores contract over the card's rows, the way the weighted sum of the
+ * values does.  A card of the other grouping is refused on the device (QKV_STATUS_BAD_HEADER, nothing
+ * written), and so does qkv_card_attend refuse a card of this one; qkv_card_flags says which a card is.
+ */
+int qkv_card_attend_kc(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect,
+                       const void* q_dev, int32_t q_heads, float softmax_scale,
+                       float* out_dev, float* lse_dev, void* workspace_dev, uint64_t workspace_bytes,
+                       uint32_t* status_dev, void* stream);
 
 /*
  * qkv_card_attend for callers that cannot allocate device memory - code under HIP graph capture,

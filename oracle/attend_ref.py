@@ -46,7 +46,9 @@ def attend_dense(q, K, V, scale):
     return o, lse
 
 
-def card_attend(card, desc, q, scale):
-    """card: uint8 array; desc: ref.RefDesc of the card; q: float16 [L, Hq, D]."""
-    k_bits, v_bits = ref.unpack_dequant(card, desc)
+def card_attend(card, desc, q, scale, keys_per_channel=False):
+    """card: uint8 array; desc: ref.RefDesc of the card; q: float16 [L, Hq, D].  keys_per_channel: the card is a
+    uniform card whose key groups run along the tokens of one channel (Sec. 2's per-channel key scheme); the
+    definition is the same, over the cache that card dequantizes to."""
+    k_bits, v_bits = (ref.unpack_dequant_kc if keys_per_channel else ref.unpack_dequant)(card, desc)
     return attend_dense(q, k_bits.view(np.float16), v_bits.view(np.float16), scale)

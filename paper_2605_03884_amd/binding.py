@@ -131,6 +131,9 @@ def lib():
     L.qkv_card_attend.restype = ctypes.c_int
     L.qkv_card_attend.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, ctypes.c_int32, ctypes.c_float, vp, vp,
                                   vp, ctypes.c_uint64, vp, vp]
+    L.qkv_card_attend_kc.restype = ctypes.c_int
+    L.qkv_card_attend_kc.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, ctypes.c_int32, ctypes.c_float, vp, vp,
+                                  vp, ctypes.c_uint64, vp, vp]
     L.qkv_card_attend_static.restype = ctypes.c_int
     L.qkv_card_attend_static.argtypes = [vp, ctypes.c_uint64, ctypes.POINTER(Desc), vp, ctypes.c_int32, ctypes.c_float, vp, vp,
                                          vp, vp]
@@ -367,6 +370,22 @@ def card_attend(card, expect, q, softmax_scale, out, lse=None, workspace=None, s
                                  _dev_ptr(q, torch.float16, "q"), int(q_heads), float(softmax_scale),
                                  _dev_ptr(out, torch.float32, "out"), lp, _dev_ptr(workspace, torch.uint8, "workspace"),
                                  workspace.numel(), sp, _stream(stream)), "qkv_card_attend")
+    return out, lse
+
+
+def card_attend_kc(card, expect, q, softmax_scale, out, lse=None, workspace=None, status=None, card_nbytes=None,
+                   stream=None):
+    """card_attend for a card whose keys are grouped per channel (made by quantize_pack_kc)."""
+    n = card.numel() if card_nbytes is None else int(card_nbytes)
+    q_heads = q.shape[1]
+    if workspace is None:
+        workspace = torch.empty(card_attend_workspace(expect, q_heads), dtype=torch.uint8, device=card.device)
+    lp = ctypes.c_void_p(0) if lse is None else _dev_ptr(lse, torch.float32, "lse")
+    sp = ctypes.c_void_p(0) if status is None else _dev_ptr(status, None, "status")
+    _check(lib().qkv_card_attend_kc(_dev_ptr(card, torch.uint8, "card"), n, ctypes.byref(expect),
+                                    _dev_ptr(q, torch.float16, "q"), int(q_heads), float(softmax_scale),
+                                    _dev_ptr(out, torch.float32, "out"), lp, _dev_ptr(workspace, torch.uint8, "workspace"),
+                                    workspace.numel(), sp, _stream(stream)), "qkv_card_attend_kc")
     return out, lse
 
 

@@ -505,10 +505,14 @@ namespace {
 // the floats of scratch the launch needs.
 static int prepare_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, const void* q_dev, int32_t q_heads,
                    float softmax_scale, const float* out_dev, const float* lse_dev, const uint32_t* status_dev, CardGeom& g,
-                   uint64_t& floats) {
+                   uint64_t& floats, bool keys_per_channel = false) {
   if (!card_dev || !expect || !q_dev || !out_dev) return QKV_ERR_NULL;
   const int rc = attend_workspace_floats(expect, q_heads, &floats);
   if (rc) return rc;
+  if (keys_per_channel) {                      // the shape rules of qkv_quantize_pack_kc
+    if (expect->group_size != 32) return QKV_ERR_GROUP;
+    if (expect->head_dim > 128 || expect->tokens % (expect->head_dim == 64 ? 64 : 32) != 0) return QKV_ERR_SHAPE;
+  }
   if (!std::isfinite(softmax_scale)) return QKV_ERR_SHAPE;
   if (card_bytes < QKV_CARD_HEADER_BYTES) return QKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(card_dev) % QKV_CARD_ALIGN != 0 || reinterpret_cast<uintptr_t>(q_dev) % 16 != 0 ||
@@ -532,7 +536,25 @@ int qkv_card_attend(const void* card_dev, uint64_t card_bytes, const qkv_desc_t*
   if (workspace_bytes < floats * sizeof(float)) return QKV_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(workspace_dev) % 16 != 0) return QKV_ERR_ALIGN;
   if (launch_attend(static_cast<const uint8_t*>(card_dev), card_bytes, g, q_dev, (uint32_t)q_heads, softmax_scale,
-                    out_dev, lse_dev, static_cast<float*>(workspace_dev), status_dev,
+                    out_dev, lse_dev, static_cast<float*>(workspace_dev), status_dev, false,
+                    static_cast<hipStream_t>(stream)) != hipSuccess)
+    return QKV_ERR_HIP;
+  return QKV_OK;
+}
+
+int qkv_card_attend_kc(const void* card_dev, uint64_t card_bytes, const qkv_desc_t* expect, const void* q_dev,
+                       int32_t q_heads, float softmax_scale, float* out_dev, float* lse_dev, void* workspace_dev,
+                       uint64_t workspace_bytes, uint32_t* status_dev, void* stream) {
+  if (!workspace_dev) return QKV_ERR_NULL;
+  CardGeom g;
+  uint64_t floats = 0;
+  const int rc = prepare_attend(card_dev, card_bytes, expect, q_dev, q_heads, softmax_scale, out_dev, lse_dev, status_dev, g, floats,
+                                true);
+  if (rc) return rc;
+  if (workspace_bytes < floats * sizeof(float)) return QKV_ERR_CAPACITY;
+  if (reinterpret_cast<uintptr_t>(workspace_dev) % 16 != 0) return QKV_ERR_ALIGN;
+  if (launch_attend(static_cast<const uint8_t*>(card_dev), card_bytes, g, q_dev, (uint32_t)q_heads, softmax_scale,
+                    out_dev, lse_dev, static_cast<float*>(workspace_dev), status_dev, true,
                     static_cast<hipStream_t>(stream)) != hipSuccess)
     return QKV_ERR_HIP;
   return QKV_OK;
@@ -549,7 +571,7 @@ int qkv_card_attend_static(const void* card_dev, uint64_t card_bytes, const qkv_
   float* scratch_at = nullptr;
   if (attend_static_scratch(&scratch_at) != hipSuccess) return QKV_ERR_HIP;
   if (launch_attend(static_cast<const uint8_t*>(card_dev), card_bytes, g, q_dev, (uint32_t)q_heads, softmax_scale,
-                    out_dev, lse_dev, scratch_at, status_dev, static_cast<hipStream_t>(stream)) != hipSuccess)
+                    out_dev, lse_dev, scratch_at, status_dev, false, static_cast<hipStream_t>(stream)) != hipSuccess)
     return QKV_ERR_HIP;
   return QKV_OK;
 }

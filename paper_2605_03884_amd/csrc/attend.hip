@@ -200,6 +200,110 @@ __device__ inline uint32_t decode_two_tokens(float c0, float s0, float z0, float
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
 }
 
+// ---- the LDS tile of a round: 16 packed rows, regrouped ------------------------------------------
+//
+// Used for the value rows of every card and for the key rows of cards grouped per channel.  In both
+// cases the MFMA contracts over the tile's rows, so a lane must hold four consecutive rows of one
+// column; the loader lane (n, kq) holds row n, columns 32 kq .. 32 kq + 31.
+
+// one row's pitch in the tile; rows of 32 / 64 bytes get a pitch of 40 / 80 so that the four rows a read
+// instruction touches (4 apart) fall on different banks.  Behind the rows, as [quarter][row]: the
+// 4 x 16 pairs (2-bit rows: 4 x 16 four-value tables), and at 2 bits the 2 KiB selector table.
+template <int W> struct TileGeo {
+  static constexpr uint32_t kRowBytes = (W == 2) ? 40u : (W == 4) ? 80u : 16u * W;
+  static constexpr uint32_t kPairsAt = (W == 16) ? 0u : 16u * kRowBytes;
+};
+
+// Loader side: lane (n, kq) drops its fetched span and the span's pair into the tile.
+template <int W, int G>
+__device__ inline void stage_span(const SpanData<W, G>& d, uint8_t* tile, uint32_t n, uint32_t kq) {
+  uint32_t* pairs_lds = reinterpret_cast<uint32_t*>(tile + TileGeo<W>::kPairsAt);
+  uint8_t* dst = tile + n * TileGeo<W>::kRowBytes + kq * (4u * W);
+  if constexpr (W == 2) {
+    *reinterpret_cast<u32x2*>(dst) = (u32x2){d.cw[0], d.cw[1]};
+  } else {
+#pragma unroll
+    for (int h = 0; h < (W == 16 ? 16 : W) / 4; ++h)
+      reinterpret_cast<u32x4*>(dst)[h] = (u32x4){d.cw[4 * h], d.cw[4 * h + 1], d.cw[4 * h + 2], d.cw[4 * h + 3]};
+  }
+  if constexpr (W == 2 && kSelectV) {
+    // the span's four decoded values instead of its (scale, zero): x_k = fp16(fma(k, scale, zero))
+    const float s = half_bits_to_float(d.pair & 0xFFFFu);
+    const float z = half_bits_to_float(d.pair >> 16);
+    reinterpret_cast<u32x2*>(pairs_lds)[kq * 16u + n] = (u32x2){decode_pair(0.0f, 1.0f, s, z), decode_pair(2.0f, 3.0f, s, z)};
+  } else if constexpr (W != 16) {
+    pairs_lds[kq * 16u + n] = d.pair;
+  }
+}
+
+// Reader side: lane (a, kt) picks up the pieces "rows 4 kt + i, columns 8 a .. 8 a + 7", i = 0 .. 3, and decodes
+// them into the eight operands b[e] = {X[4kt][8a+e], X[4kt+1][8a+e], X[4kt+2][8a+e], X[4kt+3][8a+e]}.
+template <int W>
+__device__ inline void operands_from_tile(const uint8_t* tile, const uint8_t* table, uint32_t a, uint32_t kt, u32x2 (&b)[8]) {
+  constexpr uint32_t kRowBytes = TileGeo<W>::kRowBytes;
+  const uint32_t* pairs_lds = reinterpret_cast<const uint32_t*>(tile + TileGeo<W>::kPairsAt);
+  if constexpr (W == 2 && kSelectV) {
+    // by selection: the piece's two code bytes index the selector table, the selectors pick the
+    // values out of the row's four; then pairs of columns are turned into pairs of rows
+    uint32_t tv[4][4];                     // row i, column pair m: {X[8a+2m], X[8a+2m+1]}
+    const u32x4* xs = reinterpret_cast<const u32x4*>(pairs_lds) + ((a >> 2) * 16u + 4u * kt) / 2u;
+    const u32x4 x01 = xs[0], x23 = xs[1];  // the four-value tables of rows 4 kt .. 4 kt + 3 for this lane's columns
+    const uint32_t xl[4] = {x01.x, x01.z, x23.x, x23.z}, xh[4] = {x01.y, x01.w, x23.y, x23.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t piece = *reinterpret_cast<const uint16_t*>(tile + (4u * kt + i) * kRowBytes + a * 2u);
+      const u32x2 s0 = *reinterpret_cast<const u32x2*>(table + byte_times8<0>(piece));
+      const u32x2 s1 = *reinterpret_cast<const u32x2*>(table + byte_times8<1>(piece));
+      tv[i][0] = __builtin_amdgcn_perm(xh[i], xl[i], s0.x);
+      tv[i][1] = __builtin_amdgcn_perm(xh[i], xl[i], s0.y);
+      tv[i][2] = __builtin_amdgcn_perm(xh[i], xl[i], s1.x);
+      tv[i][3] = __builtin_amdgcn_perm(xh[i], xl[i], s1.y);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;      // high or low halves of two words
+      b[e].x = __builtin_amdgcn_perm(tv[1][e >> 1], tv[0][e >> 1], sel);
+      b[e].y = __builtin_amdgcn_perm(tv[3][e >> 1], tv[2][e >> 1], sel);
+    }
+  } else {
+    Piece<W> pc[4];
+    uint32_t pr[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint8_t* src = tile + (4u * kt + i) * kRowBytes + a * W;
+      if constexpr (W == 2) pc[i].w[0] = *reinterpret_cast<const uint16_t*>(src);
+      else if constexpr (W == 4) pc[i].w[0] = *reinterpret_cast<const uint32_t*>(src);
+      else if constexpr (W == 8) { const u32x2 t = *reinterpret_cast<const u32x2*>(src); pc[i].w[0] = t.x; pc[i].w[1] = t.y; }
+      else { const u32x4 t = *reinterpret_cast<const u32x4*>(src); pc[i].w[0] = t.x; pc[i].w[1] = t.y; pc[i].w[2] = t.z; pc[i].w[3] = t.w; }
+    }
+    if constexpr (W != 16) {
+      const u32x4 t = *reinterpret_cast<const u32x4*>(pairs_lds + (a >> 2) * 16u + 4u * kt);
+      pr[0] = t.x; pr[1] = t.y; pr[2] = t.z; pr[3] = t.w;
+    }
+    if constexpr (W == 16) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;      // high or low halves of two words
+        b[e].x = __builtin_amdgcn_perm(pc[1].w[e >> 1], pc[0].w[e >> 1], sel);
+        b[e].y = __builtin_amdgcn_perm(pc[3].w[e >> 1], pc[2].w[e >> 1], sel);
+      }
+    } else {
+      float c0[8], c1[8], c2[8], c3[8];
+      piece_codes<W>(pc[0], pc[1], c0, c1);
+      piece_codes<W>(pc[2], pc[3], c2, c3);
+      const float s0 = half_bits_to_float(pr[0] & 0xFFFFu), z0 = half_bits_to_float(pr[0] >> 16);
+      const float s1 = half_bits_to_float(pr[1] & 0xFFFFu), z1 = half_bits_to_float(pr[1] >> 16);
+      const float s2 = half_bits_to_float(pr[2] & 0xFFFFu), z2 = half_bits_to_float(pr[2] >> 16);
+      const float s3 = half_bits_to_float(pr[3] & 0xFFFFu), z3 = half_bits_to_float(pr[3] >> 16);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        b[e].x = decode_two_tokens(c0[e], s0, z0, c1[e], s1, z1);
+        b[e].y = decode_two_tokens(c2[e], s2, z2, c3[e], s3, z3);
+      }
+    }
+  }
+}
+
 // ---- cross-lane helpers ------------------------------------------------------------------------
 
 template <int CTRL>
@@ -236,6 +340,117 @@ __device__ inline float sum_over_quarters(float a0, float a1, float a2, float a3
   return __builtin_bit_cast(float, srx) + __builtin_bit_cast(float, sry);
 }
 
+// ---- score pass over key planes grouped per channel ---------------------------------------------
+//
+// Uniform cards with group size 32 whose key spans hold the 32 tokens of one token block for ONE
+// channel (section layout [plane][token block][channel][32 codes]).  The contraction over the head
+// dimension then runs over the card's rows, exactly as the value pass contracts over tokens, and the
+// same tile does the regrouping: a round is 16 channels x 4 token blocks (a super-block of 128
+// tokens); loader lane (n, kq) fetches channel 16 r + n of token block kq, reader lane (a, kt) gets
+// "channels 16 r + 4 kt .. + 3, tokens 8 a .. 8 a + 7 of the super-block" as eight operands, and
+// the other MFMA operand is q[head][16 r + 4 kt .. + 3], exact in fp16 (one MFMA per operand).
+// After head_dim / 16 rounds the lane holds the scores of its eight tokens: summed over its own
+// channels only when NARROW (sum_over_quarters adds the four kt and leaves head kt), complete
+// otherwise (the 16 x 16 x 16 product adds the four kt itself; the lane holds heads 4 kt .. + 3).
+template <int W, bool NARROW, int DS>
+__device__ inline void score_pass_kc(const AttendArgs& a, const CardGeom& g, int c, uint32_t pair, uint32_t j0, uint32_t cnt,
+                                     uint32_t lane, float* lds, uint32_t pitch, uint32_t R4, uint8_t* tile,
+                                     const uint8_t* table) {
+  static_assert(W == 2 || W == 4 || W == 8, "per-channel key groups exist at 2, 4 and 8 bits");
+  constexpr uint32_t D = 32u * DS;
+  constexpr int kRounds = (int)D / 16;                      // rounds per super-block
+  constexpr int kAhead = (W == 2) ? 4 : 2;                  // rounds whose loads are in flight; divides kRounds
+  const uint32_t n = lane & 15u, kq = lane >> 4;
+  const uint32_t R = a.rep;
+  const uint32_t head = NARROW ? (n & 3u) : n;
+  f16x4 qa[kRounds];
+  {
+    const uint32_t l = pair / g.kv_heads, hh = pair - l * g.kv_heads;
+    const uint16_t* src = a.q + ((uint64_t)(l * a.q_heads + hh * R + (head < R ? head : 0u)) * D + 4u * kq);
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+      u32x2 raw = (u32x2)(0u);
+      if (head < R) raw = *reinterpret_cast<const u32x2*>(src + 16 * r);
+      qa[r] = __builtin_bit_cast(f16x4, raw);
+    }
+  }
+  // first group (token block, channel 0) of the task's key plane: blocks of 32 tokens, head_dim groups each
+  const uint64_t grp0 = ((uint64_t)pair * (g.tokens / 32u) + j0 / 32u) * D;
+  const uint8_t* codes0 = a.card + g.off_codes[c];
+  const uint8_t* pairs0 = a.card + g.off_meta[c];
+  const auto fetch = [&](uint32_t sb, uint32_t r) {
+    SpanData<W, 32> d;
+#pragma unroll
+    for (int i = 0; i < W; ++i) d.cw[i] = 0;
+    d.pair = 0;
+    const uint32_t tb = 4u * sb + kq;                        // token block inside the task
+    if (32u * tb < cnt) {
+      const uint64_t grp = grp0 + (uint64_t)tb * D + 16u * r + n;
+      const uint8_t* src = codes0 + grp * (4u * W);
+      if constexpr (W == 2) {
+        const u32x2 t = *reinterpret_cast<const u32x2*>(src);
+        d.cw[0] = t.x; d.cw[1] = t.y;
+      } else {
+#pragma unroll
+        for (int h = 0; h < W / 4; ++h) {
+          const u32x4 t = *reinterpret_cast<const u32x4*>(src + 16 * h);
+          d.cw[4 * h] = t.x; d.cw[4 * h + 1] = t.y; d.cw[4 * h + 2] = t.z; d.cw[4 * h + 3] = t.w;
+        }
+      }
+      d.pair = *reinterpret_cast<const uint32_t*>(pairs0 + grp * 4u);
+    }
+    return d;
+  };
+  SpanData<W, 32> buf[kAhead];
+#pragma unroll
+  for (int u = 0; u < kAhead; ++u) buf[u] = fetch(0u, (uint32_t)u);
+  const uint32_t superblocks = (cnt + 127u) / 128u;
+  for (uint32_t sb = 0; sb < superblocks; ++sb) {
+    f32x4 acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+      stage_span<W, 32>(buf[r % kAhead], tile, n, kq);
+      buf[r % kAhead] = (r + kAhead < kRounds) ? fetch(sb, (uint32_t)(r + kAhead)) : fetch(sb + 1u, (uint32_t)(r + kAhead - kRounds));
+      u32x2 b[8];
+      operands_from_tile<W>(tile, table, n, kq, b);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const f16x4 be = __builtin_bit_cast(f16x4, b[e]);
+        if constexpr (NARROW) acc[e] = __builtin_amdgcn_mfma_f32_4x4x4f16(qa[r], be, acc[e], 0, 0, 0);
+        else acc[e] = __builtin_amdgcn_mfma_f32_16x16x16f16(qa[r], be, acc[e], 0, 0, 0);
+      }
+    }
+    // tokens 128 sb + 8 a + e, e = 0 .. 7, of this lane
+    const uint32_t t0 = 128u * sb + 8u * n;
+    if constexpr (NARROW) {
+      float sc[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float v = sum_over_quarters(acc[e].x, acc[e].y, acc[e].z, acc[e].w);      // head kq
+        sc[e] = (t0 + e < cnt) ? v * a.scale_log2 : -INFINITY;
+      }
+      float* dst = lds + kq * pitch + t0;
+      if (t0 < pitch) *reinterpret_cast<f32x4*>(dst) = (f32x4){sc[0], sc[1], sc[2], sc[3]};
+      if (t0 + 4u < pitch) *reinterpret_cast<f32x4*>(dst + 4) = (f32x4){sc[4], sc[5], sc[6], sc[7]};
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t r = 4u * kq + i;                      // the lane holds heads 4 kq .. 4 kq + 3
+        if (r < R4) {
+          float sc[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) sc[e] = (t0 + e < cnt) ? acc[e][i] * a.scale_log2 : -INFINITY;
+          float* dst = lds + r * pitch + t0;
+          if (t0 < pitch) *reinterpret_cast<f32x4*>(dst) = (f32x4){sc[0], sc[1], sc[2], sc[3]};
+          if (t0 + 4u < pitch) *reinterpret_cast<f32x4*>(dst + 4) = (f32x4){sc[4], sc[5], sc[6], sc[7]};
+        }
+      }
+    }
+  }
+}
+
 // One task: rows [j0, j1) of class c for the pair (layer, kv head) = pair.
 // lds: scores / weights as [head][chunk] floats (R4 * chunk <= kLdsFloatsPerWave);
 // tile: the round's packed rows (16 tokens x up to 256 bytes) followed by the rows' pairs.
@@ -258,7 +473,7 @@ __device__ inline float sum_over_quarters(float a0, float a1, float a2, float a3
 // DS = head_dim / 32 spans per token.  The lane mapping covers a slab of 128 dimensions (4 spans);
 // head_dim 256 is two slabs (the score of a round adds both up before it is stored, the value
 // pass sweeps the task once per slab), head_dim 64 half a slab (quarters 2 and 3 see zeros).
-template <int W, int G, bool NARROW, int DS>
+template <int W, int G, bool NARROW, int DS, bool KC>
 __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c, uint32_t pair, uint32_t j0, uint32_t j1,
                                    uint32_t lane, float* lds, uint8_t* tile, const uint8_t* table, uint64_t part) {
   const uint32_t n = lane & 15u, kq = lane >> 4;          // also (a, kt) of the value pass
@@ -274,83 +489,88 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   constexpr int S = (DS + 3) / 4;                          // slabs of 128 dimensions
   constexpr uint32_t D = 32u * DS;
   const bool lane_has_span = DS >= 4 || kq < (uint32_t)DS; // head_dim 64: quarters 2 and 3 hold nothing
-  LanePtrs kp[S];
+  if constexpr (KC) {
+    if constexpr (W != 16 && G == 32 && DS <= 4) score_pass_kc<W, NARROW, DS>(a, g, c, pair, j0, cnt, lane, lds, chunk, R4, tile, table);
+  } else {
+    LanePtrs kp[S];
 #pragma unroll
-  for (int sl = 0; sl < S; ++sl) kp[sl] = lane_pointers<W, G, DS>(a.card, g, c, k_row0 + j0, n, lane_has_span ? 4u * sl + kq : 0u);
+    for (int sl = 0; sl < S; ++sl) kp[sl] = lane_pointers<W, G, DS>(a.card, g, c, k_row0 + j0, n, lane_has_span ? 4u * sl + kq : 0u);
 
-  // ---- q as MFMA operands: the lane holds q[head][128 sl + 32 kq .. + 31] of head n (head n % 4 when
-  // NARROW); operand j of slab sl is q[head][128 sl + 32 kq + 4 j .. + 3]
-  f16x4 qa[S][8];
+    // ---- q as MFMA operands: the lane holds q[head][128 sl + 32 kq .. + 31] of head n (head n % 4 when
+    // NARROW); operand j of slab sl is q[head][128 sl + 32 kq + 4 j .. + 3]
+    f16x4 qa[S][8];
 #pragma unroll
-  for (int sl = 0; sl < S; ++sl) {
-    u32x4 raw[4];
+    for (int sl = 0; sl < S; ++sl) {
+      u32x4 raw[4];
 #pragma unroll
-    for (int h = 0; h < 4; ++h) raw[h] = (u32x4)(0u);
-    const uint32_t head = NARROW ? (n & 3u) : n;
-    if (head < R && lane_has_span) {
-      const uint32_t l = pair / g.kv_heads, hh = pair - l * g.kv_heads;
-      const u32x4* src = reinterpret_cast<const u32x4*>(a.q + ((uint64_t)(l * a.q_heads + hh * R + head) * D + 128u * sl + 32u * kq));
+      for (int h = 0; h < 4; ++h) raw[h] = (u32x4)(0u);
+      const uint32_t head = NARROW ? (n & 3u) : n;
+      if (head < R && lane_has_span) {
+        const uint32_t l = pair / g.kv_heads, hh = pair - l * g.kv_heads;
+        const u32x4* src = reinterpret_cast<const u32x4*>(a.q + ((uint64_t)(l * a.q_heads + hh * R + head) * D + 128u * sl + 32u * kq));
 #pragma unroll
-      for (int h = 0; h < 4; ++h) raw[h] = src[h];
+        for (int h = 0; h < 4; ++h) raw[h] = src[h];
+      }
+#pragma unroll
+      for (int h = 0; h < 4; ++h) {
+        qa[sl][2 * h] = __builtin_bit_cast(f16x4, (u32x2){raw[h].x, raw[h].y});
+        qa[sl][2 * h + 1] = __builtin_bit_cast(f16x4, (u32x2){raw[h].z, raw[h].w});
+      }
     }
-#pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      qa[sl][2 * h] = __builtin_bit_cast(f16x4, (u32x2){raw[h].x, raw[h].y});
-      qa[sl][2 * h + 1] = __builtin_bit_cast(f16x4, (u32x2){raw[h].z, raw[h].w});
-    }
-  }
 
-  // ---- scores: lds[head * chunk + token] in log2 units, -inf for tokens past the task's end.
-  // The loads of the next kPrefetch rounds are always in flight.
-  {
-    SpanData<W, G> buf[kPrefetch][S];
-#pragma unroll
-    for (int u = 0; u < kPrefetch; ++u) {
-      const uint32_t t = u * kRoundTokens + n;
-#pragma unroll
-      for (int sl = 0; sl < S; ++sl) buf[u][sl] = fetch_span<W, G, DS>(kp[sl], u, t < cnt && lane_has_span);
-    }
-    for (uint32_t rd0 = 0; rd0 < rounds; rd0 += kPrefetch) {
+    // ---- scores: lds[head * chunk + token] in log2 units, -inf for tokens past the task's end.
+    // The loads of the next kPrefetch rounds are always in flight.
+    {
+      SpanData<W, G> buf[kPrefetch][S];
 #pragma unroll
       for (int u = 0; u < kPrefetch; ++u) {
-        const uint32_t rd = rd0 + u;
-        {                                          // rounds past the task's end see zeros and store -inf
-          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        const uint32_t t = u * kRoundTokens + n;
 #pragma unroll
-          for (int sl = 0; sl < S; ++sl) {
-            uint32_t kb[16];
-            if constexpr (W == 2) decode_fetched_select<G>(buf[u][sl], table, kb);
-            else decode_fetched<W, G>(buf[u][sl], kb);
-            const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
-            buf[u][sl] = fetch_span<W, G, DS>(kp[sl], rd + kPrefetch, tn < cnt && lane_has_span);
+        for (int sl = 0; sl < S; ++sl) buf[u][sl] = fetch_span<W, G, DS>(kp[sl], u, t < cnt && lane_has_span);
+      }
+      for (uint32_t rd0 = 0; rd0 < rounds; rd0 += kPrefetch) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-              const f16x4 kj = __builtin_bit_cast(f16x4, (u32x2){kb[2 * j], kb[2 * j + 1]});
-              if constexpr (NARROW) acc = __builtin_amdgcn_mfma_f32_4x4x4f16(qa[sl][j], kj, acc, 0, 0, 0);
-              else acc = __builtin_amdgcn_mfma_f32_16x16x16f16(kj, qa[sl][j], acc, 0, 0, 0);
+        for (int u = 0; u < kPrefetch; ++u) {
+          const uint32_t rd = rd0 + u;
+          {                                          // rounds past the task's end see zeros and store -inf
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int sl = 0; sl < S; ++sl) {
+              uint32_t kb[16];
+              if constexpr (W == 2) decode_fetched_select<G>(buf[u][sl], table, kb);
+              else decode_fetched<W, G>(buf[u][sl], kb);
+              const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
+              buf[u][sl] = fetch_span<W, G, DS>(kp[sl], rd + kPrefetch, tn < cnt && lane_has_span);
+#pragma unroll
+              for (int j = 0; j < 8; ++j) {
+                const f16x4 kj = __builtin_bit_cast(f16x4, (u32x2){kb[2 * j], kb[2 * j + 1]});
+                if constexpr (NARROW) acc = __builtin_amdgcn_mfma_f32_4x4x4f16(qa[sl][j], kj, acc, 0, 0, 0);
+                else acc = __builtin_amdgcn_mfma_f32_16x16x16f16(kj, qa[sl][j], acc, 0, 0, 0);
+              }
             }
-          }
-          if constexpr (NARROW) {
-            // head kq of token n
-            const float sc = sum_over_quarters(acc.x, acc.y, acc.z, acc.w);
-            const uint32_t t = rd * kRoundTokens + n;
-            lds[kq * chunk + t] = (t < cnt) ? sc * a.scale_log2 : -INFINITY;
-          } else {
-            // tokens 4 kq .. 4 kq + 3 of head n
-            const uint32_t t = rd * kRoundTokens + 4u * kq;
-            if (n < R4) {
-              f32x4 sc;
-              sc.x = (t < cnt) ? acc.x * a.scale_log2 : -INFINITY;
-              sc.y = (t + 1u < cnt) ? acc.y * a.scale_log2 : -INFINITY;
-              sc.z = (t + 2u < cnt) ? acc.z * a.scale_log2 : -INFINITY;
-              sc.w = (t + 3u < cnt) ? acc.w * a.scale_log2 : -INFINITY;
-              *reinterpret_cast<f32x4*>(lds + n * chunk + t) = sc;
+            if constexpr (NARROW) {
+              // head kq of token n
+              const float sc = sum_over_quarters(acc.x, acc.y, acc.z, acc.w);
+              const uint32_t t = rd * kRoundTokens + n;
+              lds[kq * chunk + t] = (t < cnt) ? sc * a.scale_log2 : -INFINITY;
+            } else {
+              // tokens 4 kq .. 4 kq + 3 of head n
+              const uint32_t t = rd * kRoundTokens + 4u * kq;
+              if (n < R4) {
+                f32x4 sc;
+                sc.x = (t < cnt) ? acc.x * a.scale_log2 : -INFINITY;
+                sc.y = (t + 1u < cnt) ? acc.y * a.scale_log2 : -INFINITY;
+                sc.z = (t + 2u < cnt) ? acc.z * a.scale_log2 : -INFINITY;
+                sc.w = (t + 3u < cnt) ? acc.w * a.scale_log2 : -INFINITY;
+                *reinterpret_cast<f32x4*>(lds + n * chunk + t) = sc;
+              }
             }
           }
         }
       }
     }
-  }
+
+  }   // per-token key groups
 
   // ---- softmax over the task's tokens, four heads at a time: row kq of the wave takes head
   // 4 hg + kq, its lane n the tokens 64 i + 4 n .. + 3 (the wave's own LDS accesses are in order).
@@ -400,11 +620,6 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   }
 
   // ---- values
-  // one token's packed row in the LDS tile; rows of 32 / 64 bytes get a pitch of 40 / 80 so that
-  // the four rows a read instruction touches (4 apart) fall on different banks
-  constexpr uint32_t kRowBytes = (W == 2) ? 40u : (W == 4) ? 80u : 16u * W;
-  // behind the rows, as [quarter of the head dimension][token]: the 4 x 16 pairs (2-bit rows: 4 x 16 four-value tables)
-  uint32_t* pairs_lds = reinterpret_cast<uint32_t*>(tile + ((W == 16) ? 0u : 16u * kRowBytes));
   const uint32_t w_head = NARROW ? (n & 3u) : n;            // the head whose weights this lane feeds the MFMA
   // one sweep over the task's rows per slab of 128 output dimensions (the weights stay in LDS)
 #pragma unroll 1
@@ -428,90 +643,13 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
           const uint32_t rd = rd0 + u;
           {                                          // rounds past the task's end add zero weights times zeros
             // rows into LDS as they were loaded: token n, quarter kq
-            {
-              uint8_t* dst = tile + n * kRowBytes + kq * (4u * W);
-              if constexpr (W == 2) {
-                *reinterpret_cast<u32x2*>(dst) = (u32x2){buf[u].cw[0], buf[u].cw[1]};
-              } else {
-#pragma unroll
-                for (int h = 0; h < (W == 16 ? 16 : W) / 4; ++h)
-                  reinterpret_cast<u32x4*>(dst)[h] = (u32x4){buf[u].cw[4 * h], buf[u].cw[4 * h + 1], buf[u].cw[4 * h + 2], buf[u].cw[4 * h + 3]};
-              }
-              if constexpr (W == 2 && kSelectV) {
-                // the span's four decoded values instead of its (scale, zero): x_k = fp16(fma(k, scale, zero))
-                const float s = half_bits_to_float(buf[u].pair & 0xFFFFu);
-                const float z = half_bits_to_float(buf[u].pair >> 16);
-                reinterpret_cast<u32x2*>(pairs_lds)[kq * 16u + n] = (u32x2){decode_pair(0.0f, 1.0f, s, z), decode_pair(2.0f, 3.0f, s, z)};
-              } else if constexpr (W != 16) {
-                pairs_lds[kq * 16u + n] = buf[u].pair;
-              }
-            }
+            stage_span<W, G>(buf[u], tile, n, kq);
             const uint32_t tn = (rd + kPrefetch) * kRoundTokens + n;
             buf[u] = fetch_span<W, G, DS>(vp, rd + kPrefetch, tn < cnt && lane_has_span);
 
-            // pieces of lane (a, kt) = (n, kq): tokens 4 kt + i, dimensions 8 a .. 8 a + 7
-            // B operands: b[e] = {V^[4kt][8a+e], V^[4kt+1][8a+e], V^[4kt+2][8a+e], V^[4kt+3][8a+e]}
+            // lane (a, kt) = (n, kq): b[e] = {V^[4kt][8a+e], V^[4kt+1][8a+e], V^[4kt+2][8a+e], V^[4kt+3][8a+e]}
             u32x2 b[8];
-            if constexpr (W == 2 && kSelectV) {
-              // by selection: the piece's two code bytes index the selector table, the selectors pick the
-              // values out of the token's four; then pairs of dimensions are turned into pairs of tokens
-              uint32_t tv[4][4];                     // token i, dimension pair m: {V^[8a+2m], V^[8a+2m+1]}
-              const u32x4* xs = reinterpret_cast<const u32x4*>(pairs_lds) + ((n >> 2) * 16u + 4u * kq) / 2u;
-              const u32x4 x01 = xs[0], x23 = xs[1];  // the four-value tables of tokens 4 kt .. 4 kt + 3 for this lane's dimensions
-              const uint32_t xl[4] = {x01.x, x01.z, x23.x, x23.z}, xh[4] = {x01.y, x01.w, x23.y, x23.w};
-#pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                const uint32_t piece = *reinterpret_cast<const uint16_t*>(tile + (4u * kq + i) * kRowBytes + n * 2u);
-                const u32x2 s0 = *reinterpret_cast<const u32x2*>(table + byte_times8<0>(piece));
-                const u32x2 s1 = *reinterpret_cast<const u32x2*>(table + byte_times8<1>(piece));
-                tv[i][0] = __builtin_amdgcn_perm(xh[i], xl[i], s0.x);
-                tv[i][1] = __builtin_amdgcn_perm(xh[i], xl[i], s0.y);
-                tv[i][2] = __builtin_amdgcn_perm(xh[i], xl[i], s1.x);
-                tv[i][3] = __builtin_amdgcn_perm(xh[i], xl[i], s1.y);
-              }
-#pragma unroll
-              for (int e = 0; e < 8; ++e) {
-                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;      // high or low halves of two words
-                b[e].x = __builtin_amdgcn_perm(tv[1][e >> 1], tv[0][e >> 1], sel);
-                b[e].y = __builtin_amdgcn_perm(tv[3][e >> 1], tv[2][e >> 1], sel);
-              }
-            } else {
-            Piece<W> pc[4];
-            uint32_t pr[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const uint8_t* src = tile + (4u * kq + i) * kRowBytes + n * W;
-              if constexpr (W == 2) pc[i].w[0] = *reinterpret_cast<const uint16_t*>(src);
-              else if constexpr (W == 4) pc[i].w[0] = *reinterpret_cast<const uint32_t*>(src);
-              else if constexpr (W == 8) { const u32x2 t = *reinterpret_cast<const u32x2*>(src); pc[i].w[0] = t.x; pc[i].w[1] = t.y; }
-              else { const u32x4 t = *reinterpret_cast<const u32x4*>(src); pc[i].w[0] = t.x; pc[i].w[1] = t.y; pc[i].w[2] = t.z; pc[i].w[3] = t.w; }
-            }
-            if constexpr (W != 16) {
-              const u32x4 t = *reinterpret_cast<const u32x4*>(pairs_lds + (n >> 2) * 16u + 4u * kq);
-              pr[0] = t.x; pr[1] = t.y; pr[2] = t.z; pr[3] = t.w;
-            }
-            if constexpr (W == 16) {
-#pragma unroll
-              for (int e = 0; e < 8; ++e) {
-                const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;      // high or low halves of two words
-                b[e].x = __builtin_amdgcn_perm(pc[1].w[e >> 1], pc[0].w[e >> 1], sel);
-                b[e].y = __builtin_amdgcn_perm(pc[3].w[e >> 1], pc[2].w[e >> 1], sel);
-              }
-            } else {
-              float c0[8], c1[8], c2[8], c3[8];
-              piece_codes<W>(pc[0], pc[1], c0, c1);
-              piece_codes<W>(pc[2], pc[3], c2, c3);
-              const float s0 = half_bits_to_float(pr[0] & 0xFFFFu), z0 = half_bits_to_float(pr[0] >> 16);
-              const float s1 = half_bits_to_float(pr[1] & 0xFFFFu), z1 = half_bits_to_float(pr[1] >> 16);
-              const float s2 = half_bits_to_float(pr[2] & 0xFFFFu), z2 = half_bits_to_float(pr[2] >> 16);
-              const float s3 = half_bits_to_float(pr[3] & 0xFFFFu), z3 = half_bits_to_float(pr[3] >> 16);
-#pragma unroll
-              for (int e = 0; e < 8; ++e) {
-                b[e].x = decode_two_tokens(c0[e], s0, z0, c1[e], s1, z1);
-                b[e].y = decode_two_tokens(c2[e], s2, z2, c3[e], s3, z3);
-              }
-            }
-            }
+            operands_from_tile<W>(tile, table, n, kq, b);
             // A operands: the weights of head w_head for tokens 4 kt .. 4 kt + 3, high parts and low parts
             u32x4 pw = (u32x4)(0u);
             if (w_head < R4) pw = *reinterpret_cast<const u32x4*>(lds + w_head * chunk + rd * kRoundTokens + 4u * kq);
@@ -564,7 +702,8 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   }
 }
 
-template <int G, bool NARROW, int DS>
+// KC: the card's key planes are grouped per channel (a uniform card at 2, 4 or 8 bits, group size 32).
+template <int G, bool NARROW, int DS, bool KC>
 __global__ __launch_bounds__(kAttendWaves * kWaveSize) __attribute__((amdgpu_waves_per_eu(2)))
 void attend_kernel(AttendArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[kAttendWaves][kLdsFloatsPerWave];
@@ -572,8 +711,12 @@ void attend_kernel(AttendArgs a) {
   // rows' pairs (256 bytes; 512 bytes of four-value tables at 2 bits), then at 2 bits the 2 KiB selector table
   __shared__ __attribute__((aligned(16))) uint8_t tiles[kAttendWaves][16 * 256];
   CardGeom g;
-  const bool ok = card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size,
-                                            a.tokens, g);
+  bool ok = card_geometry_from_header(a.card, a.card_bytes, a.layers, a.kv_heads, a.head_dim, a.group_size,
+                                      a.tokens, g, KC ? QKV_FLAG_KEYS_PER_CHANNEL : 0u);
+  if (KC && ok) {                              // the shapes the per-channel score pass is written for
+    const bool uniform = g.n[0] == g.tokens || g.n[1] == g.tokens || g.n[2] == g.tokens;
+    ok = uniform && g.group_size == 32u && g.head_dim <= 128u && g.tokens % (g.head_dim == 64u ? 64u : 32u) == 0u;
+  }
   // the header's verdict, for the merging kernel that follows on the stream and for the caller
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     *a.valid = ok ? 1u : 0u;
@@ -617,11 +760,13 @@ void attend_kernel(AttendArgs a) {
   uint8_t* my_table = my_tile + 16 * 40 + 512;
   if (cls == 0) {
     build_select_table(reinterpret_cast<u32x2*>(my_table), lane);
-    attend_task<2, G, NARROW, DS>(a, g, 0, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+    attend_task<2, G, NARROW, DS, KC>(a, g, 0, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
   }
-  if (cls == 1) attend_task<4, G, NARROW, DS>(a, g, 1, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
-  if (cls == 2) attend_task<8, G, NARROW, DS>(a, g, 2, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
-  if (cls == 3) attend_task<16, G, NARROW, DS>(a, g, 3, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+  if (cls == 1) attend_task<4, G, NARROW, DS, KC>(a, g, 1, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+  if (cls == 2) attend_task<8, G, NARROW, DS, KC>(a, g, 2, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+  if constexpr (!KC) {                         // a card grouped per channel has no raw rows
+    if (cls == 3) attend_task<16, G, NARROW, DS, false>(a, g, 3, pair, j0, j1, lane, my_lds, my_tile, my_table, part);
+  }
 }
 
 // Merges the partials of one (layer, query head): thread d owns output dimension d.  The
@@ -721,7 +866,7 @@ hipError_t attend_static_scratch(float** ptr) {
 
 hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeom& expect, const void* q,
                          uint32_t q_heads, float softmax_scale, float* out, float* lse, float* workspace,
-                         uint32_t* status, hipStream_t stream) {
+                         uint32_t* status, bool keys_per_channel, hipStream_t stream) {
   AttendArgs a;
   a.card = card;
   a.card_bytes = card_bytes;
@@ -746,10 +891,18 @@ hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeo
   const uint32_t G = expect.group_size;
 #define QKV_LAUNCH_ATTEND(GG, DSS)                                                                     \
   do {                                                                                                 \
-    if (narrow) hipLaunchKernelGGL((attend_kernel<GG, true, DSS>), grid, block, 0, stream, a);         \
-    else hipLaunchKernelGGL((attend_kernel<GG, false, DSS>), grid, block, 0, stream, a);               \
+    if (narrow) hipLaunchKernelGGL((attend_kernel<GG, true, DSS, false>), grid, block, 0, stream, a);  \
+    else hipLaunchKernelGGL((attend_kernel<GG, false, DSS, false>), grid, block, 0, stream, a);        \
   } while (0)
-  if (D == 64u) {
+  if (keys_per_channel) {                      // the host has checked: group size 32, head_dim 64 or 128
+    if (D == 64u) {
+      if (narrow) hipLaunchKernelGGL((attend_kernel<32, true, 2, true>), grid, block, 0, stream, a);
+      else hipLaunchKernelGGL((attend_kernel<32, false, 2, true>), grid, block, 0, stream, a);
+    } else {
+      if (narrow) hipLaunchKernelGGL((attend_kernel<32, true, 4, true>), grid, block, 0, stream, a);
+      else hipLaunchKernelGGL((attend_kernel<32, false, 4, true>), grid, block, 0, stream, a);
+    }
+  } else if (D == 64u) {
     if (G == 32u) QKV_LAUNCH_ATTEND(32, 2); else QKV_LAUNCH_ATTEND(64, 2);
   } else if (D == 128u) {
     if (G == 32u) QKV_LAUNCH_ATTEND(32, 4); else if (G == 64u) QKV_LAUNCH_ATTEND(64, 4); else QKV_LAUNCH_ATTEND(128, 4);

@@ -162,7 +162,7 @@ hipError_t launch_assign_plan(const float* scores, const uint32_t cuts[3], uint8
 void attend_plan(uint64_t tokens, uint32_t rep, uint64_t pairs, uint32_t* chunk, uint32_t* max_tasks);
 hipError_t launch_attend(const uint8_t* card, uint64_t card_bytes, const CardGeom& expect, const void* q,
                          uint32_t q_heads, float softmax_scale, float* out, float* lse, float* workspace,
-                         uint32_t* status, hipStream_t stream);
+                         uint32_t* status, bool keys_per_channel, hipStream_t stream);
 hipError_t attend_static_scratch(float** ptr);     // the current device's copy of the static scratch array
 hipError_t launch_count(const uint8_t* bits, uint64_t tokens, unsigned long long* counts4, hipStream_t stream);
 hipError_t launch_controller(const float* features, uint32_t tokens, const qkv_controller_t& params, float* scores,

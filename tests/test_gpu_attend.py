@@ -118,6 +118,71 @@ def test_other_head_dims_uniform_widths_and_ragged_tasks(D, width):
               "attend head_dim=%d uniform %d-bit T=%d" % (D, width, T), D=D)
 
 
+def check_kc(L, H, rep, T, D, width, seed, label, kind="llama"):
+    """Attention over a uniform card whose keys are grouped per channel, against the same float64 definition."""
+    say(label)
+    G, scale = 32, D ** -0.5
+    K, V = qkv_synth.make_kv(L, H, T, D, seed, kind)
+    bits = np.full(T, width, dtype=np.uint8)
+    counts = [T if width == w else 0 for w in (2, 4, 8, 16)]
+    rd = ref.make_desc(L, H, T, D, G)
+    card = ref.quantize_pack_kc(rd, K.numpy(), V.numpy(), bits, counts)
+    q = np.random.default_rng(seed + 1).standard_normal((L, H * rep, D)).astype(np.float16)
+    desc = qkv.Desc.make(L, H, T, D, G)
+    card_dev = torch.from_numpy(card).to(DEV)
+    out = torch.full((L, H * rep, D), float("nan"), dtype=torch.float32, device=DEV)
+    lse = torch.full((L, H * rep), float("nan"), dtype=torch.float32, device=DEV)
+    status = torch.full((1,), 0x7777, dtype=torch.int32, device=DEV)
+    qkv.card_attend_kc(card_dev, desc, torch.from_numpy(q).to(DEV), scale, out, lse=lse, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    want_o, want_lse = attend_ref.card_attend(card, rd, q, scale, keys_per_channel=True)
+    kq, vq = ref.unpack_dequant_kc(card, rd)
+    Kf = np.abs(kq.view(np.float16).astype(np.float64))
+    ds = max(float((Kf[l, hq // rep] @ np.abs(q[l, hq].astype(np.float64))).max()) for l in range(L) for hq in range(H * rep))
+    ds *= D * 2.0 ** -24 * scale
+    vmax = float(np.abs(vq.view(np.float16).astype(np.float64)).max())
+    base = (T + 8) * 2.0 ** -24 + 2.0 ** -21
+    tol_o, tol_lse = min((2 * ds + base) * vmax, 1e-5 * max(1.0, vmax)), min(ds + base, 1e-4)
+    err_o, err_l = float(np.abs(out.cpu().numpy() - want_o).max()), float(np.abs(lse.cpu().numpy() - want_lse).max())
+    print("        max |do| %.3g (bound %.3g)   max |dlse| %.3g (bound %.3g)" % (err_o, tol_o, err_l, tol_lse), flush=True)
+    assert err_o <= tol_o and err_l <= tol_lse
+    return card_dev, desc, q
+
+
+@pytest.mark.parametrize("width", [2, 4, 8])
+@pytest.mark.parametrize("D,T", [(128, 32), (128, 96), (128, 416), (128, 1024), (64, 64), (64, 448), (64, 1024)])
+def test_cards_grouped_per_channel(width, D, T):
+    """Token counts below, at and across the 128-token super-blocks and the 384-token tasks."""
+    check_kc(2, 2, 4, T, D, width, 1100 + width + D + T, "attend per-channel keys head_dim=%d %d-bit T=%d" % (D, width, T))
+
+
+@pytest.mark.parametrize("rep", [1, 3, 8, 16])
+def test_cards_grouped_per_channel_query_head_counts(rep):
+    check_kc(1, 2, rep, 800, 128, 4, 1200 + rep, "attend per-channel keys rep=%d" % rep)
+    check_kc(1, 2, rep, 768, 64, 2, 1300 + rep, "attend per-channel keys head_dim=64 rep=%d" % rep)
+
+
+def test_cards_grouped_per_channel_are_told_apart():
+    """Each of the two calls refuses a card of the other grouping on the device and leaves the outputs alone."""
+    card_dev, desc, q = check_kc(1, 2, 4, 256, 128, 4, 1400, "attend per-channel keys, then the wrong call")
+    out = torch.full((1, 8, 128), float("nan"), dtype=torch.float32, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    qkv.card_attend(card_dev, desc, torch.from_numpy(q).to(DEV), 1.0, out, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == qkv.STATUS_BAD_HEADER and bool(torch.isnan(out).all())
+    rd, card = build_card(1, 2, 256, 128, 32, np.full(256, 4, dtype=np.uint8), 1401)
+    qkv.card_attend_kc(torch.from_numpy(card).to(DEV), desc, torch.from_numpy(q).to(DEV), 1.0, out, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == qkv.STATUS_BAD_HEADER and bool(torch.isnan(out).all())
+    with pytest.raises(qkv.QkvError) as e:       # group size 64 has no per-channel form
+        qkv.card_attend_kc(card_dev, qkv.Desc.make(1, 2, 256, 128, 64), torch.from_numpy(q).to(DEV), 1.0, out)
+    assert e.value.code == -3
+    with pytest.raises(qkv.QkvError) as e:       # tokens not a multiple of 32
+        qkv.card_attend_kc(card_dev, qkv.Desc.make(1, 2, 250, 128, 32), torch.from_numpy(q).to(DEV), 1.0, out)
+    assert e.value.code == -2
+
+
 def test_skewed_mixes_empty_classes_and_scales():
     T = 1100
     rng = np.random.default_rng(8)

@@ -120,3 +120,36 @@ def test_card_attend_uses_the_dequantized_cache():
     o16, _ = attend_ref.card_attend(card16, d, q, D ** -0.5)
     od, _ = attend_ref.attend_dense(q, K.numpy(), V.numpy(), D ** -0.5)
     assert np.array_equal(o16, od)
+
+
+def test_card_attend_over_per_channel_key_groups():
+    # the grouping of the keys is part of what the card means: the same definition over the cache that a per-channel
+    # card dequantizes to; a zero query makes the keys irrelevant (o = mean of the values, which both groupings
+    # quantize alike); keys constant along the tokens of a block are exact under per-channel groups, so there the
+    # result equals attention over the keys themselves
+    L, H, T, D, G = 1, 2, 64, 64, 32
+    K, V = qkv_synth.make_kv(L, H, T, D, 79, "llama")
+    bits = np.full(T, 4, dtype=np.uint8)
+    counts = ref.count_bits(bits)
+    d = ref.make_desc(L, H, T, D, G)
+    card_kc = ref.quantize_pack_kc(d, K.numpy(), V.numpy(), bits, counts)
+    card_pt = ref.quantize_pack(d, K.numpy(), V.numpy(), bits, counts)
+    q = np.random.default_rng(2).standard_normal((L, 4, D)).astype(np.float16)
+    o, lse = attend_ref.card_attend(card_kc, d, q, D ** -0.5, keys_per_channel=True)
+    kq, vq = ref.unpack_dequant_kc(card_kc, d)
+    o2, lse2 = attend_ref.attend_dense(q, kq.view(np.float16), vq.view(np.float16), D ** -0.5)
+    assert np.array_equal(o, o2) and np.array_equal(lse, lse2)
+    o_pt, _ = attend_ref.card_attend(card_pt, d, q, D ** -0.5)
+    assert not np.array_equal(o, o_pt)                       # the two groupings round the keys differently
+    zero = np.zeros_like(q)
+    oz, lz = attend_ref.card_attend(card_kc, d, zero, 1.0, keys_per_channel=True)
+    ozp, _ = attend_ref.card_attend(card_pt, d, zero, 1.0)
+    assert np.array_equal(oz, ozp) and np.allclose(lz, math.log(T), atol=1e-14)
+    Kc = K.numpy().copy()
+    Kc[:, :, :32, :] = Kc[:, :, :1, :]                      # every channel constant over each block of 32 tokens
+    Kc[:, :, 32:, :] = Kc[:, :, 32:33, :]
+    card_c = ref.quantize_pack_kc(d, Kc, V.numpy(), bits, counts)
+    oc, lc = attend_ref.card_attend(card_c, d, q, D ** -0.5, keys_per_channel=True)
+    _, vqc = ref.unpack_dequant_kc(card_c, d)
+    od, ld = attend_ref.attend_dense(q, Kc, vqc.view(np.float16), D ** -0.5)
+    assert np.array_equal(oc, od) and np.array_equal(lc, ld)
