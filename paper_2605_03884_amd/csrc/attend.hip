@@ -354,7 +354,7 @@ __device__ inline float sum_over_quarters(float a0, float a1, float a2, float a3
 // otherwise (the 16 x 16 x 16 product adds the four kt itself; the lane holds heads 4 kt .. + 3).
 template <int W, bool NARROW, int DS>
 __device__ inline void score_pass_kc(const AttendArgs& a, const CardGeom& g, int c, uint32_t pair, uint32_t j0, uint32_t cnt,
-                                     uint32_t lane, float* lds, uint32_t pitch, uint32_t R4, uint8_t* tile,
+                                     uint32_t slots, uint32_t lane, float* lds, uint32_t pitch, uint32_t R4, uint8_t* tile,
                                      const uint8_t* table) {
   static_assert(W == 2 || W == 4 || W == 8, "per-channel key groups exist at 2, 4 and 8 bits");
   constexpr uint32_t D = 32u * DS;
@@ -404,7 +404,9 @@ __device__ inline void score_pass_kc(const AttendArgs& a, const CardGeom& g, int
   SpanData<W, 32> buf[kAhead];
 #pragma unroll
   for (int u = 0; u < kAhead; ++u) buf[u] = fetch(0u, (uint32_t)u);
-  const uint32_t superblocks = (cnt + 127u) / 128u;
+  // every slot the softmax will read gets a value: `slots` is the task's token count rounded up to the softmax's
+  // own granularity (at most the pitch), which can reach into a super-block that holds no token
+  const uint32_t superblocks = (slots + 127u) / 128u;
   for (uint32_t sb = 0; sb < superblocks; ++sb) {
     f32x4 acc[8];
 #pragma unroll
@@ -489,8 +491,12 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
   constexpr int S = (DS + 3) / 4;                          // slabs of 128 dimensions
   constexpr uint32_t D = 32u * DS;
   const bool lane_has_span = DS >= 4 || kq < (uint32_t)DS; // head_dim 64: quarters 2 and 3 hold nothing
+  // Rounds are processed in whole groups of kPrefetch; the task size is a multiple of such a group, so the padded
+  // rounds stay inside the task's share of LDS.  The softmax covers `slots` tokens, those past the task's end at -inf.
+  const uint32_t slots = (rounds + kPrefetch - 1) / kPrefetch * kPrefetch * kRoundTokens;
   if constexpr (KC) {
-    if constexpr (W != 16 && G == 32 && DS <= 4) score_pass_kc<W, NARROW, DS>(a, g, c, pair, j0, cnt, lane, lds, chunk, R4, tile, table);
+    if constexpr (W != 16 && G == 32 && DS <= 4)
+      score_pass_kc<W, NARROW, DS>(a, g, c, pair, j0, cnt, slots, lane, lds, chunk, R4, tile, table);
   } else {
     LanePtrs kp[S];
 #pragma unroll
@@ -574,9 +580,6 @@ __device__ inline void attend_task(const AttendArgs& a, const CardGeom& g, int c
 
   // ---- softmax over the task's tokens, four heads at a time: row kq of the wave takes head
   // 4 hg + kq, its lane n the tokens 64 i + 4 n .. + 3 (the wave's own LDS accesses are in order).
-  // Whole groups of kPrefetch rounds are processed; the task size is a multiple of such a group,
-  // so the padded rounds stay inside the task's share of LDS.
-  const uint32_t slots = (rounds + kPrefetch - 1) / kPrefetch * kPrefetch * kRoundTokens;
   // the first value rows are requested now, so that they arrive while the softmax runs
   LanePtrs vp = lane_pointers<W, G, DS>(a.card, g, c, v_row0 + j0, n, lane_has_span ? kq : 0u);
   SpanData<W, G> vbuf[kPrefetch];

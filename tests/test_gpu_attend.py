@@ -151,9 +151,11 @@ def check_kc(L, H, rep, T, D, width, seed, label, kind="llama"):
 
 
 @pytest.mark.parametrize("width", [2, 4, 8])
-@pytest.mark.parametrize("D,T", [(128, 32), (128, 96), (128, 416), (128, 1024), (64, 64), (64, 448), (64, 1024)])
+@pytest.mark.parametrize("D,T", [(128, 32), (128, 96), (128, 128), (128, 320), (128, 416), (128, 1024), (64, 64), (64, 320), (64, 448),
+                                 (64, 1024)])
 def test_cards_grouped_per_channel(width, D, T):
-    """Token counts below, at and across the 128-token super-blocks and the 384-token tasks."""
+    """Token counts below, at and across the 128-token super-blocks and the 384-token tasks; tasks of exactly 128 tokens,
+    where the softmax's granularity at 4 bits (48 tokens) reaches past the last super-block that holds a token."""
     check_kc(2, 2, 4, T, D, width, 1100 + width + D + T, "attend per-channel keys head_dim=%d %d-bit T=%d" % (D, width, T))
 
 
@@ -161,6 +163,7 @@ def test_cards_grouped_per_channel(width, D, T):
 def test_cards_grouped_per_channel_query_head_counts(rep):
     check_kc(1, 2, rep, 800, 128, 4, 1200 + rep, "attend per-channel keys rep=%d" % rep)
     check_kc(1, 2, rep, 768, 64, 2, 1300 + rep, "attend per-channel keys head_dim=64 rep=%d" % rep)
+    check_kc(3, 4, rep, 320, 64, 4, 1350 + rep, "attend per-channel keys head_dim=64 4-bit T=320 rep=%d" % rep)
 
 
 def test_cards_grouped_per_channel_are_told_apart():
