@@ -47,7 +47,7 @@ KERNEL_SOURCES = ["pack.hip", "unpack.hip", "qkv_encode.h", "qkv_decode.h", "qkv
 VECTOR_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 MEASURED_ATTEND = {
     "llama8b_8k_b3": {"valu_instructions": 24405761, "mfma_instructions": 3182592, "lds_instructions": 2981888,
-                      "lds_active_cycles": 18725549, "lds_bank_conflict_cycles": 10719405, "sources": "8f14bdad7072ecc5",
+                      "lds_active_cycles": 18725549, "lds_bank_conflict_cycles": 10719405, "sources": "884543a9d0931eac",
                       "profile": "profiles/card_attend_llama8b_8k_b3.txt"},
 }
 ATTEND_SOURCES = ["attend.hip", "qkv_decode.h", "qkv_common.h"]

@@ -43,21 +43,11 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRoundTokens = 16;
-#ifndef QKV_ATTEND_V_SELECT
-#define QKV_ATTEND_V_SELECT 1
-#endif
-constexpr bool kSelectV = QKV_ATTEND_V_SELECT != 0;        // 2-bit value rows decoded by selection
-#ifndef QKV_ATTEND_WAVES_PER_BLOCK
-#define QKV_ATTEND_WAVES_PER_BLOCK 1
-#endif
-constexpr int kAttendWaves = QKV_ATTEND_WAVES_PER_BLOCK;   // waves per workgroup; they do not interact
+constexpr int kAttendWaves = 1;              // waves per workgroup (they would not interact): one keeps every LDS address an immediate
 // Rounds whose loads are in flight ahead of the arithmetic: as many as the registers allow
 // (a fetched span is 3 / 5 / 9 / 16 registers at 2 / 4 / 8 / 16 bits).
 template <int W> struct Prefetch { static constexpr int kRounds = (W == 2) ? 4 : (W == 4) ? 3 : (W == 8) ? 2 : 1; };
-#ifndef QKV_ATTEND_LDS_FLOATS
-#define QKV_ATTEND_LDS_FLOATS 1536
-#endif
-constexpr int kLdsFloatsPerWave = QKV_ATTEND_LDS_FLOATS;   // scores of one task: chunk tokens x padded query heads
+constexpr int kLdsFloatsPerWave = 1536;      // scores of one task: chunk tokens x padded query heads (6 KiB)
 
 struct AttendArgs {
   const uint8_t* card;
@@ -226,7 +216,7 @@ __device__ inline void stage_span(const SpanData<W, G>& d, uint8_t* tile, uint32
     for (int h = 0; h < (W == 16 ? 16 : W) / 4; ++h)
       reinterpret_cast<u32x4*>(dst)[h] = (u32x4){d.cw[4 * h], d.cw[4 * h + 1], d.cw[4 * h + 2], d.cw[4 * h + 3]};
   }
-  if constexpr (W == 2 && kSelectV) {
+  if constexpr (W == 2) {
     // the span's four decoded values instead of its (scale, zero): x_k = fp16(fma(k, scale, zero))
     const float s = half_bits_to_float(d.pair & 0xFFFFu);
     const float z = half_bits_to_float(d.pair >> 16);
@@ -242,7 +232,7 @@ template <int W>
 __device__ inline void operands_from_tile(const uint8_t* tile, const uint8_t* table, uint32_t a, uint32_t kt, u32x2 (&b)[8]) {
   constexpr uint32_t kRowBytes = TileGeo<W>::kRowBytes;
   const uint32_t* pairs_lds = reinterpret_cast<const uint32_t*>(tile + TileGeo<W>::kPairsAt);
-  if constexpr (W == 2 && kSelectV) {
+  if constexpr (W == 2) {
     // by selection: the piece's two code bytes index the selector table, the selectors pick the
     // values out of the row's four; then pairs of columns are turned into pairs of rows
     uint32_t tv[4][4];                     // row i, column pair m: {X[8a+2m], X[8a+2m+1]}
